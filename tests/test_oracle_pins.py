@@ -1,0 +1,326 @@
+"""Pins for the fp64 CPU oracle: what the paper and the mathematics fix.
+
+None of these tests re-types the oracle's own formula as the expected value:
+they use library routines on special cases, closed forms, hand-computed
+examples (numbers worked out on paper and written here as literals),
+brute-force enumeration and the invariants the paper states.
+"""
+
+import math
+
+import numpy as np
+import pytest
+from scipy.special import softmax as sp_softmax
+
+import brute_force as bf
+
+RNG = np.random.default_rng(20251022)
+
+
+# ------------------------------------------------------------------ score
+def test_score_single_row_is_library_softmax(oracle):
+    # G = 1, W = 1: the one window query sees every key, so s is one softmax row of K q / sqrt(D) (Eq. 1)
+    D, L = 24, 57
+    q = RNG.normal(size=(1, 1, D))
+    k = RNG.normal(size=(L, D))
+    s, e = oracle.score(q, k, eps=1e-6)
+    np.testing.assert_allclose(s, sp_softmax(k @ q[0, 0] / math.sqrt(D)), rtol=1e-12, atol=1e-15)
+    # one query => Ahat == 1 for every key => e_t = -ln(1 + eps)
+    np.testing.assert_allclose(e, -math.log1p(1e-6), rtol=1e-9)
+
+
+def test_score_matches_library_matmul_softmax_mean(oracle):
+    # general case through library routines: matmul, masked softmax, mean over heads, sum over queries
+    G, W, D, L = 3, 5, 16, 41
+    T = L - W
+    q = RNG.normal(size=(G, W, D))
+    k = RNG.normal(size=(L, D))
+    logits = np.einsum("gwd,ld->gwl", q, k) / math.sqrt(D)
+    for i in range(W):
+        logits[:, i, T + i + 1:] = -np.inf
+    abar = sp_softmax(logits, axis=-1).mean(axis=0)
+    s, e = oracle.score(q, k, eps=1e-6)
+    np.testing.assert_allclose(s, abar.sum(axis=0), rtol=1e-12)
+    ahat = abar / abar.sum(axis=0, keepdims=True)
+    from scipy.special import xlogy
+    # -sum a*ln(a+eps) written with xlogy(a, a+eps) (0 where a == 0)
+    np.testing.assert_allclose(e, -xlogy(ahat, ahat + 1e-6).sum(axis=0), rtol=1e-10, atol=1e-14)
+
+
+def test_score_zero_queries_closed_form(oracle):
+    # Q == 0 => every visible key gets 1/(T+i+1) from query i
+    G, W, D, L = 2, 4, 8, 30
+    T = L - W
+    eps = 1e-6
+    s, e = oracle.score(np.zeros((G, W, D)), RNG.normal(size=(L, D)), eps=eps)
+    w = np.array([1.0 / (T + i + 1) for i in range(W)])
+    for t in range(L):
+        first = max(0, t - T)            # queries first..W-1 see key t
+        st = w[first:].sum()
+        assert s[t] == pytest.approx(st, rel=1e-13)
+        ah = w[first:] / st
+        assert e[t] == pytest.approx(-(ah * np.log(ah + eps)).sum(), rel=1e-12)
+    # compressible keys: identical score, entropy just under ln W
+    assert np.ptp(s[:T]) < 1e-15
+    assert math.log(W) - 1e-2 < e[0] <= math.log(W) + 1e-9
+
+
+def test_score_columns_sum_to_window(oracle):
+    G, W, D, L = 2, 6, 16, 100
+    s, e = oracle.score(RNG.normal(size=(G, W, D)) * 2, RNG.normal(size=(L, D)), eps=1e-6)
+    assert s.sum() == pytest.approx(W, rel=1e-12)           # every softmax row sums to one
+    assert (s >= 0).all()
+    assert (e >= -W * 1e-6 - 1e-12).all() and (e <= math.log(W) + 1e-9).all()
+
+
+def test_score_one_hot_limit(oracle):
+    # orthogonal keys c*I and queries aligned with key t0: all mass on t0 as c grows
+    D = L = 16
+    W, t0, c = 3, 5, 12.0
+    k = c * np.eye(L, D)
+    q = np.zeros((1, W, D))
+    q[0, :, t0] = c
+    s, e = oracle.score(q, k, eps=1e-6)
+    assert s[t0] == pytest.approx(W, abs=1e-10)
+    assert np.delete(s, t0).max() < 1e-10
+    # all W queries attend t0 equally: its Ahat is uniform over W
+    assert e[t0] == pytest.approx(math.log(W), abs=1e-5)
+
+
+def test_score_head_mean_is_linear_in_heads(oracle):
+    # s under a group of G heads equals the mean of the single-head scores (Eq. barA then Eq. st)
+    G, W, D, L = 4, 3, 8, 25
+    q = RNG.normal(size=(G, W, D))
+    k = RNG.normal(size=(L, D))
+    s, _ = oracle.score(q, k)
+    singles = np.stack([oracle.score(q[h:h + 1], k)[0] for h in range(G)])
+    np.testing.assert_allclose(s, singles.mean(axis=0), rtol=1e-12)
+    # G identical heads reduce to one head, entropy included
+    s1, e1 = oracle.score(q[:1], k)
+    s4, e4 = oracle.score(np.repeat(q[:1], 4, axis=0), k)
+    np.testing.assert_allclose(s4, s1, rtol=1e-12)
+    np.testing.assert_allclose(e4, e1, rtol=1e-10, atol=1e-14)
+
+
+def test_score_scale_uses_head_dim(oracle):
+    # doubling D by zero padding changes only the 1/sqrt(D) scale: equals scaling q by 1/sqrt(2)
+    G, W, D, L = 1, 2, 8, 20
+    q = RNG.normal(size=(G, W, D))
+    k = RNG.normal(size=(L, D))
+    qp = np.concatenate([q, np.zeros_like(q)], axis=-1)
+    kp = np.concatenate([k, np.zeros_like(k)], axis=-1)
+    np.testing.assert_allclose(oracle.score(qp, kp)[0], oracle.score(q / math.sqrt(2), k)[0], rtol=1e-12)
+
+
+# ------------------------------------------------------------------ refine
+def test_refine_hand_example(oracle):
+    # two segments of three tokens, alpha = 0.5, eta = 2; worked by hand:
+    # seg 1: I = .2, D = 1   -> omega = .2 * (1 + 2)   = .6 -> factor 1.3
+    # seg 2: I = .2, D = .5  -> omega = .2 * (1 + 1)   = .4 -> factor 1.2
+    s = [0.1, 0.3, 0.2, 0.4, 0.0, 0.2]
+    e = [1.0, 2.0, 0.0, 0.5, 0.5, 0.5]
+    st, om = oracle.refine(s, e, [0, 3, 6], alpha=0.5, eta=2.0)
+    np.testing.assert_allclose(om, [0.6, 0.4], rtol=1e-14)
+    np.testing.assert_allclose(st, [0.13, 0.39, 0.26, 0.48, 0.0, 0.24], rtol=1e-14)
+
+
+def test_refine_special_cases(oracle):
+    T = 200
+    s = RNG.random(T)
+    e = RNG.random(T) * 3
+    off = np.array([0, 7, 8, 50, 120, 200], dtype=np.int32)
+    st0, _ = oracle.refine(s, e, off, alpha=0.0, eta=1.0)
+    np.testing.assert_array_equal(st0, s)                               # alpha = 0: no change
+    _, om = oracle.refine(s, e, off, alpha=0.9, eta=0.0)                # eta = 0: omega = I_k
+    np.testing.assert_allclose(om, [s[a:b].mean() for a, b in zip(off[:-1], off[1:])], rtol=1e-13)
+    st, om = oracle.refine(s, e, off, alpha=0.9, eta=1.0)
+    for a, b in zip(off[:-1], off[1:]):                                 # order inside a segment unchanged
+        np.testing.assert_array_equal(np.argsort(-st[a:b], kind="stable"), np.argsort(-s[a:b], kind="stable"))
+        ratio = st[a:b] / s[a:b]
+        assert np.ptp(ratio) < 1e-12 and ratio[0] > 1.0
+    # one segment over everything: a single closed-form factor
+    st1, _ = oracle.refine(s, e, [0, T], alpha=0.9, eta=1.0)
+    c = 1.0 + 0.9 * s.mean() * (1.0 + e.mean())
+    np.testing.assert_allclose(st1, c * s, rtol=1e-13)
+
+
+# ------------------------------------------------------------------ search / select
+HAND = [9, 1, 1, 8, 7, 6, 1, 1, 5, 0.5, 0.5, 4]
+HAND_OFF = [0, 8, 12]
+
+
+@pytest.mark.parametrize("tau,g_exp,idx_exp", [
+    # worked by hand: Top-6 = {0,3,4,5,8,11}; b = (4, 2); base = (30, 9)
+    # seg 1: R(4) = 19/30, R(2) = 23/30; seg 2: R(2) = 5.5/9
+    (0.85, [1, 1], [0, 3, 4, 5, 8, 11]),
+    (0.75, [2, 1], [0, 1, 4, 5, 8, 11]),
+    (0.60, [4, 2], [0, 1, 2, 3, 8, 9]),
+])
+def test_search_hand_example(oracle, tau, g_exp, idx_exp):
+    b, g = oracle.search_blocks(HAND, HAND_OFF, [1, 2, 4], 6, tau)
+    assert b.tolist() == [4, 2]
+    assert g.tolist() == g_exp
+    idx, n = oracle.select(HAND, HAND_OFF, b, g, 6)
+    assert n == 6 and idx.tolist() == idx_exp
+
+
+def test_search_partial_block_and_short_tail_by_hand(oracle):
+    # one segment, B = 3: Top-3 = {5, 0, 1}, base 16; g = 4 infeasible (> b_k);
+    # g = 2: blocks 6, 4, 11 -> take {4,5}, then the best token of {0,1} (tie -> 0): 14/16 = .875
+    st = [3, 3, 3, 1, 1, 10]
+    b, g = oracle.search_blocks(st, [0, 6], [1, 2, 4], 3, 0.85)
+    assert (b.tolist(), g.tolist()) == ([3], [2])
+    assert oracle.select(st, [0, 6], b, g, 3)[0].tolist() == [0, 4, 5]
+    # short last block competes with its own (smaller) sum: blocks 2, 2, 9 -> {4}, then token 0
+    st = [1, 1, 1, 1, 9]
+    b, g = oracle.search_blocks(st, [0, 5], [1, 2], 2, 0.85)
+    assert (b.tolist(), g.tolist()) == ([2], [2])
+    assert oracle.select(st, [0, 5], b, g, 2)[0].tolist() == [0, 4]
+    sc, take = oracle.segment_score(st, 0, 5, 2, 2)
+    assert sc == 10.0 and take.tolist() == [True, False, False, False, True]
+
+
+def _random_case(rng, T, mean_len, levels=None):
+    lens = []
+    while sum(lens) < T:
+        lens.append(int(rng.integers(1, 2 * mean_len)))
+    off = np.minimum(np.concatenate([[0], np.cumsum(lens)]), T)
+    off = np.unique(off).astype(np.int32)
+    st = rng.random(T) ** 4
+    if levels:                          # few distinct values: exercises every tie-break
+        st = np.round(st * levels) / levels
+    return st, off
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_search_equals_brute_force_enumeration(oracle, seed):
+    rng = np.random.default_rng(seed)
+    T = int(rng.integers(40, 400))
+    st, off = _random_case(rng, T, int(rng.integers(3, 40)), levels=(8 if seed % 3 == 0 else None))
+    cand = [[1, 2, 4, 8], [1, 2, 3, 5, 7, 9, 11, 13], [1, 3, 4], [1]][seed % 4]
+    B = int(rng.integers(1, T))
+    tau = [0.85, 0.6, 0.95, 1.0][seed % 4]
+    b, g = oracle.search_blocks(st, off, cand, B, tau)
+    idx, n = oracle.select(st, off, b, g, B)
+    ref = bf.run(st, off.tolist(), cand, B, tau)
+    assert b.tolist() == ref["b"]
+    assert g.tolist() == ref["g"]            # Alg. 2's descending walk == Eq. gk_star's max-form
+    assert idx[:n].tolist() == ref["idx"]
+    # invariants the paper states
+    assert n == min(B, T) == int(b.sum())
+    assert (np.diff(idx[:n]) > 0).all()
+    for r in ref["segs"]:
+        for gg, (sc, base) in r["R"].items():
+            assert sc <= base * (1 + 1e-12)                      # baseline is the maximum: R <= 1
+            assert len(r["sets"][gg]) == r["bk"]                 # every candidate fills b_k exactly
+        if r["bk"]:
+            assert r["R"][1][0] == pytest.approx(r["base"], rel=1e-13)   # R_k(1) = 1
+
+
+def test_topb_is_library_sort(oracle):
+    rng = np.random.default_rng(7)
+    T, B = 500, 123
+    st = np.round(rng.random(T) * 50) / 50           # many ties
+    off = np.arange(0, T + 1, 10, dtype=np.int32)
+    b, g = oracle.search_blocks(st, off, [1], B, 0.85)
+    order = np.lexsort((np.arange(T), -st))[:B]       # value descending, index ascending
+    counts = np.bincount(order // 10, minlength=T // 10)
+    assert b.tolist() == counts.tolist()
+    idx, n = oracle.select(st, off, b, g, B)
+    assert idx[:n].tolist() == sorted(order.tolist())   # candidates {1}: plain token-level top-k
+
+
+def test_search_tau_extremes_and_budget_edges(oracle):
+    rng = np.random.default_rng(3)
+    st, off = _random_case(rng, 300, 20)
+    cand = [1, 2, 4, 8, 16]
+    b, g = oracle.search_blocks(st, off, cand, 150, 0.0)      # tau = 0: largest feasible candidate
+    lens = np.diff(off)
+    for bk, gk, ln in zip(b, g, lens):
+        assert gk == (max(c for c in cand if c <= min(bk, ln)) if bk else 0)
+    b, g = oracle.search_blocks(st, off, cand, 10 ** 6, 0.85)  # B >= T: everything kept
+    assert b.tolist() == lens.tolist()
+    idx, n = oracle.select(st, off, b, g, 300)
+    assert n == 300 and idx.tolist() == list(range(300))
+    b, g = oracle.search_blocks(st, off, cand, 0, 0.85)        # B = 0: nothing kept
+    assert not b.any() and not g.any()
+    assert oracle.select(st, off, b, g, 0)[1] == 0
+    # tau > 1: only candidates that reproduce the baseline exactly survive; g = 1 always does
+    b, g = oracle.search_blocks(st, off, cand, 100, 1.5)
+    assert set(g[b > 0].tolist()) <= set(cand) and (g[b > 0] >= 1).all()
+
+
+def test_blocks_never_cross_segments(oracle):
+    # selected tokens of a segment with g* > 1 are whole aligned blocks plus at most one partial block
+    rng = np.random.default_rng(11)
+    st, off = _random_case(rng, 600, 30)
+    b, g = oracle.search_blocks(st, off, [1, 2, 4, 8], 300, 0.5)
+    idx, n = oracle.select(st, off, b, g, 300)
+    sel = np.zeros(600, dtype=bool)
+    sel[idx[:n]] = True
+    assert (g > 1).sum() > 3
+    for k in range(len(off) - 1):
+        a, e_ = int(off[k]), int(off[k + 1])
+        assert sel[a:e_].sum() == b[k]
+        if g[k] > 1:
+            partial = 0
+            for lo in range(a, e_, int(g[k])):
+                cnt = sel[lo:min(lo + g[k], e_)].sum()
+                if 0 < cnt < min(lo + g[k], e_) - lo:
+                    partial += 1
+            assert partial <= 1
+
+
+def test_block_size_trend_with_budget_and_tau(oracle):
+    # sanity only (Sec. 3.3 / block-size trends): larger budget or smaller tau => larger blocks on average
+    rng = np.random.default_rng(5)
+    st, off = _random_case(rng, 4000, 32)
+    cand = [1, 2, 4, 8, 16]
+
+    def mean_g(B, tau):
+        b, g = oracle.search_blocks(st, off, cand, B, tau)
+        return (g * b).sum() / max(b.sum(), 1)
+
+    assert mean_g(100, 0.85) < mean_g(800, 0.85) < mean_g(3000, 0.85)
+    assert mean_g(800, 0.95) <= mean_g(800, 0.85) <= mean_g(800, 0.6)
+
+
+# ------------------------------------------------------------------ compact
+def test_compact_is_fancy_indexing(oracle):
+    rng = np.random.default_rng(9)
+    L, W, D, B = 90, 6, 16, 20
+    k = rng.integers(0, 2 ** 16, size=(L, D), dtype=np.uint16)
+    v = rng.integers(0, 2 ** 16, size=(L, D), dtype=np.uint16)
+    idx = np.sort(rng.choice(L - W, size=13, replace=False)).astype(np.int32)
+    full = np.concatenate([idx, -np.ones(B - 13, dtype=np.int32)])
+    ko, vo = oracle.compact(k, v, W, full, 13, B, append_window=True)
+    assert ko.shape == (B + W, D)
+    np.testing.assert_array_equal(ko[:13], k[idx])
+    np.testing.assert_array_equal(vo[:13], v[idx])
+    assert not ko[13:B].any() and not vo[13:B].any()
+    np.testing.assert_array_equal(ko[B:], k[L - W:])
+    np.testing.assert_array_equal(vo[B:], v[L - W:])
+    ko2, _ = oracle.compact(k.view(np.float16), v.view(np.float16), W, full, 13, B, append_window=False)
+    assert ko2.shape == (B, D)
+    np.testing.assert_array_equal(ko2.view(np.uint16)[:13], k[idx])
+
+
+# ------------------------------------------------------------------ whole path on the tiny workload
+def test_pipeline_tiny_invariants(oracle):
+    from paper_2510_22556_amd import synth
+
+    w = synth.WORKLOADS["tiny"]
+    q, k, v = synth.host_layer(w)
+    off, ptr = synth.workload_segments(w)
+    B = w.budget()
+    for j in range(w.n_kv_heads):
+        r = oracle.pipeline_head(q[j * w.G:(j + 1) * w.G], k[j], v[j], off, w.cand, B,
+                                 w.eps, w.alpha, w.eta, w.tau)
+        assert r["s"].sum() == pytest.approx(w.window, rel=1e-12)
+        assert r["n_sel"] == B and int(r["b"].sum()) == B
+        assert r["k_out"].shape == (B + w.window, w.head_dim)       # retained entries == cache budget
+        assert B + w.window <= w.cache_budgets[0]
+        np.testing.assert_array_equal(r["k_out"][:B], k[j][r["idx"]])
+        np.testing.assert_array_equal(r["v_out"][B:], v[j][w.T:])
+        ref = bf.run(r["s_tilde"], off.tolist(), list(w.cand), B, w.tau)
+        assert r["g"].tolist() == ref["g"] and r["idx"].tolist() == ref["idx"]
