@@ -1,0 +1,159 @@
+/*
+ * sablock.h -- C ABI of the SABlock prefill-time KV-cache compression path on
+ * MI355X (gfx950).
+ *
+ * The five calls are the steps of the paper's method in order:
+ *   sablock_score          window attention scores of every cached key   (Sec. 3.2, Eqs. barA, st, Dk)
+ *   sablock_refine         segment-guided score refinement               (Alg. 1, Eqs. Ik, Dk, omegak, st_tilde)
+ *   sablock_search_blocks  Top-B, implicit budgets, block-size search    (Alg. 2, Eqs. topk, implicit_budget, rk, gk_star)
+ *   sablock_select         per-segment token sets and their union        (Alg. 2, Eq. final_selection)
+ *   sablock_compact        gather of K/V rows into the retained cache    (end of Sec. 3.3)
+ *
+ * Conventions shared by all calls
+ * -------------------------------
+ * Problems.  A call covers n_seq sequences x n_layers layers x n_kv_heads KV
+ *   heads; every (sequence, layer, KV head) is an independent problem p =
+ *   (seq * n_layers + layer) * n_kv_heads + head, and every per-problem array
+ *   is dense in that order.  L = seq_len, W = window (observation window, the
+ *   paper's n_rcnt), T = L - W (compressible region), G = n_q_heads/n_kv_heads.
+ * Pointers.  Every pointer is a DEVICE pointer unless its comment says "host".
+ *   The caller owns all buffers; the library allocates no device memory, keeps
+ *   no state between calls and frees nothing.  Scratch comes from the
+ *   caller's workspace `ws` (device, 256-byte aligned) of at least
+ *   sablock_workspace_bytes() bytes; its contents are undefined between calls.
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = default stream).
+ *   Calls only enqueue work and return; outputs are valid once the stream
+ *   reaches that point; calls on one stream are ordered.
+ * Errors.  Status code only (never exceptions/aborts).  Host scalars are
+ *   validated before anything is enqueued: on a non-OK status nothing was
+ *   launched.  Device-resident data (segment offsets, NaNs) is not validated.
+ *   sablock_last_error() returns a thread-local message for the last failure.
+ * Segments.  Sequence s owns the offsets seg_off[seg_ptr[s] .. seg_ptr[s+1])
+ *   (device int32, CSR), first entry 0, strictly increasing, last entry T; its
+ *   segment count is K_s = seg_ptr[s+1] - seg_ptr[s] - 1.  seg_ptr is a HOST
+ *   array of n_seq+1 int32.  Segments are shared by all layers and heads of a
+ *   sequence.  Per-segment outputs use the row stride max_segments >= max_s K_s
+ *   passed by the caller; entries k >= K_s are written as 0.
+ * Ranking.  Wherever tokens or blocks are ranked: value descending, index
+ *   ascending.
+ */
+#ifndef SABLOCK_H
+#define SABLOCK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SABLOCK_API __attribute__((visibility("default")))
+
+typedef enum {
+    SABLOCK_OK = 0,
+    SABLOCK_ERR_INVALID_ARG = 1,          /* null pointer, negative or inconsistent host scalar */
+    SABLOCK_ERR_UNSUPPORTED = 2,          /* shape outside what the kernels cover */
+    SABLOCK_ERR_WORKSPACE_TOO_SMALL = 3,
+    SABLOCK_ERR_DEVICE = 4                /* a HIP call or launch failed */
+} sablock_status;
+
+typedef enum { SABLOCK_F32 = 0, SABLOCK_BF16 = 1 } sablock_dtype;
+
+/* Host scalars describing one call.  Strides are in ELEMENTS for the four outer
+ * axes (sequence, layer, head, token); the head_dim axis is contiguous. */
+typedef struct {
+    int32_t n_seq;
+    int32_t n_layers;
+    int32_t n_q_heads;        /* multiple of n_kv_heads */
+    int32_t n_kv_heads;
+    int32_t head_dim;         /* D: multiple of 8, 8 <= D <= 256 */
+    int32_t seq_len;          /* L */
+    int32_t window;           /* W: 1 <= W <= 64, W < L */
+    int32_t dtype;            /* sablock_dtype of Q, K, V and the compacted outputs */
+    int64_t q_stride[4];      /* Q window [n_seq][n_layers][n_q_heads][W][D]; token axis = window query */
+    int64_t k_stride[4];      /* K [n_seq][n_layers][n_kv_heads][L][D] */
+    int64_t v_stride[4];      /* V, same axes as K */
+} sablock_shape;
+
+/* Hyperparameters; the paper's defaults are eps 1e-6, alpha 0.9, eta 1.0, tau 0.85 (Sec. 4.1). */
+typedef struct { float eps, alpha, eta, tau; } sablock_hparams;
+
+SABLOCK_API const char *sablock_version(void);
+SABLOCK_API const char *sablock_last_error(void);
+
+/* Bytes of workspace that any of the calls below may need for this shape
+ * (host computation only).  max_segments and budget as passed to the calls. */
+SABLOCK_API sablock_status sablock_workspace_bytes(const sablock_shape *shape, int32_t max_segments,
+                                       int32_t budget, size_t *bytes_out /* host */);
+
+/* Window scoring (Sec. 3.2).  For each problem and each key t in [0, L):
+ *   A[h,i,t] = softmax over the keys visible to window query i (t <= T+i; causal
+ *              inside the window) of <Q[h,i,:], K[t,:]> / sqrt(D)      (Eq. 1)
+ *   Abar[i,t] = mean of A over the G query heads of the KV head          (Eq. barA)
+ *   s_out[p][t]   = sum_i Abar[i,t]                                      (Eq. st)
+ *   ent_out[p][t] = -sum_i Ahat[i,t] ln(Ahat[i,t] + eps), Ahat = Abar/s  (inner sum of Eq. Dk)
+ * q_win, k: shape->dtype, laid out by q_stride/k_stride.
+ * row_lse: optional [n_seq][n_layers][n_q_heads][W] float, the natural-log
+ *   sum-exp of each window query's scaled logits over its visible keys (what a
+ *   prefill attention kernel already has); when NULL it is computed here with an
+ *   extra pass over K.
+ * s_out, ent_out: [P][L] float.  Arithmetic: fp32 accumulate and outputs. */
+SABLOCK_API sablock_status sablock_score(const sablock_shape *shape, const void *q_win, const void *k,
+                             const float *row_lse /* nullable */, float eps,
+                             float *s_out, float *ent_out,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/* Segment-guided refinement (Alg. 1).  Per segment S_k of the compressible region:
+ *   I_k = mean s_t (Eq. Ik), D_k = mean ent_t (Eq. Dk), omega_k = I_k (1 + eta D_k) (Eq. omegak);
+ *   s_tilde_out[p][t] = s_t (1 + alpha omega_k(t)), t in [0, T)            (Eq. st_tilde)
+ * s, ent: [P][L] float (as written by sablock_score).  s_tilde_out: [P][T] float.
+ * omega_out: optional [P][max_segments] float.  Segment sums are accumulated in fp64. */
+SABLOCK_API sablock_status sablock_refine(const sablock_shape *shape, const float *s, const float *ent,
+                              const int32_t *seg_off, const int32_t *seg_ptr /* host */,
+                              int32_t max_segments, const sablock_hparams *hp /* host */,
+                              float *s_tilde_out, float *omega_out /* nullable */,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* Budget-driven block-size search (Alg. 2).  Per problem: T_topB = the min(budget, T)
+ * best tokens of s_tilde (Eq. topk); per segment b_k = |T_topB & S_k| (Eq.
+ * implicit_budget) and Score_base = sum of s_tilde over T_topB & S_k.  For each
+ * candidate g <= min(|S_k|, b_k), largest first: blocks of g tokens from the
+ * segment's first token (last block may be short), Phi = block sum, blocks taken
+ * in rank order while they fit in b_k, the first that does not fit is cut to its
+ * best (b_k - n) tokens; accepted iff Score_k(g) >= tau * Score_base (Eq. rk);
+ * g_k* = first accepted (Eq. gk_star); g = 1 is accepted unconditionally.
+ * cand: HOST array, ascending, cand[0] == 1, n_cand <= 16.  budget = the paper's B
+ *   (entries chosen from the compressible region; may exceed T, may be 0).
+ * seg_budget_out (b_k), block_size_out (g_k*, 0 where b_k == 0): [P][max_segments] int32.
+ * Block sums, scores and the accept test are evaluated in fp64 on the fp32 inputs. */
+SABLOCK_API sablock_status sablock_search_blocks(const sablock_shape *shape, const float *s_tilde,
+                                     const int32_t *seg_off, const int32_t *seg_ptr /* host */,
+                                     int32_t max_segments,
+                                     const int32_t *cand /* host */, int32_t n_cand,
+                                     int32_t budget, float tau,
+                                     int32_t *seg_budget_out, int32_t *block_size_out,
+                                     void *ws, size_t ws_bytes, void *stream);
+
+/* Selection (Alg. 2, Eq. final_selection): T_k* = T_k(g_k*) per segment, T* their union.
+ * seg_budget, block_size: as written by sablock_search_blocks for the same s_tilde.
+ * idx_out: [P][budget] int32, token indices in ascending order, entries past n_sel = -1.
+ * n_sel_out: [P] int32 (= min(budget, T)). */
+SABLOCK_API sablock_status sablock_select(const sablock_shape *shape, const float *s_tilde,
+                              const int32_t *seg_off, const int32_t *seg_ptr /* host */,
+                              int32_t max_segments,
+                              const int32_t *seg_budget, const int32_t *block_size, int32_t budget,
+                              int32_t *idx_out, int32_t *n_sel_out,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* Cache construction (end of Sec. 3.3): per problem, rows idx[0..n_sel) of K and V copied
+ * bit for bit, rows n_sel..budget-1 zero-filled, then, if append_window, the W most
+ * recent rows T..L-1 in order.  k, v: shape->dtype, laid out by k_stride / v_stride.
+ * k_out, v_out: dense [P][budget + (append_window ? W : 0)][D] of shape->dtype. */
+SABLOCK_API sablock_status sablock_compact(const sablock_shape *shape, const void *k, const void *v,
+                               const int32_t *idx, const int32_t *n_sel, int32_t budget,
+                               int32_t append_window, void *k_out, void *v_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SABLOCK_H */

@@ -1,0 +1,228 @@
+// Host side of the C ABI: argument validation, workspace carving, kernel dispatch.
+// Nothing here touches the device except kernel launches on the caller's stream.
+#include "sablock_internal.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+using namespace sablock;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+sablock_status fail(sablock_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+sablock_status make_dims(const sablock_shape *s, Dims *d)
+{
+    if (!s) return fail(SABLOCK_ERR_INVALID_ARG, "shape is NULL");
+    if (s->n_seq < 1 || s->n_layers < 1 || s->n_kv_heads < 1 || s->n_q_heads < 1)
+        return fail(SABLOCK_ERR_INVALID_ARG, "n_seq, n_layers, n_q_heads, n_kv_heads must be >= 1");
+    if (s->n_q_heads % s->n_kv_heads != 0)
+        return fail(SABLOCK_ERR_INVALID_ARG, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)", s->n_q_heads, s->n_kv_heads);
+    if (s->window < 1 || s->seq_len < 2 || s->window >= s->seq_len)
+        return fail(SABLOCK_ERR_INVALID_ARG, "need 1 <= window < seq_len (window %d, seq_len %d)", s->window, s->seq_len);
+    if (s->dtype != SABLOCK_F32 && s->dtype != SABLOCK_BF16)
+        return fail(SABLOCK_ERR_INVALID_ARG, "unknown dtype %d", s->dtype);
+    if (s->head_dim < 8 || s->head_dim > 256 || s->head_dim % 8 != 0)
+        return fail(SABLOCK_ERR_UNSUPPORTED, "head_dim %d: need a multiple of 8 in [8, 256]", s->head_dim);
+    if (s->window > 64) return fail(SABLOCK_ERR_UNSUPPORTED, "window %d: at most 64", s->window);
+    if (s->n_seq > MAX_SEQ) return fail(SABLOCK_ERR_UNSUPPORTED, "n_seq %d: at most %d per call", s->n_seq, MAX_SEQ);
+    const int64_t P = (int64_t)s->n_seq * s->n_layers * s->n_kv_heads;
+    if (P > 65535) return fail(SABLOCK_ERR_UNSUPPORTED, "n_seq*n_layers*n_kv_heads = %lld: at most 65535 per call", (long long)P);
+    if ((int64_t)s->n_q_heads / s->n_kv_heads * s->window > 1024)
+        return fail(SABLOCK_ERR_UNSUPPORTED, "G*W > 1024");
+    for (int a = 0; a < 4; ++a) {
+        if (s->q_stride[a] < 0 || s->k_stride[a] < 0 || s->v_stride[a] < 0)
+            return fail(SABLOCK_ERR_INVALID_ARG, "negative stride");
+        if (s->q_stride[a] % 8 || s->k_stride[a] % 8 || s->v_stride[a] % 8)
+            return fail(SABLOCK_ERR_UNSUPPORTED, "strides must be multiples of 8 elements (16-byte row alignment)");
+    }
+    if (s->q_stride[3] < s->head_dim || s->k_stride[3] < s->head_dim)
+        return fail(SABLOCK_ERR_INVALID_ARG, "token stride smaller than head_dim");
+    d->n_seq = s->n_seq; d->n_layers = s->n_layers; d->Hq = s->n_q_heads; d->Hkv = s->n_kv_heads;
+    d->G = s->n_q_heads / s->n_kv_heads; d->D = s->head_dim; d->L = s->seq_len; d->W = s->window;
+    d->T = s->seq_len - s->window; d->M = d->G * d->W; d->P = (int32_t)P; d->dtype = s->dtype;
+    for (int a = 0; a < 4; ++a) { d->qs[a] = s->q_stride[a]; d->ks[a] = s->k_stride[a]; d->vs[a] = s->v_stride[a]; }
+    return SABLOCK_OK;
+}
+
+sablock_status make_segview(const Dims &d, const int32_t *seg_off, const int32_t *seg_ptr, int32_t max_segments,
+                            SegView *sv)
+{
+    if (!seg_off || !seg_ptr) return fail(SABLOCK_ERR_INVALID_ARG, "seg_off or seg_ptr is NULL");
+    if (max_segments < 0) return fail(SABLOCK_ERR_INVALID_ARG, "max_segments < 0");
+    if (seg_ptr[0] < 0) return fail(SABLOCK_ERR_INVALID_ARG, "seg_ptr[0] < 0");
+    for (int s = 0; s < d.n_seq; ++s) {
+        const int n = seg_ptr[s + 1] - seg_ptr[s];
+        if (n < 1) return fail(SABLOCK_ERR_INVALID_ARG, "sequence %d: seg_ptr must leave at least one offset", s);
+        if (n - 1 > max_segments)
+            return fail(SABLOCK_ERR_INVALID_ARG, "sequence %d has %d segments > max_segments %d", s, n - 1, max_segments);
+    }
+    sv->seg_off = seg_off;
+    sv->max_segments = max_segments;
+    memset(sv->seq_ptr, 0, sizeof(sv->seq_ptr));
+    for (int s = 0; s <= d.n_seq; ++s) sv->seq_ptr[s] = seg_ptr[s];
+    return SABLOCK_OK;
+}
+
+size_t score_ws(const Dims &d)
+{
+    size_t a = score_generic_ws_bytes(d);
+    if (score_mfma_supported(d)) { size_t b = score_mfma_ws_bytes(d); if (b > a) a = b; }
+    return a;
+}
+size_t search_ws(const Dims &d) { return align256((size_t)d.P * 2 * 4); }
+
+sablock_status dev(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return SABLOCK_OK;
+    return fail(SABLOCK_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *sablock_version(void) { return "sablock-gfx950 0.1"; }
+const char *sablock_last_error(void) { return g_err; }
+
+sablock_status sablock_workspace_bytes(const sablock_shape *shape, int32_t max_segments, int32_t budget,
+                                       size_t *bytes_out)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!bytes_out) return fail(SABLOCK_ERR_INVALID_ARG, "bytes_out is NULL");
+    if (max_segments < 0 || budget < 0) return fail(SABLOCK_ERR_INVALID_ARG, "max_segments or budget < 0");
+    size_t b = score_ws(d);
+    size_t c = search_ws(d); if (c > b) b = c;
+    c = select_ws_bytes(d, max_segments); if (c > b) b = c;
+    *bytes_out = b + 256;
+    return SABLOCK_OK;
+}
+
+sablock_status sablock_score(const sablock_shape *shape, const void *q_win, const void *k,
+                             const float *row_lse, float eps, float *s_out, float *ent_out,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!q_win || !k || !s_out || !ent_out) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score: NULL tensor");
+    if (!aligned16(q_win) || !aligned16(k)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score: Q/K must be 16-byte aligned");
+    if (!(eps >= 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score: eps must be >= 0");
+    const bool mfma = score_mfma_supported(d);
+    const size_t need = row_lse && !mfma ? 0 : (mfma ? score_mfma_ws_bytes(d) : score_generic_ws_bytes(d));
+    if (need && (!ws || ws_bytes < need))
+        return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_score: workspace %zu < %zu bytes", ws_bytes, need);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    hipError_t e = mfma ? launch_score_mfma(d, q_win, k, row_lse, eps, s_out, ent_out, ws, hs)
+                        : launch_score_generic(d, q_win, k, row_lse, eps, s_out, ent_out, ws, hs);
+    return dev(e, "sablock_score");
+}
+
+sablock_status sablock_refine(const sablock_shape *shape, const float *s, const float *ent,
+                              const int32_t *seg_off, const int32_t *seg_ptr, int32_t max_segments,
+                              const sablock_hparams *hp, float *s_tilde_out, float *omega_out,
+                              void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!s || !ent || !s_tilde_out || !hp) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_refine: NULL argument");
+    if (!(hp->alpha >= 0.f) || !(hp->eta >= 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_refine: alpha, eta must be >= 0");
+    SegView sv;
+    st = make_segview(d, seg_off, seg_ptr, max_segments, &sv);
+    if (st != SABLOCK_OK) return st;
+    return dev(launch_refine(d, s, ent, sv, *hp, s_tilde_out, omega_out, static_cast<hipStream_t>(stream)),
+               "sablock_refine");
+}
+
+sablock_status sablock_search_blocks(const sablock_shape *shape, const float *s_tilde,
+                                     const int32_t *seg_off, const int32_t *seg_ptr, int32_t max_segments,
+                                     const int32_t *cand, int32_t n_cand, int32_t budget, float tau,
+                                     int32_t *seg_budget_out, int32_t *block_size_out,
+                                     void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!s_tilde || !seg_budget_out || !block_size_out || !cand)
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: NULL argument");
+    if (budget < 0) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: budget < 0");
+    if (!(tau >= 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: tau must be >= 0");
+    if (n_cand < 1 || n_cand > MAX_CAND) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: n_cand must be in [1, %d]", MAX_CAND);
+    if (cand[0] != 1) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: cand[0] must be 1");
+    CandList cl;
+    memset(&cl, 0, sizeof(cl));
+    cl.n = n_cand;
+    for (int c = 0; c < n_cand; ++c) {
+        if (c && cand[c] <= cand[c - 1]) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: cand must be strictly ascending");
+        if (cand[c] > 64) return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_search_blocks: block size %d > 64", cand[c]);
+        cl.g[c] = cand[c];
+    }
+    SegView sv;
+    st = make_segview(d, seg_off, seg_ptr, max_segments, &sv);
+    if (st != SABLOCK_OK) return st;
+    const size_t need = search_ws(d);
+    if (!ws || ws_bytes < need)
+        return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_search_blocks: workspace %zu < %zu bytes", ws_bytes, need);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    int32_t *thr = static_cast<int32_t *>(ws);
+    hipError_t e = launch_topb(d, s_tilde, budget, thr, hs);
+    if (e == hipSuccess) e = launch_search(d, s_tilde, sv, cl, tau, thr, seg_budget_out, block_size_out, hs);
+    return dev(e, "sablock_search_blocks");
+}
+
+sablock_status sablock_select(const sablock_shape *shape, const float *s_tilde,
+                              const int32_t *seg_off, const int32_t *seg_ptr, int32_t max_segments,
+                              const int32_t *seg_budget, const int32_t *block_size, int32_t budget,
+                              int32_t *idx_out, int32_t *n_sel_out, void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!s_tilde || !seg_budget || !block_size || !n_sel_out || (!idx_out && budget > 0))
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_select: NULL argument");
+    if (budget < 0) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_select: budget < 0");
+    SegView sv;
+    st = make_segview(d, seg_off, seg_ptr, max_segments, &sv);
+    if (st != SABLOCK_OK) return st;
+    const size_t need = select_ws_bytes(d, max_segments);
+    if (!ws || ws_bytes < need)
+        return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_select: workspace %zu < %zu bytes", ws_bytes, need);
+    return dev(launch_select(d, s_tilde, sv, seg_budget, block_size, budget, idx_out, n_sel_out, ws,
+                             static_cast<hipStream_t>(stream)), "sablock_select");
+}
+
+sablock_status sablock_compact(const sablock_shape *shape, const void *k, const void *v,
+                               const int32_t *idx, const int32_t *n_sel, int32_t budget,
+                               int32_t append_window, void *k_out, void *v_out, void *stream)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (budget < 0) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact: budget < 0");
+    if (!k || !v || !n_sel || (!idx && budget > 0)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact: NULL argument");
+    const int rows = budget + (append_window ? d.W : 0);
+    if (rows > 0 && (!k_out || !v_out)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact: NULL output");
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact: K/V buffers must be 16-byte aligned");
+    if (shape->v_stride[3] < d.D) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact: V token stride smaller than head_dim");
+    return dev(launch_compact(d, k, v, idx, n_sel, budget, append_window, k_out, v_out,
+                              static_cast<hipStream_t>(stream)), "sablock_compact");
+}
+
+}  // extern "C"

@@ -1,0 +1,54 @@
+// Cache construction (end of Sec. 3.3): gather the retained K/V rows, then the
+// observation-window rows, into a dense cache.  Pure bit copy, 16 bytes per lane,
+// a row (D elements) per group of consecutive lanes so that both the gathered
+// reads and the dense writes are coalesced row-wise.
+#include "sablock_internal.h"
+
+namespace sablock {
+namespace {
+
+constexpr int NT = 256;
+
+// grid (ceil(rows * chunks / NT), P, 2): z = 0 copies K, z = 1 copies V
+__global__ void __launch_bounds__(NT)
+compact_kernel(Dims d, const char *k, const char *v, const int32_t *idx, const int32_t *n_sel,
+               int budget, int rows, int chunks, int elt, char *k_out, char *v_out)
+{
+    const int p = blockIdx.y;
+    const int e = blockIdx.x * NT + threadIdx.x;
+    if (e >= rows * chunks) return;
+    const int row = e / chunks, ch = e - row * chunks;
+    const bool is_v = blockIdx.z != 0;
+    const char *src = is_v ? v : k;
+    char *dst = (is_v ? v_out : k_out) + ((int64_t)p * rows + row) * ((int64_t)chunks * 16) + (int64_t)ch * 16;
+    const int64_t poff = is_v ? v_problem_offset(d, p) : k_problem_offset(d, p);
+    const int64_t tstride = is_v ? d.vs[3] : d.ks[3];
+    int t;
+    if (row < budget) {
+        t = (row < n_sel[p]) ? idx[(int64_t)p * budget + row] : -1;
+    } else {
+        t = d.T + (row - budget);                       // the W most recent rows, in order
+    }
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (t >= 0 && t < d.L) val = *reinterpret_cast<const uint4 *>(src + (poff + (int64_t)t * tstride) * elt + (int64_t)ch * 16);
+    *reinterpret_cast<uint4 *>(dst) = val;
+}
+
+}  // namespace
+
+hipError_t launch_compact(const Dims &d, const void *k, const void *v, const int32_t *idx,
+                          const int32_t *n_sel, int32_t budget, int32_t append_window,
+                          void *k_out, void *v_out, hipStream_t st)
+{
+    const int elt = d.dtype == SABLOCK_F32 ? 4 : 2;
+    const int rows = budget + (append_window ? d.W : 0);
+    const int chunks = d.D * elt / 16;
+    if (rows <= 0 || d.P <= 0) return hipSuccess;
+    dim3 grid((unsigned)(((int64_t)rows * chunks + NT - 1) / NT), d.P, 2);
+    hipLaunchKernelGGL(compact_kernel, grid, dim3(NT), 0, st, d, static_cast<const char *>(k),
+                       static_cast<const char *>(v), idx, n_sel, budget, rows, chunks, elt,
+                       static_cast<char *>(k_out), static_cast<char *>(v_out));
+    return hipGetLastError();
+}
+
+}  // namespace sablock

@@ -1,0 +1,99 @@
+// Internal declarations shared by the host ABI layer and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/sablock.h"
+
+namespace sablock {
+
+// Host-validated view of one call; passed to kernels by value.
+struct Dims {
+    int32_t n_seq, n_layers, Hq, Hkv, G, D, L, W, T, M;   // M = G * W rows of the window-query matrix
+    int32_t P;                                            // problems = n_seq * n_layers * Hkv
+    int32_t dtype;
+    int64_t qs[4], ks[4], vs[4];
+};
+
+constexpr int MAX_SEQ = 64;
+constexpr int MAX_CAND = 16;
+
+struct SegView {
+    const int32_t *seg_off;      // device, CSR
+    int32_t seq_ptr[MAX_SEQ + 1];  // host copy of the CSR pointers, travels in the kernel arguments
+    int32_t max_segments;
+};
+
+struct CandList {
+    int32_t n;
+    int32_t g[MAX_CAND];
+};
+
+__host__ __device__ inline int32_t seq_of_problem(const Dims &d, int32_t p) { return p / (d.n_layers * d.Hkv); }
+__host__ __device__ inline int32_t layer_of_problem(const Dims &d, int32_t p) { return (p / d.Hkv) % d.n_layers; }
+__host__ __device__ inline int32_t head_of_problem(const Dims &d, int32_t p) { return p % d.Hkv; }
+
+__host__ __device__ inline int64_t k_problem_offset(const Dims &d, int32_t p)
+{
+    return seq_of_problem(d, p) * d.ks[0] + layer_of_problem(d, p) * d.ks[1] + head_of_problem(d, p) * d.ks[2];
+}
+__host__ __device__ inline int64_t v_problem_offset(const Dims &d, int32_t p)
+{
+    return seq_of_problem(d, p) * d.vs[0] + layer_of_problem(d, p) * d.vs[1] + head_of_problem(d, p) * d.vs[2];
+}
+// offset of window-query row (h_local, i) of problem p
+__host__ __device__ inline int64_t q_row_offset(const Dims &d, int32_t p, int32_t h_local, int32_t i)
+{
+    return seq_of_problem(d, p) * d.qs[0] + layer_of_problem(d, p) * d.qs[1] +
+           (int64_t)(head_of_problem(d, p) * d.G + h_local) * d.qs[2] + (int64_t)i * d.qs[3];
+}
+
+// order-preserving map float -> uint32 (larger float <=> larger key)
+__host__ __device__ inline uint32_t ordered_key(float f)
+{
+    uint32_t u;
+#if defined(__HIP_DEVICE_COMPILE__)
+    u = __float_as_uint(f);
+#else
+    __builtin_memcpy(&u, &f, 4);
+#endif
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ---- kernel launchers (each returns the hipError_t of its launches) ----
+
+// generic (any shape/dtype) scoring; row statistics go through ws
+size_t score_generic_ws_bytes(const Dims &d);
+hipError_t launch_score_generic(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
+                                float *s_out, float *ent_out, void *ws, hipStream_t st);
+
+// MFMA scoring for bf16, D = 128, G*W = 128
+bool score_mfma_supported(const Dims &d);
+size_t score_mfma_ws_bytes(const Dims &d);
+hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
+                             float *s_out, float *ent_out, void *ws, hipStream_t st);
+
+hipError_t launch_refine(const Dims &d, const float *s, const float *ent, const SegView &sv,
+                         sablock_hparams hp, float *s_tilde, float *omega, hipStream_t st);
+
+// Top-B threshold per problem: thr[p] = {ordered key of the B-th best score, index cut among its ties}
+hipError_t launch_topb(const Dims &d, const float *s_tilde, int32_t budget, int32_t *thr, hipStream_t st);
+
+hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
+                         float tau, const int32_t *thr, int32_t *seg_budget, int32_t *block_size,
+                         hipStream_t st);
+
+size_t select_ws_bytes(const Dims &d, int32_t max_segments);
+hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv, const int32_t *seg_budget,
+                         const int32_t *block_size, int32_t budget, int32_t *idx_out, int32_t *n_sel_out,
+                         void *ws, hipStream_t st);
+
+hipError_t launch_compact(const Dims &d, const void *k, const void *v, const int32_t *idx,
+                          const int32_t *n_sel, int32_t budget, int32_t append_window,
+                          void *k_out, void *v_out, hipStream_t st);
+
+}  // namespace sablock

@@ -1,0 +1,445 @@
+// Budget-driven block-size search and selection (Alg. 2; Eqs. topk,
+// implicit_budget, rk, gk_star, final_selection).
+//
+// topb_kernel     one workgroup per problem: LDS radix select (11+11+10 bits) of
+//                 the min(B,T)-th best score, ties resolved by ascending index.
+//                 Result: (ordered key v, index cut c); token t is in T_topB iff
+//                 key(t) > v or (key(t) == v and t <= c).
+// search_kernel   one wavefront per (problem, segment): b_k, Score_base, then the
+//                 candidates largest first.
+// select_kernel   one wavefront per (problem, segment): T_k(g_k*) written in
+//                 ascending order at the segment's offset (prefix sum of b_k).
+//
+// All quantities that decide an integer (block sums Phi, Score_k(g), Score_base,
+// tau * Score_base) are fp64 and summed in ascending token order, one addition at
+// a time, so that they are identical for identical fp32 inputs regardless of how
+// the work is spread over lanes.  Rankings use (value descending, index ascending).
+#include "sablock_internal.h"
+
+namespace sablock {
+namespace {
+
+constexpr int WAVES = 4;            // wavefronts (segments) per workgroup in search/select
+constexpr int CAPB = 1024;          // blocks per segment whose Phi/class fit the wave's LDS slice
+constexpr int MAX_G = 64;           // largest candidate block size
+
+__device__ inline int wave_sum_i(int v)
+{
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+__device__ inline int wave_max_i(int v)
+{
+    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off));
+    return v;
+}
+
+// acc += v[j] for every set bit j of mask, ascending; mask and acc are wave-uniform
+__device__ inline double add_in_order(double acc, unsigned long long mask, float v)
+{
+    while (mask) {
+        int j = __builtin_ctzll(mask);
+        acc += (double)__shfl(v, j);
+        mask &= mask - 1;
+    }
+    return acc;
+}
+
+// ------------------------------------------------------------------ Top-B
+constexpr int TB_THREADS = 1024;
+
+__global__ void __launch_bounds__(TB_THREADS)
+topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr)
+{
+    __shared__ uint32_t hist[2048];
+    __shared__ uint32_t sh_bin, sh_above;
+    __shared__ int sh_wcnt[TB_THREADS / 64];
+    __shared__ int sh_cut;
+    const int p = blockIdx.x, T = d.T;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *sp = s_tilde + (int64_t)p * T;
+    const int k = min(budget, T);
+    if (k <= 0) { if (tid == 0) { thr[2 * p] = (int32_t)0xFFFFFFFFu; thr[2 * p + 1] = -1; } return; }
+    if (k >= T) { if (tid == 0) { thr[2 * p] = 0; thr[2 * p + 1] = T - 1; } return; }
+
+    uint32_t prefix = 0, mask = 0, krem = (uint32_t)k, n_eq = 0;
+    const int shifts[3] = {21, 10, 0};
+    const int bits[3] = {11, 11, 10};
+    for (int pass = 0; pass < 3; ++pass) {
+        const int nbins = 1 << bits[pass], shift = shifts[pass];
+        for (int i = tid; i < nbins; i += TB_THREADS) hist[i] = 0;
+        __syncthreads();
+        for (int t = tid; t < T; t += TB_THREADS) {
+            uint32_t key = ordered_key(sp[t]);
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (nbins - 1)], 1u);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // position r counts bins from the top: r = nbins-1-bin; lane owns `per` consecutive positions
+            const int per = nbins / 64;
+            uint32_t mine = 0;
+            for (int j = 0; j < per; ++j) mine += hist[nbins - 1 - (lane * per + j)];
+            uint32_t incl = mine;
+            for (int off = 1; off < 64; off <<= 1) {
+                uint32_t o = __shfl_up(incl, off);
+                if (lane >= off) incl += o;
+            }
+            uint32_t excl = incl - mine;
+            if (excl < krem && krem <= incl) {
+                uint32_t run = excl;
+                for (int j = 0; j < per; ++j) {
+                    int bin = nbins - 1 - (lane * per + j);
+                    uint32_t c = hist[bin];
+                    if (run + c >= krem) { sh_bin = (uint32_t)bin; sh_above = run; break; }
+                    run += c;
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t bin = sh_bin;
+        krem -= sh_above;
+        n_eq = hist[bin];
+        prefix |= bin << shift;
+        mask |= (uint32_t)(nbins - 1) << shift;
+        __syncthreads();
+    }
+    // prefix is the key v of the k-th best score; krem of its n_eq ties are inside, lowest indices first
+    int cut = T - 1;
+    if (krem < n_eq) {
+        int seen = 0;
+        for (int c0 = 0; c0 < T; c0 += TB_THREADS) {
+            const int t = c0 + tid;
+            const bool tie = t < T && ordered_key(sp[t]) == prefix;
+            const unsigned long long bal = __ballot(tie);
+            if (lane == 0) sh_wcnt[wave] = __popcll(bal);
+            __syncthreads();
+            int before = 0, total = 0;
+            for (int w = 0; w < TB_THREADS / 64; ++w) { int c = sh_wcnt[w]; if (w < wave) before += c; total += c; }
+            const bool found = seen + total >= (int)krem;
+            if (found && tie && seen + before + __popcll(bal & ((1ull << lane) - 1ull)) + 1 == (int)krem) sh_cut = t;
+            __syncthreads();
+            if (found) { cut = sh_cut; break; }
+            seen += total;
+        }
+    }
+    if (tid == 0) { thr[2 * p] = (int32_t)prefix; thr[2 * p + 1] = cut; }
+}
+
+// ------------------------------------------------------------------ one segment, one block size
+struct WaveScratch {
+    double *phi;        // CAPB block sums
+    uint8_t *cls;       // CAPB block classes: 0 not taken, 1 taken whole, 2 cut to its best tokens
+};
+
+// Phi of block m of segment [a,b) with block size g: ascending fp64 sum
+__device__ inline double block_sum(const float *sp, int a, int b, int g, int m)
+{
+    const int lo = a + m * g, hi = min(lo + g, b);
+    double phi = 0.0;
+    for (int t = lo; t < hi; ++t) phi += (double)sp[t];
+    return phi;
+}
+
+// number of blocks ranked before block m
+__device__ inline int block_rank(const float *sp, int a, int b, int g, int nb, int m, double phi_m,
+                                 const double *phi_lds, bool fast)
+{
+    int r = 0;
+    for (int o = 0; o < nb; ++o) {
+        double po = fast ? phi_lds[o] : block_sum(sp, a, b, g, o);
+        r += (po > phi_m || (po == phi_m && o < m)) ? 1 : 0;
+    }
+    return r;
+}
+
+// T_k(g) for segment [a,b) with implicit budget bk (Alg. 2's inner loop).  Calls
+// emit(c0, taken_mask, value) for each 64-token chunk in ascending order; lane l
+// of the chunk starting at token c0 holds the value of token c0 + l.
+// Requires 1 <= g <= MAX_G, g <= min(b - a, bk); all arguments wave-uniform.
+template <typename F>
+__device__ inline void segment_fill(const float *sp, int a, int b, int g, int bk, WaveScratch ws, F &&emit)
+{
+    const int lane = threadIdx.x & 63;
+    const int len = b - a;
+    const int nb = (len + g - 1) / g;
+    const int ts = len - (nb - 1) * g;                 // size of the last block, 1..g
+    const bool fast = nb <= CAPB;
+    const int mt = nb - 1;
+
+    if (fast) {
+        for (int m = lane; m < nb; m += 64) ws.phi[m] = block_sum(sp, a, b, g, m);
+        __builtin_amdgcn_wave_barrier();
+    }
+    // blocks taken whole: the first rstar in rank order; all blocks have g tokens except a short last one,
+    // whose rank q decides how many blocks fit
+    int rstar, nwhole;
+    if (ts == g) {
+        rstar = min(nb, bk / g);
+        nwhole = rstar * g;
+    } else {
+        const double phi_t = fast ? ws.phi[mt] : block_sum(sp, a, b, g, mt);
+        int cnt = 0;
+        for (int o = lane; o < mt; o += 64) {
+            double po = fast ? ws.phi[o] : block_sum(sp, a, b, g, o);
+            cnt += (po >= phi_t) ? 1 : 0;                // o < mt: an equal sum ranks first
+        }
+        const int q = wave_sum_i(cnt);
+        const int c = bk / g, r = bk - c * g;
+        if (q < c) {
+            if (ts <= r) { rstar = c + 1; nwhole = c * g + ts; } else { rstar = c; nwhole = c * g - g + ts; }
+        } else if (q == c) {
+            if (ts <= r) { rstar = c + 1; nwhole = c * g + ts; } else { rstar = c; nwhole = c * g; }
+        } else {
+            rstar = c; nwhole = c * g;
+        }
+        rstar = min(rstar, nb);
+    }
+    const int rem = bk - nwhole;                         // tokens to take from the block ranked rstar
+
+    // classify blocks; remember the cut block
+    int mp_local = -1;
+    if (fast) {
+        for (int m = lane; m < nb; m += 64) {
+            int rk = (rstar >= nb) ? 0 : block_rank(sp, a, b, g, nb, m, ws.phi[m], ws.phi, true);
+            uint8_t c = (rk < rstar) ? 1 : ((rk == rstar && rem > 0) ? 2 : 0);
+            ws.cls[m] = c;
+            if (c == 2) mp_local = m;
+        }
+        __builtin_amdgcn_wave_barrier();
+    } else if (rem > 0 && rstar < nb) {
+        for (int m = lane; m < nb; m += 64) {
+            int rk = block_rank(sp, a, b, g, nb, m, block_sum(sp, a, b, g, m), nullptr, false);
+            if (rk == rstar) mp_local = m;
+        }
+    }
+    const int mp = wave_max_i(mp_local);
+
+    // inside the cut block: its best rem tokens
+    unsigned long long pmask = 0;
+    int plo = 0;
+    if (mp >= 0) {
+        plo = a + mp * g;
+        const int phi_hi = min(plo + g, b);
+        const int sz = phi_hi - plo;
+        bool tk = false;
+        if (lane < sz) {
+            const float v = sp[plo + lane];
+            int rk = 0;
+            for (int j = 0; j < sz; ++j) {
+                float o = sp[plo + j];
+                rk += (o > v || (o == v && j < lane)) ? 1 : 0;
+            }
+            tk = rk < rem;
+        }
+        pmask = __ballot(tk);
+    }
+
+    for (int c0 = a; c0 < b; c0 += 64) {
+        const int t = c0 + lane;
+        const bool live = t < b;
+        float v = 0.f;
+        bool take = false;
+        if (live) {
+            v = sp[t];
+            const int m = (t - a) / g;
+            int c;
+            if (fast) {
+                c = ws.cls[m];
+            } else {
+                int rk = (rstar >= nb) ? 0 : block_rank(sp, a, b, g, nb, m, block_sum(sp, a, b, g, m), nullptr, false);
+                c = (rk < rstar) ? 1 : ((m == mp) ? 2 : 0);
+            }
+            take = (c == 1) || (c == 2 && ((pmask >> (t - plo)) & 1ull));
+        }
+        emit(c0, __ballot(take), v);
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ inline bool in_topb(float v, int t, uint32_t thr_key, int thr_cut)
+{
+    const uint32_t key = ordered_key(v);
+    return key > thr_key || (key == thr_key && t <= thr_cut);
+}
+
+// ------------------------------------------------------------------ search
+// grid (ceil(max_segments / WAVES), P)
+__global__ void __launch_bounds__(WAVES * 64)
+search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau, const int32_t *thr,
+              int32_t *seg_budget, int32_t *block_size)
+{
+    __shared__ double sh_phi[WAVES][CAPB];
+    __shared__ uint8_t sh_cls[WAVES][CAPB];
+    const int p = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = blockIdx.x * WAVES + wave;
+    if (k >= sv.max_segments) return;
+    const int seq = seq_of_problem(d, p);
+    const int sbase = sv.seq_ptr[seq];
+    const int K = sv.seq_ptr[seq + 1] - sbase - 1;
+    const int64_t o = (int64_t)p * sv.max_segments + k;
+    if (k >= K) {
+        if (lane == 0) { seg_budget[o] = 0; block_size[o] = 0; }
+        return;
+    }
+    const int a = sv.seg_off[sbase + k], b = sv.seg_off[sbase + k + 1];
+    const float *sp = s_tilde + (int64_t)p * d.T;
+    const uint32_t thr_key = (uint32_t)thr[2 * p];
+    const int thr_cut = thr[2 * p + 1];
+
+    // implicit budget b_k (Eq. implicit_budget) and token-level baseline Score_base
+    int bk = 0;
+    double base = 0.0;
+    for (int c0 = a; c0 < b; c0 += 64) {
+        const int t = c0 + lane;
+        float v = 0.f;
+        bool in = false;
+        if (t < b) { v = sp[t]; in = in_topb(v, t, thr_key, thr_cut); }
+        const unsigned long long m = __ballot(in);
+        bk += __popcll(m);
+        base = add_in_order(base, m, v);
+    }
+    int gstar = 0;
+    if (bk > 0) {
+        const int gcap = min(b - a, bk);                    // G_k: g <= min(|S_k|, b_k, g_max)
+        const double need = (double)tau * base;            // R_k(g) >= tau  <=>  Score_k(g) >= tau * Score_base
+        WaveScratch ws{sh_phi[wave], sh_cls[wave]};
+        for (int c = cand.n - 1; c >= 0; --c) {
+            const int g = cand.g[c];
+            if (g > gcap) continue;
+            if (g == 1) { gstar = 1; break; }               // token level: the unconditional last resort
+            double score = 0.0;
+            segment_fill(sp, a, b, g, bk, ws,
+                         [&](int, unsigned long long m, float v) { score = add_in_order(score, m, v); });
+            if (score >= need) { gstar = g; break; }        // Eq. gk_star: first accepted, largest first
+        }
+    }
+    if (lane == 0) { seg_budget[o] = bk; block_size[o] = gstar; }
+}
+
+// ------------------------------------------------------------------ select
+// exclusive prefix of b_k over the segments of one problem; also n_sel and the -1 padding of idx_out
+__global__ void __launch_bounds__(256)
+seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, int budget, int32_t *prefix,
+                  int32_t *idx_out, int32_t *n_sel_out)
+{
+    __shared__ int sh_w[4];
+    const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seq = seq_of_problem(d, p);
+    const int K = sv.seq_ptr[seq + 1] - sv.seq_ptr[seq] - 1;
+    const int32_t *bp = seg_budget + (int64_t)p * sv.max_segments;
+    int32_t *pp = prefix + (int64_t)p * sv.max_segments;
+    int carry = 0;
+    for (int c0 = 0; c0 < K; c0 += 256) {
+        const int k = c0 + tid;
+        const int v = (k < K) ? bp[k] : 0;
+        int incl = v;
+        for (int off = 1; off < 64; off <<= 1) { int o = __shfl_up(incl, off); if (lane >= off) incl += o; }
+        if (lane == 63) sh_w[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+        for (int w = 0; w < 4; ++w) { if (w < wave) before += sh_w[w]; total += sh_w[w]; }
+        if (k < K) pp[k] = carry + before + incl - v;
+        carry += total;
+        __syncthreads();
+    }
+    const int n = min(carry, budget);
+    if (tid == 0) n_sel_out[p] = n;
+    for (int j = n + tid; j < budget; j += 256) idx_out[(int64_t)p * budget + j] = -1;
+}
+
+// grid (ceil(max_segments / WAVES), P)
+__global__ void __launch_bounds__(WAVES * 64)
+select_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, const int32_t *seg_budget,
+              const int32_t *block_size, const int32_t *prefix, int budget, int32_t *idx_out)
+{
+    __shared__ double sh_phi[WAVES][CAPB];
+    __shared__ uint8_t sh_cls[WAVES][CAPB];
+    const int p = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = blockIdx.x * WAVES + wave;
+    const int seq = seq_of_problem(d, p);
+    const int sbase = sv.seq_ptr[seq];
+    const int K = sv.seq_ptr[seq + 1] - sbase - 1;
+    if (k >= K) return;
+    const int64_t o = (int64_t)p * sv.max_segments + k;
+    const int a = sv.seg_off[sbase + k], b = sv.seg_off[sbase + k + 1];
+    const int bk = min(seg_budget[o], b - a);
+    int g = block_size[o];
+    if (bk <= 0 || g <= 0) return;
+    g = min(min(g, MAX_G), bk);
+    const float *sp = s_tilde + (int64_t)p * d.T;
+    int32_t *out = idx_out + (int64_t)p * budget;
+    int pos = prefix[o];
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    auto put = [&](int c0, unsigned long long m, float) {
+        const int j = pos + __popcll(m & lt);
+        if (((m >> lane) & 1ull) && j < budget) out[j] = c0 + lane;
+        pos += __popcll(m);
+    };
+    if (g == 1) {
+        // T_k(1) = T_topB & S_k whenever b_k is the implicit budget; otherwise rank the tokens
+        const uint32_t thr_key = (uint32_t)thr[2 * p];
+        const int thr_cut = thr[2 * p + 1];
+        int cnt = 0;
+        for (int c0 = a; c0 < b; c0 += 64) {
+            const int t = c0 + lane;
+            cnt += (t < b && in_topb(sp[t], t, thr_key, thr_cut)) ? 1 : 0;
+        }
+        if (wave_sum_i(cnt) == bk) {
+            for (int c0 = a; c0 < b; c0 += 64) {
+                const int t = c0 + lane;
+                put(c0, __ballot(t < b && in_topb(sp[t], t, thr_key, thr_cut)), 0.f);
+            }
+            return;
+        }
+    }
+    WaveScratch ws{sh_phi[wave], sh_cls[wave]};
+    segment_fill(sp, a, b, g, bk, ws, put);
+}
+
+}  // namespace
+
+hipError_t launch_topb(const Dims &d, const float *s_tilde, int32_t budget, int32_t *thr, hipStream_t st)
+{
+    if (d.P <= 0) return hipSuccess;
+    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr);
+    return hipGetLastError();
+}
+
+hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
+                         float tau, const int32_t *thr, int32_t *seg_budget, int32_t *block_size,
+                         hipStream_t st)
+{
+    if (d.P <= 0 || sv.max_segments <= 0) return hipSuccess;
+    dim3 grid((sv.max_segments + WAVES - 1) / WAVES, d.P);
+    hipLaunchKernelGGL(search_kernel, grid, dim3(WAVES * 64), 0, st, d, s_tilde, sv, cand, tau, thr,
+                       seg_budget, block_size);
+    return hipGetLastError();
+}
+
+size_t select_ws_bytes(const Dims &d, int32_t max_segments)
+{
+    return align256((size_t)d.P * 2 * 4) + align256((size_t)d.P * (size_t)(max_segments > 0 ? max_segments : 1) * 4);
+}
+
+hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv, const int32_t *seg_budget,
+                         const int32_t *block_size, int32_t budget, int32_t *idx_out, int32_t *n_sel_out,
+                         void *ws, hipStream_t st)
+{
+    if (d.P <= 0) return hipSuccess;
+    int32_t *thr = static_cast<int32_t *>(ws);
+    int32_t *prefix = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + align256((size_t)d.P * 2 * 4));
+    hipError_t e = launch_topb(d, s_tilde, budget, thr, st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(seg_prefix_kernel, dim3(d.P), dim3(256), 0, st, d, sv, seg_budget, budget, prefix,
+                       idx_out, n_sel_out);
+    if (sv.max_segments > 0 && budget > 0) {
+        dim3 grid((sv.max_segments + WAVES - 1) / WAVES, d.P);
+        hipLaunchKernelGGL(select_kernel, grid, dim3(WAVES * 64), 0, st, d, s_tilde, sv, thr, seg_budget,
+                           block_size, prefix, budget, idx_out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace sablock

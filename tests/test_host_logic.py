@@ -1,0 +1,133 @@
+"""CPU-side checks of the HIP library: it loads, exports what the header declares,
+and rejects bad host arguments before anything is enqueued (no GPU needed)."""
+
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2510_22556_amd import binding as B
+from paper_2510_22556_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2510_22556_amd.build import build
+        build()
+    return B.load()
+
+
+def _shape(**kw):
+    s = B.CShape()
+    s.n_seq, s.n_layers, s.n_q_heads, s.n_kv_heads = 1, 1, 4, 2
+    s.head_dim, s.seq_len, s.window, s.dtype = 64, 2048, 16, B.SABLOCK_F32
+    for a, (qv, kv) in enumerate([(4 * 16 * 64, 2 * 2048 * 64), (4 * 16 * 64, 2 * 2048 * 64), (16 * 64, 2048 * 64), (64, 64)]):
+        s.q_stride[a], s.k_stride[a], s.v_stride[a] = qv, kv, kv
+    for k, v in kw.items():
+        setattr(s, k, v)
+    return s
+
+
+def test_exports_match_header(lib):
+    hdr = open(os.path.join(ROOT, "include", "sablock.h")).read()
+    declared = re.findall(r"SABLOCK_API\s+[\w\s\*]+?\b(sablock_\w+)\s*\(", hdr)
+    assert sorted(declared) == sorted(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.sablock_version().decode().startswith("sablock")
+
+
+def test_struct_layout_matches_header():
+    # 8 int32 then 3 x 4 int64, no padding surprises
+    assert ctypes.sizeof(B.CShape) == 8 * 4 + 12 * 8
+    assert B.CShape.q_stride.offset == 32 and B.CShape.v_stride.offset == 96
+    assert ctypes.sizeof(B.CHparams) == 16
+
+
+def test_workspace_bytes_and_shape_validation(lib):
+    n = B.sablock_workspace_bytes(_shape(), 100, 112)
+    assert n > 0 and n % 256 == 0
+    for bad, status in [(dict(n_q_heads=3), 1), (dict(window=2048), 1), (dict(window=0), 1), (dict(dtype=7), 1),
+                        (dict(head_dim=60), 2), (dict(head_dim=512), 2), (dict(window=65), 2), (dict(n_seq=0), 1)]:
+        with pytest.raises(B.SablockError) as ei:
+            B.sablock_workspace_bytes(_shape(**bad), 100, 112)
+        assert ei.value.status == status, bad
+    with pytest.raises(B.SablockError):
+        B.sablock_workspace_bytes(_shape(), -1, 10)
+
+
+def test_calls_reject_bad_host_arguments_before_launch(lib):
+    s = _shape()
+    sp = ctypes.byref(s)
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    ptr2 = (ctypes.c_int32 * 2)(0, 5)
+    cand_bad = (ctypes.c_int32 * 3)(2, 4, 8)
+    cand_ok = (ctypes.c_int32 * 3)(1, 2, 4)
+    cand_desc = (ctypes.c_int32 * 3)(1, 4, 2)
+    hp = B.CHparams(1e-6, 0.9, 1.0, 0.85)
+    assert lib.sablock_score(sp, None, fake, None, 1e-6, fake, fake, fake, 1 << 30, None) == 1
+    assert lib.sablock_score(sp, fake, fake, None, 1e-6, fake, fake, fake, 16, None) == 3       # workspace too small
+    assert b"workspace" in lib.sablock_last_error()
+    assert lib.sablock_score(sp, ctypes.c_void_p(0x1004), fake, None, 1e-6, fake, fake, fake, 1 << 30, None) == 1
+    assert lib.sablock_refine(sp, fake, fake, fake, None, 4, ctypes.byref(hp), fake, None, fake, 0, None) == 1
+    assert lib.sablock_refine(sp, fake, fake, fake, ptr2, 2, ctypes.byref(hp), fake, None, fake, 0, None) == 1  # 4 segs > 2
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_bad, 3, 10, 0.85, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_desc, 3, 10, 0.85, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 3, -1, 0.85, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 0, 10, 0.85, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 3, 10, 0.85, fake, fake, fake, 0, None) == 3
+    big = (ctypes.c_int32 * 2)(1, 128)
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, big, 2, 10, 0.85, fake, fake, fake, 1 << 20, None) == 2
+    assert lib.sablock_select(sp, fake, fake, ptr2, 4, fake, fake, -5, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.sablock_select(sp, fake, fake, ptr2, 4, fake, fake, 5, fake, fake, fake, 8, None) == 3
+    assert lib.sablock_compact(sp, fake, None, fake, fake, 8, 1, fake, fake, None) == 1
+    assert lib.sablock_compact(sp, fake, fake, fake, fake, -8, 1, fake, fake, None) == 1
+    assert lib.sablock_score(None, fake, fake, None, 1e-6, fake, fake, fake, 0, None) == 1
+
+
+def test_binding_refuses_missing_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        B.load()
+
+
+def test_synth_backends_agree_and_recipes_hold():
+    import torch
+
+    a = synth.hash_u64(77, synth.STREAM_K, 5, 4096)
+    b = synth.hash_i64_torch(77, synth.STREAM_K, 5, 4096, "cpu").numpy().view(np.uint64)
+    assert (a == b).all()
+    x = synth.normal_f32(3, synth.STREAM_Q, (256, 128))
+    y = synth.normal_torch(3, synth.STREAM_Q, (256, 128), "cpu").numpy()
+    np.testing.assert_allclose(x, y, rtol=1e-6, atol=1e-7)
+    assert abs(x.mean()) < 0.02 and abs(x.std() - 1) < 0.02
+    bits = synth.f32_to_bf16_bits(x)
+    assert (torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16) == bits).all()
+    np.testing.assert_array_equal(synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(bits)), bits)
+    for w in synth.WORKLOADS.values():
+        off, ptr = synth.workload_segments(w)
+        assert len(ptr) == w.n_seq + 1
+        for s in range(w.n_seq):
+            o = off[ptr[s]:ptr[s + 1]]
+            assert o[0] == 0 and o[-1] == w.T and (np.diff(o) >= 1).all()
+            mean = w.seg_means[s % len(w.seg_means)]
+            assert 0.7 * mean < np.diff(o).mean() < 1.3 * mean
+            if w.seg_max:
+                assert np.diff(o).max() <= w.seg_max + w.seg_min
+        assert w.budget() + w.window == w.cache_budgets[0]
+
+
+def test_paper_defaults_in_workloads():
+    vals = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "hyperparameters.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, *v = line.split()
+            vals[k] = v
+    w = synth.WORKLOADS["llama8b_128k"]
+    assert (w.eps, w.alpha, w.eta, w.tau) == tuple(float(vals[k][0]) for k in ("eps", "alpha", "eta", "tau"))
