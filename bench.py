@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the SABlock compression hot path on one MI355X.
+
+A step is one pass of the whole path (score, refine, search_blocks, select,
+compact: five C-ABI calls) over every layer of one synthetic workload whose
+Q/K/V already sit in HBM.  Prints ONE JSON line:
+  value     tokens/s per layer = n_seq * L * n_layers / step time
+  roofline  the scoring step (the kernels that stream K): algorithmic bytes per
+            step / their HIP-event time per step, against the 8 TB/s HBM peak
+  cpu_baseline  the fp64 oracle timed on the host on a bounded sample
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+# HBM traffic of the scoring kernels per step from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (bytes; see profiles/); None until measured for the workload.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_bytes(w, budget, append_window=True):
+    """Bytes the method must move per step (all layers), per stage."""
+    elt = 4 if w.dtype == "f32" else 2
+    n, nl, Hkv, Hq, L, T, W, D = w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.seq_len, w.T, w.window, w.head_dim
+    P = n * nl * Hkv
+    rows = budget + (W if append_window else 0)
+    return {
+        "score": P * L * D * elt + n * nl * Hq * W * D * elt + 2 * 4 * P * L,
+        "refine": 3 * 4 * P * T,
+        "search": 4 * P * T,
+        "select": 4 * P * budget,
+        "compact": 2 * 2 * P * rows * D * elt,
+    }
+
+
+def cpu_baseline(w, q, k, v, off, ptr, budget, n_layers_sample, threads):
+    """Time the fp64 oracle (all five steps) on `n_layers_sample` layers of sequence 0."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+
+    import oracle
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import gpu_helpers as H
+
+    oracle.build()
+    so = off[ptr[0]:ptr[1]]
+    jobs = []
+    for layer in range(n_layers_sample):
+        for h in range(w.n_kv_heads):
+            qr = H.widen(H.to_np(q[0, layer, h * w.G:(h + 1) * w.G]))
+            kraw, vraw = H.to_np(k[0, layer, h]), H.to_np(v[0, layer, h])
+            jobs.append((qr, H.widen(kraw), kraw, vraw))
+
+    def one(job):
+        qr, kd, kraw, vraw = job
+        return oracle.pipeline_head(qr, kd, None, so, w.cand, budget, w.eps, w.alpha, w.eta, w.tau,
+                                    k_raw=kraw, v_raw=vraw)["n_sel"]
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(one, jobs))
+    dt = time.perf_counter() - t0
+    return {
+        "value": w.seq_len * n_layers_sample / dt,
+        "unit": "tokens/s per layer",
+        "cores": min(threads, len(jobs)),
+        "kind": "oracle",
+        "sample": f"{n_layers_sample} of {w.n_layers} layers of sequence 0 ({len(jobs)} KV-head problems, "
+                  f"full L={w.seq_len}), all five steps, {dt:.2f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b_128k")
+    ap.add_argument("--budget-index", type=int, default=0)
+    ap.add_argument("--cpu-layers", type=int, default=1, help="layers of the oracle sample (0: skip)")
+    ap.add_argument("--cpu-threads", type=int, default=8)
+    ap.add_argument("--row-lse", action="store_true", help="also time the variant that is handed the rows' log-sum-exp")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_22556_amd import binding as B
+    from paper_2510_22556_amd import synth
+
+    B.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    budget = w.budget(args.budget_index)
+    q, k, v = synth.device_tensors(w, dev)
+    off, ptr = synth.workload_segments(w)
+    shape = B.make_shape(q, k, v)
+    seg = B.make_segments(off, ptr, dev)
+    buf = B.Buffers(shape, seg, budget, dev, append_window=True)
+    torch.cuda.synchronize()
+
+    hp = dict(eps=w.eps, alpha=w.alpha, eta=w.eta, tau=w.tau)
+    names = ["score", "refine", "search", "select", "compact"]
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, w.eps)
+        mark(1)
+        B.sablock_refine(shape, buf.s, buf.ent, seg, buf.s_tilde, buf.ws, w.alpha, w.eta, buf.omega)
+        mark(2)
+        B.sablock_search_blocks(shape, buf.s_tilde, seg, w.cand, budget, w.tau, buf.seg_budget, buf.block_size, buf.ws)
+        mark(3)
+        B.sablock_select(shape, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws)
+        mark(4)
+        B.sablock_compact(shape, k, v, buf.idx, buf.n_sel, budget, True, buf.k_out, buf.v_out)
+        mark(5)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    stage_ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, n in enumerate(names)}
+
+    alg = algorithmic_bytes(w, budget)
+    score_gbs = alg["score"] / (stage_ms["score"] * 1e-3) / 1e9
+    result = {
+        "metric": "compressed context tokens/sec per layer (score+select+compact); % HBM roofline",
+        "value": w.n_seq * w.seq_len * w.n_layers / (dt / args.steps),
+        "unit": "tokens/s per layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.dtype == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "n_seq": w.n_seq, "n_layers": w.n_layers, "seq_len": w.seq_len,
+                   "window": w.window, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "cand": list(w.cand), "cache_budget": w.cache_budgets[args.budget_index],
+                   "budget_B": budget, "segments": int(seg.max_segments)},
+        "end_to_end": {"algorithmic_GB": sum(alg.values()) / 1e9,
+                       "GBps": sum(alg.values()) / (dt / args.steps) / 1e9,
+                       "frac_hbm_peak": sum(alg.values()) / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
+        "stages_ms": stage_ms,
+        "roofline": {"kernel": "sablock_score (all kernels of the scoring step: row statistics + column pass)",
+                     "bound": "hbm", "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": score_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),
+                     "algorithmic_bytes": alg["score"], "ms": stage_ms["score"]},
+    }
+    if args.row_lse:
+        # scoring handed the rows' log-sum-exp (single pass over K); lse taken from a first run's statistics
+        # is not available through the ABI, so time the kernel on arbitrary finite lse values
+        lse = torch.zeros((w.n_seq, w.n_layers, w.n_q_heads, w.window), dtype=torch.float32, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, w.eps, row_lse=lse)
+        e0.record()
+        for _ in range(args.steps):
+            B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, w.eps, row_lse=lse)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        result["score_with_row_lse"] = {"ms": ms, "GBps": alg["score"] / (ms * 1e-3) / 1e9,
+                                        "frac": alg["score"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    if args.cpu_layers > 0:
+        result["cpu_baseline"] = cpu_baseline(w, q, k, v, off, ptr, budget, min(args.cpu_layers, w.n_layers),
+                                              args.cpu_threads)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

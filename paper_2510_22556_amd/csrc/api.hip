@@ -123,7 +123,7 @@ sablock_status sablock_score(const sablock_shape *shape, const void *q_win, cons
     if (!aligned16(q_win) || !aligned16(k)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score: Q/K must be 16-byte aligned");
     if (!(eps >= 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score: eps must be >= 0");
     const bool mfma = score_mfma_supported(d);
-    const size_t need = row_lse && !mfma ? 0 : (mfma ? score_mfma_ws_bytes(d) : score_generic_ws_bytes(d));
+    const size_t need = row_lse ? 0 : (mfma ? score_mfma_ws_bytes(d) : score_generic_ws_bytes(d));
     if (need && (!ws || ws_bytes < need))
         return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_score: workspace %zu < %zu bytes", ws_bytes, need);
     hipStream_t hs = static_cast<hipStream_t>(stream);

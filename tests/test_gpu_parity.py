@@ -230,3 +230,41 @@ def test_row_lse_input_equals_internal_pass(oracle, torch_cuda):
     torch.cuda.synchronize()
     np.testing.assert_allclose(H.to_np(buf.s), s0, rtol=2e-5, atol=1e-9)
     np.testing.assert_allclose(H.to_np(buf.ent), e0, rtol=2e-5, atol=1e-6)
+
+
+def test_mfma_score_long_ragged_with_heavy_rows(oracle, torch_cuda):
+    # the MFMA shape (bf16, D 128, G 4, W 32) at a length that is no multiple of the tile, long enough
+    # for many subtiles per wavefront, with key rows scaled up so that row references move (rescale path)
+    # and K given as a strided view (token stride 2*D)
+    torch = torch_cuda
+    L, W, D, G, Hkv = 131072 + 77, 32, 128, 4, 2
+    T = L - W
+    q = synth.normal_torch(4242, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
+    kbig = synth.normal_torch(4242, 2, (1, 1, Hkv, L, 2 * D), "cuda", torch.bfloat16)
+    k = kbig[..., :D]
+    v = synth.normal_torch(4242, 3, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    heavy = torch.as_tensor(np.random.default_rng(0).choice(T, size=48, replace=False)).cuda()
+    k[0, 0, :, heavy, :] *= 12.0
+    k[0, 0, :, L - 5, :] *= 8.0                      # a heavy key inside the observation window
+    off = synth.segment_offsets(99, T, mean=64.0, min_len=2, max_len=512)
+    w = synth.Workload("long", 0, 1, 1, G * Hkv, Hkv, D, L, W, "bf16", (1, 2, 4, 8, 16, 32, 64), (1024,), (64.0,))
+    run = H.GpuRun(q, k, v, off, [0, len(off)], w.cand, w.budget())
+    assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
+    _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
+
+
+def test_mfma_score_many_problems_and_groups(oracle, torch_cuda):
+    # several launch groups (P = 24 problems of 5000 keys), ragged tail, two sequences with their own segments
+    torch = torch_cuda
+    L, W, D, G, Hkv, nl, ns = 5000, 32, 128, 4, 4, 3, 2
+    T = L - W
+    q = synth.normal_torch(777, 1, (ns, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(777, 2, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(777, 3, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    o0 = synth.segment_offsets(1, T, mean=20.0, min_len=1, max_len=100)
+    o1 = synth.segment_offsets(2, T, mean=120.0, min_len=1, max_len=1500)
+    off, ptr = np.concatenate([o0, o1]), [0, len(o0), len(o0) + len(o1)]
+    w = synth.Workload("many", 0, ns, nl, G * Hkv, Hkv, D, L, W, "bf16", (1, 2, 4, 8, 16, 32), (600,), (20.0, 120.0))
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget())
+    _check_all(oracle, w, run, q, k, v, off, ptr, [0, 5, 11, 12, 17, 23])
+    assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)        # all 24 problems
