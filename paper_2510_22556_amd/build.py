@@ -16,7 +16,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 SOURCES = ["api.hip", "score_generic.hip", "score_mfma.hip", "refine.hip", "search_select.hip", "compact.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
          # keep packed fp32 instructions out of the generated code
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA results and C operands in ordinary VGPRs (A/B operands may still sit in accumulation registers)
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 
 
 def _compile(src: str, force: bool) -> str:

@@ -1,7 +1,7 @@
 // MFMA window scoring (Sec. 3.2, Eqs. barA, st, Dk) for bf16, D = 128, G = 4, W = 32.
 //
-// The 128 window-query rows of a KV head (4 query heads x 32 window queries)
-// stay in registers as MFMA A operands; keys are the B operand, 32 per
+// The window-query rows of a KV head (4 query heads x 32 window queries) stay in
+// accumulation registers as MFMA A operands; keys are the B operand, 32 per
 // wavefront iteration ("subtile"), so in the 32x32 accumulator layout a lane
 // owns ONE key column and 16 of the 32 queries of each head:
 //   * the head mean (Eq. barA) is an in-lane add over the four accumulators,
@@ -10,15 +10,19 @@
 //   * the per-row softmax statistics are kept per lane and only reduced across
 //     lanes once per workgroup.
 // Each wavefront streams its own keys: global -> LDS with direct-to-LDS loads
-// (16 bytes per lane, fully coalesced 256-byte key rows) into a private
-// four-deep ring, LDS -> registers with an XOR swizzle so the 16-byte reads of 32
-// different key rows do not collide on banks.  No workgroup barrier in the loop.
+// (16 bytes per lane, fully coalesced 256-byte key rows) into a private ring,
+// LDS -> registers with an XOR swizzle so the 16-byte reads of 32 different key
+// rows do not collide on banks.  No workgroup barrier in the loops.
 //
 // Softmax over all keys needs each row's log-sum-exp before any column is
 // final, so scoring is two kernels unless the caller supplies row_lse:
-//   pass 1  row statistics (running reference, sum of exp2) per key chunk,
-//   combine chunk partials -> natural-log lse per row,
-//   pass 2  probabilities, head mean, column sum, entropy term.
+//   pass 1  (8 wavefronts, two per SIMD, each two query heads x its own keys)
+//           per-lane running reference and sum of exp2 per row; the reference
+//           enters the MFMA as its C operand, so the exponent is one multiply;
+//   pass 2  (4 wavefronts, all four heads each) the chunk partials are combined
+//           into the row log-sum-exp in the prologue and fed as the MFMA C
+//           operand; accumulators are double-buffered so the MFMAs of the next
+//           subtile overlap the exp/log work of the current one.
 // Problems are processed in groups whose keys fit the memory-side cache, so the
 // second read of K is served from it rather than from HBM.
 #include "sablock_internal.h"
@@ -34,13 +38,15 @@ typedef const void __attribute__((address_space(1))) *gptr_t;
 typedef void __attribute__((address_space(3))) *lptr_t;
 
 constexpr int SUB = 32;                    // keys per wavefront iteration
-constexpr int NBUF = 4;                    // ring depth (subtiles) per wavefront
-constexpr int WAVES = 4;
 constexpr int ROW_BYTES = 256;             // D = 128 bf16
 constexpr int BUF_BYTES = SUB * ROW_BYTES; // 8 KiB
-constexpr int RING_BYTES = NBUF * BUF_BYTES;
 constexpr int M_ROWS = 128;
-constexpr int LDS_BYTES = WAVES * RING_BYTES + WAVES * M_ROWS * 2 * 4;
+constexpr int STREAMS = 4;                 // key streams per workgroup (subtile u of the chunk goes to stream u % 4)
+constexpr int STRIDE = STREAMS * SUB;      // keys between consecutive subtiles of one stream
+
+constexpr int P1_LDS = 4 * 4 * BUF_BYTES + 4 * M_ROWS * 2 * 4 + 4 * M_ROWS * 4;   // rings + cross-wave reduction + row references
+constexpr int P2_LDS = 4 * 4 * BUF_BYTES + M_ROWS * 4 + 256 * 2 * 4;   // four rings + the rows' log-sum-exp + combine scratch
+
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float RESCALE_AT = 64.f;         // pass 1 moves a row's reference when an exponent exceeds this
@@ -49,89 +55,68 @@ struct ScoreArgs {
     Dims d;
     const uint16_t *q, *k;
     int p0;                // first problem of the group
-    int chunk_len;         // keys per workgroup, multiple of WAVES * SUB
+    int chunk_len;         // keys per workgroup, multiple of STRIDE
     int n_chunks;          // workgroups per problem
     float c1;              // log2(e) / sqrt(D)
     float eps;
-    float *partial;        // pass 1 out: [group problem][chunk][128][2] (reference, sum) in the log2 domain
-    const float *lse;      // pass 2 in: [P][128] natural-log sum-exp per row
+    float *partial;        // pass 1 out / pass 2 in: [group problem][chunk][128][2] (reference, sum), log2 domain
+    const float *lse;      // pass 2 in, optional: [P][128] natural-log sum-exp per row (NULL: use partial)
     float *s_out, *e_out;  // pass 2 out: [P][L]
 };
 
-__device__ inline uint32_t lds_addr(const void *p)
+__device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)(lptr_t)p; }
+
+// window query owned by accumulator register i in lane half hf
+__device__ __forceinline__ int query_of(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
+
+// Direct-to-LDS load of 32 key rows starting at t0: 8 instructions of 1 KiB (4 rows each); LDS slot
+// (row, pos) receives 16-byte chunk pos ^ (row & 15) of the row.  The address is a wave-uniform 64-bit base
+// (scalar registers) plus a per-lane 32-bit byte offset; M0 carries the LDS destination of each 1 KiB group.
+__device__ __forceinline__ void dma_1k(uint32_t voff, const char *sbase, uint32_t lds_dst)
 {
-    return (uint32_t)(uintptr_t)(lptr_t)p;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sbase), "s"(lds_dst) : "memory", "m0");
 }
 
-// Window-query rows as A operands: qa[h][s] = Q[h][lane % 32][(2s + lane/32) * 8 .. +8]
-__device__ inline void load_q(const Dims &d, const uint16_t *q, int p, int lane, bf16x8 qa[4][8])
+// subtile entirely inside [0, L): one of four precomputed lane offsets
+//   lane_off[j & 3] = (lane / 16) * row_bytes + (((lane & 15) ^ (lane / 16) ^ 4 (j & 3)) << 4),
+// so issuing costs no vector ALU work
+__device__ __forceinline__ void issue_subtile_fast(const char *base, int64_t row_bytes, const uint32_t (&lane_off)[4], uint32_t buf_lds)
 {
-    const int iq = lane & 31, hf = lane >> 5;
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
-        const uint16_t *row = q + q_row_offset(d, p, h, iq);
-#pragma unroll
-        for (int s = 0; s < 8; ++s) qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
-    }
+    for (int j = 0; j < 8; ++j) dma_1k(lane_off[j & 3], base + (int64_t)(4 * j) * row_bytes, buf_lds + j * 1024);
 }
 
-// Direct-to-LDS load of 32 key rows starting at t0 (rows past L-1 are clamped): 8 instructions of
-// 1 KiB; LDS slot (row, pos) receives 16-byte chunk pos ^ (row & 15) of the row.
-__device__ inline void issue_subtile(const uint16_t *kp, int64_t ks3, int t0, int L, char *buf, int lane)
+// subtile that crosses L: rows past L-1 read row L-1 instead (their results are masked later); t0 < L
+__device__ __forceinline__ void issue_subtile_clamped(const char *base, int64_t row_bytes, int rows_valid, uint32_t buf_lds, int lane)
 {
     const int r4 = lane >> 4, pos = lane & 15;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int row = 4 * j + r4;
-        const int t = min(t0 + row, L - 1);
-        const uint16_t *g = kp + (int64_t)t * ks3 + ((pos ^ (row & 15)) << 3);
-        __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(buf + j * 1024), 16, 0, 0);
+        const uint32_t voff = (uint32_t)min(row, rows_valid - 1) * (uint32_t)row_bytes + (uint32_t)(((pos ^ row) & 15) << 4);
+        dma_1k(voff, base, buf_lds + j * 1024);
     }
 }
 
-// B operands of one subtile: kb[s] = K[key lane % 32][(2s + lane/32) * 8 .. +8]
-__device__ inline void read_subtile(uint32_t buf_addr, const uint32_t xoff[8], bf16x8 kb[8])
+// wait until this wavefront's direct-to-LDS loads issued before the last `subtiles_after` subtiles have landed
+// (8 loads per subtile; later stores only make the wait longer, never shorter)
+__device__ __forceinline__ void wait_loads(int subtiles_after)
 {
-#pragma unroll
-    for (int s = 0; s < 8; ++s)
-        asm volatile("ds_read_b128 %0, %1" : "=v"(kb[s]) : "v"(buf_addr + xoff[s]) : "memory");
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(kb[0]), "+v"(kb[1]), "+v"(kb[2]), "+v"(kb[3]), "+v"(kb[4]), "+v"(kb[5]), "+v"(kb[6]), "+v"(kb[7])
-                 :
-                 : "memory");
-}
-
-// wait until at most `loads_after` of this wavefront's vector-memory operations are outstanding
-__device__ inline void wait_loads(int subtiles_after)
-{
-    if (subtiles_after >= 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    if (subtiles_after >= 3) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+    else if (subtiles_after == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     else if (subtiles_after == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-__device__ inline void qk_tile(const bf16x8 qa[4][8], const bf16x8 kb[8], floatx16 acc[4])
-{
-#pragma unroll
-    for (int h = 0; h < 4; ++h)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[h][i] = 0.f;
-#pragma unroll
-    for (int s = 0; s < 8; ++s)
-#pragma unroll
-        for (int h = 0; h < 4; ++h) acc[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[h][s], kb[s], acc[h], 0, 0, 0);
-}
-
-// window query owned by accumulator register i in lane half hf
-__device__ inline int query_of(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
-
 struct WaveWork {
     const uint16_t *kp;    // keys of the problem
     int p, pl, chunk;
-    int first, n_sub;      // this wavefront's subtiles: keys [first + u * WAVES * SUB, +SUB), u < n_sub
+    int first, n_sub;      // this stream's subtiles: keys [first + u * STRIDE, +SUB), u < n_sub
 };
 
-__device__ inline WaveWork wave_work(const ScoreArgs &a, int wave)
+__device__ __forceinline__ WaveWork wave_work(const ScoreArgs &a, int stream)
 {
+    stream = __builtin_amdgcn_readfirstlane(stream);         // wave-uniform: addresses below stay in scalar registers
     WaveWork w;
     w.pl = blockIdx.x / a.n_chunks;
     w.chunk = blockIdx.x - w.pl * a.n_chunks;
@@ -139,233 +124,402 @@ __device__ inline WaveWork wave_work(const ScoreArgs &a, int wave)
     w.kp = a.k + k_problem_offset(a.d, w.p);
     const int lo = w.chunk * a.chunk_len;
     const int hi = min(lo + a.chunk_len, a.d.L);
-    w.first = lo + wave * SUB;
+    w.first = lo + stream * SUB;
     const int span = hi - w.first;
-    w.n_sub = span > 0 ? (span + WAVES * SUB - 1) / (WAVES * SUB) : 0;
+    w.n_sub = span > 0 ? (span + STRIDE - 1) / STRIDE : 0;
     return w;
 }
 
+// ------------------------------------------------------------------ shared pieces of both passes
+// B operands of one subtile into accumulation registers: kb[s] = K[key lane % 32][(2s + lane/32) * 8 .. +8].
+// lane_addr = buffer address + row * 256 + ((hf ^ (row & 15)) << 4); chunk 2s+hf sits at that address ^ (s << 5).
+__device__ __forceinline__ void read_subtile_acc(uint32_t lane_addr, bf16x8 (&kb)[8])
+{
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+        asm volatile("ds_read_b128 %0, %1" : "=a"(kb[s]) : "v"(lane_addr ^ (uint32_t)(s << 5)) : "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+a"(kb[0]), "+a"(kb[1]), "+a"(kb[2]), "+a"(kb[3]), "+a"(kb[4]), "+a"(kb[5]), "+a"(kb[6]), "+a"(kb[7])
+                 :
+                 : "memory");
+}
+
+// k-steps [S0, S1) of one head's 32x32 tile; the first step takes `c` as its C operand
+template <int S0, int S1>
+__device__ __forceinline__ floatx16 chain(const bf16x8 (&qa)[8], const bf16x8 (&kb)[8], floatx16 c)
+{
+#pragma unroll
+    for (int s = S0; s < S1; ++s) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], kb[s], c, 0, 0, 0);
+    return c;
+}
+
+// Per-wavefront stream of subtiles through a ring of NBUF LDS buffers.  Subtile u lives in buffer u % NBUF; at
+// the top of iteration u the stream waits for subtile u, reads it into registers, and immediately re-fills the
+// same buffer with subtile u + NBUF, so NBUF subtiles (32 KiB per wavefront) are in flight or landed at any time.
+template <int NBUF>
+struct KeyStream {
+    const uint16_t *kp;
+    int64_t ks3;
+    char *ring;
+    uint32_t lane_addr0, ring_lds;
+    uint32_t lane_off[4];
+    int first, n_sub, L, lane;
+
+    __device__ __forceinline__ void init(const uint16_t *kp_, int64_t ks3_, char *ring_, int first_, int n_sub_, int L_, int lane_)
+    {
+        kp = kp_; ks3 = ks3_; ring = ring_; first = first_; n_sub = n_sub_; L = L_; lane = lane_;
+        const int n = lane & 31, hf = lane >> 5, r4 = lane >> 4, pos = lane & 15;
+        ring_lds = __builtin_amdgcn_readfirstlane(lds_addr(ring));
+        lane_addr0 = ring_lds + n * ROW_BYTES + ((hf ^ (n & 15)) << 4);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) lane_off[jj] = (uint32_t)(r4 * ks3 * 2) + (uint32_t)(((pos ^ r4 ^ (4 * jj)) & 15) << 4);
+    }
+    __device__ __forceinline__ void issue(int u) const
+    {
+        const int t0 = first + u * STRIDE;                     // wave-uniform, < L
+        const char *base = reinterpret_cast<const char *>(kp) + (int64_t)t0 * ks3 * 2;
+        const uint32_t buf_lds = ring_lds + (u % NBUF) * BUF_BYTES;
+        if (t0 + SUB <= L) issue_subtile_fast(base, ks3 * 2, lane_off, buf_lds);
+        else issue_subtile_clamped(base, ks3 * 2, L - t0, buf_lds, lane);
+    }
+    __device__ __forceinline__ void prime() const
+    {
+        for (int u = 0; u < min(NBUF, n_sub); ++u) issue(u);
+    }
+    __device__ __forceinline__ void fetch(int u, bf16x8 (&kb)[8]) const
+    {
+        wait_loads(min(NBUF - 1, n_sub - 1 - u));
+        read_subtile_acc(lane_addr0 + (u % NBUF) * BUF_BYTES, kb);
+        if (u + NBUF < n_sub) issue(u + NBUF);
+    }
+};
+
+constexpr int NBUF = 4;
+constexpr int WAVES = 4;
+constexpr int RING_BYTES = NBUF * BUF_BYTES;
+
 // ------------------------------------------------------------------ pass 1
+// Row statistics.  Every window-query row keeps, per wavefront, ONE reference shared by the 32 lanes that hold
+// the row (stored negated and divided by c1 in LDS, `cref`), and per lane the sum z of exp2(c1 * <q,k> - ref) over
+// the lane's keys.  cref is the MFMA C operand, so acc = <q,k> - ref/c1 and the exponent is c1 * acc.  A row is
+// anchored at the maximum over the wavefront's first 32 keys and re-anchored (rarely) when a later logit exceeds
+// the reference by more than RESCALE_AT, so any finite logits are handled without overflow or total underflow.
+//
+// stats_head reduces one head of one subtile; `tail` (the second half of the NEXT head's MFMAs) is issued between
+// its two halves so that the matrix pipe stays busy across the rare re-anchor branch.
+template <bool EDGE, typename Tail>
+__device__ __forceinline__ void stats_head(const floatx16 &acc, float (&z)[16], float *cref_h, float c1, bool first,
+                                           int t, int hf, int n, int T, int L, Tail &&tail)
+{
+    float dd[16];
+    float dmax = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        float v = acc[i] * c1;
+        if (EDGE && !(t < L && t <= T + query_of(i, hf))) v = -INFINITY;     // causal inside the window
+        dd[i] = v;
+        dmax = fmaxf(dmax, v);
+    }
+    if (first || __any(dmax > RESCALE_AT)) {
+        const float inv_c1 = 1.0f / c1;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float rm = dd[i];                                   // row maximum over the 32 lanes of this half
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) rm = fmaxf(rm, __shfl_xor(rm, o));
+            const bool move = first ? (rm > -INFINITY) : (rm > RESCALE_AT);
+            const float cshift = move ? rm * inv_c1 : 0.f;      // change of the C operand
+            const float shift = cshift * c1;                    // and the matching change of the exponent
+            z[i] *= __builtin_amdgcn_exp2f(-shift);
+            dd[i] -= shift;
+            if (n == 0 && move) cref_h[hf * 16 + i] -= cshift;
+        }
+    }
+    tail();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] += __builtin_amdgcn_exp2f(dd[i]);
+    // materialise the sums here: keeps the compiler from sinking this head's exponentials past the next heads
+    asm volatile("" : "+v"(z[0]), "+v"(z[1]), "+v"(z[2]), "+v"(z[3]), "+v"(z[4]), "+v"(z[5]), "+v"(z[6]), "+v"(z[7]),
+                      "+v"(z[8]), "+v"(z[9]), "+v"(z[10]), "+v"(z[11]), "+v"(z[12]), "+v"(z[13]), "+v"(z[14]), "+v"(z[15]));
+}
+
+// C operand of head h for this lane half: 16 consecutive floats
+__device__ __forceinline__ floatx16 load_cref(const float *cref, int h, int hf)
+{
+    return *reinterpret_cast<const floatx16 *>(cref + h * 32 + hf * 16);
+}
+
+// One subtile.  Head h is multiplied into acc[h & 1] while head h-1 (head 3: of the previous subtile) is
+// reduced from the other accumulator, so two accumulators serve the four heads.
+template <bool EDGE>
+__device__ __forceinline__ void stats_body(const bf16x8 (&qa)[4][8], const bf16x8 (&kb)[8], floatx16 (&acc)[2],
+                                           float *cref, float (&z)[4][16], float c1, bool first_prev, bool first_cur,
+                                           int t_prev, int t_cur, int hf, int n, int T, int L)
+{
+    // each head's C operand is read from LDS one head ahead of its use
+    floatx16 c_cur = load_cref(cref, 0, hf);
+    floatx16 c_nxt = load_cref(cref, 1, hf);
+    acc[0] = chain<0, 4>(qa[0], kb, c_cur);
+    stats_head<EDGE>(acc[1], z[3], cref + 96, c1, first_prev, t_prev, hf, n, T, L, [&] { acc[0] = chain<4, 8>(qa[0], kb, acc[0]); });
+    c_cur = load_cref(cref, 2, hf);
+    acc[1] = chain<0, 4>(qa[1], kb, c_nxt);
+    stats_head<EDGE>(acc[0], z[0], cref, c1, first_cur, t_cur, hf, n, T, L, [&] { acc[1] = chain<4, 8>(qa[1], kb, acc[1]); });
+    c_nxt = load_cref(cref, 3, hf);                          // after head 3 of the previous subtile was reduced
+    acc[0] = chain<0, 4>(qa[2], kb, c_cur);
+    stats_head<EDGE>(acc[1], z[1], cref + 32, c1, first_cur, t_cur, hf, n, T, L, [&] { acc[0] = chain<4, 8>(qa[2], kb, acc[0]); });
+    acc[1] = chain<0, 4>(qa[3], kb, c_nxt);
+    stats_head<EDGE>(acc[0], z[2], cref + 64, c1, first_cur, t_cur, hf, n, T, L, [&] { acc[1] = chain<4, 8>(qa[3], kb, acc[1]); });
+}
+
 __global__ void __launch_bounds__(WAVES * 64)
 score_mfma_stats(ScoreArgs a)
 {
-    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    extern __shared__ __attribute__((aligned(8192))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hf = lane >> 5;
     const Dims &d = a.d;
-    char *ring = lds + wave * RING_BYTES;
-    float *wg_red = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);     // [WAVES][128][2]
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    char *ring = lds + wave_u * RING_BYTES;
+    float *wg_red = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [WAVES][128][2]
+    float *cref = wg_red + WAVES * M_ROWS * 2 + wave_u * M_ROWS;               // [4 heads][2 halves][16], this wave's
     const WaveWork w = wave_work(a, wave);
 
+    KeyStream<NBUF> ks;
+    ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
+    ks.prime();
+
     bf16x8 qa[4][8];
-    load_q(d, a.q, w.p, lane, qa);
-    uint32_t xoff[8];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) xoff[s] = n * ROW_BYTES + (((2 * s + hf) ^ (n & 15)) << 4);
-    const uint32_t ring_addr = lds_addr(ring);
-
-    float r[4][16], z[4][16];
+    for (int h = 0; h < 4; ++h) {
+        const uint16_t *row = a.q + q_row_offset(d, w.p, h, n);
 #pragma unroll
-    for (int h = 0; h < 4; ++h)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { r[h][i] = -INFINITY; z[h][i] = 0.f; }
-
-    const int stride = WAVES * SUB;
-    for (int u = 0; u < min(NBUF - 1, w.n_sub); ++u)
-        issue_subtile(w.kp, d.ks[3], w.first + u * stride, d.L, ring + u * BUF_BYTES, lane);
-
-    for (int u = 0; u < w.n_sub; ++u) {
-        wait_loads(min(NBUF - 2, w.n_sub - 1 - u));
-        bf16x8 kb[8];
-        read_subtile(ring_addr + (u % NBUF) * BUF_BYTES, xoff, kb);
-        if (u + NBUF - 1 < w.n_sub)
-            issue_subtile(w.kp, d.ks[3], w.first + (u + NBUF - 1) * stride, d.L,
-                          ring + ((u + NBUF - 1) % NBUF) * BUF_BYTES, lane);
-        floatx16 acc[4];
-        qk_tile(qa, kb, acc);
-
-        const int t = w.first + u * stride + n;                // this lane's key
-        const bool edge = w.first + u * stride + SUB > d.T;    // subtile touches the window keys or the end
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            float dd[16];
-            float dmax = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float v = fmaf(acc[h][i], a.c1, -r[h][i]);
-                if (edge && !(t < d.L && t <= d.T + query_of(i, hf))) v = -INFINITY;   // causal inside the window
-                dd[i] = v;
-                dmax = fmaxf(dmax, v);
-            }
-            if (__any(dmax > RESCALE_AT)) {
-                // move the reference of the rows whose new logit is far above it (also the first visit: r = -inf)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    if (dd[i] > RESCALE_AT) {
-                        z[h][i] *= __builtin_amdgcn_exp2f(-dd[i]);
-                        r[h][i] = acc[h][i] * a.c1;
-                        dd[i] = 0.f;
-                    }
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) z[h][i] += __builtin_amdgcn_exp2f(dd[i]);
+        for (int s = 0; s < 8; ++s) {
+            qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+            asm volatile("" : "+a"(qa[h][s]));               // A operands live in accumulation registers
         }
     }
+    cref[lane] = 0.f;
+    cref[lane + 64] = 0.f;
 
-    // ---- reduce the lane-local (reference, sum) pairs: over the 32 lanes of a half through the wavefront's
-    // ring (all loads have landed: the last iteration waited for everything), then over wavefronts
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    float *scr_r = reinterpret_cast<float *>(ring);            // [128][32]
-    float *scr_z = scr_r + M_ROWS * 32;                        // [128][32]
+    floatx16 acc[2];
+    float z[4][16];
 #pragma unroll
     for (int h = 0; h < 4; ++h)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int row = h * 32 + query_of(i, hf);
-            scr_r[row * 32 + n] = r[h][i];
-            scr_z[row * 32 + n] = z[h][i];
-        }
+        for (int i = 0; i < 16; ++i) { z[h][i] = 0.f; acc[h & 1][i] = -INFINITY; }
+
+    // acc[1] = -inf makes the "previous subtile" work of the first iteration a no-op
+    for (int u = 0; u < w.n_sub; ++u) {
+        bf16x8 kb[8];
+        ks.fetch(u, kb);
+        const int t_cur = w.first + u * STRIDE + n;
+        if (w.first + u * STRIDE + SUB > d.T)
+            stats_body<true>(qa, kb, acc, cref, z, a.c1, u == 1, u == 0, t_cur - STRIDE, t_cur, hf, n, d.T, d.L);
+        else
+            stats_body<false>(qa, kb, acc, cref, z, a.c1, u == 1, u == 0, t_cur - STRIDE, t_cur, hf, n, d.T, d.L);
+    }
+    if (w.n_sub > 0)
+        stats_head<true>(acc[1], z[3], cref + 96, a.c1, w.n_sub == 1, w.first + (w.n_sub - 1) * STRIDE + n, hf, n, d.T, d.L, [] {});
+
+    // ---- per row: add the 32 lane sums (same reference) through the wavefront's ring (every load has landed),
+    // then combine the four wavefronts' (reference, sum) pairs
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    float *scr_z = reinterpret_cast<float *>(ring);            // [128 rows][32 lanes]
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) scr_z[(h * 32 + query_of(i, hf)) * 32 + n] = z[h][i];
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int rr = 0; rr < 2; ++rr) {
-        const int row = lane + 64 * rr;
-        float m = -INFINITY;
-        for (int j = 0; j < 32; ++j) m = fmaxf(m, scr_r[row * 32 + ((j + lane) & 31)]);
+        const int row = lane + 64 * rr;                         // row = h * 32 + query
         float zz = 0.f;
-        for (int j = 0; j < 32; ++j) {
-            const int c = (j + lane) & 31;
-            const float rj = scr_r[row * 32 + c];
-            if (rj != -INFINITY) zz += scr_z[row * 32 + c] * __builtin_amdgcn_exp2f(rj - m);
-        }
-        wg_red[(wave * M_ROWS + row) * 2] = m;
+        for (int j = 0; j < 32; ++j) zz += scr_z[row * 32 + ((j + lane) & 31)];
+        const int q = row & 31, hfq = (q >> 2) & 1, iq = ((q >> 3) << 2) | (q & 3);
+        wg_red[(wave * M_ROWS + row) * 2] = -cref[(row >> 5) * 32 + hfq * 16 + iq] * a.c1;   // reference, log2 domain
         wg_red[(wave * M_ROWS + row) * 2 + 1] = zz;
     }
     __syncthreads();
     if (threadIdx.x < M_ROWS) {
         const int row = threadIdx.x;
         float m = -INFINITY;
-        for (int wv = 0; wv < WAVES; ++wv) m = fmaxf(m, wg_red[(wv * M_ROWS + row) * 2]);
+        for (int wv = 0; wv < WAVES; ++wv) {
+            const float *e = wg_red + (wv * M_ROWS + row) * 2;
+            if (e[1] > 0.f) m = fmaxf(m, e[0]);
+        }
         float zz = 0.f;
         for (int wv = 0; wv < WAVES; ++wv) {
-            const float rj = wg_red[(wv * M_ROWS + row) * 2];
-            if (rj != -INFINITY) zz += wg_red[(wv * M_ROWS + row) * 2 + 1] * __builtin_amdgcn_exp2f(rj - m);
+            const float *e = wg_red + (wv * M_ROWS + row) * 2;
+            if (e[1] > 0.f) zz += e[1] * __builtin_amdgcn_exp2f(e[0] - m);
         }
-        float *o = a.partial + (((int64_t)w.pl * a.n_chunks + w.chunk) * M_ROWS + row) * 2;
+        float *o = a.partial + (((int64_t)w.p * a.n_chunks + w.chunk) * M_ROWS + row) * 2;
         o[0] = m;
         o[1] = zz;
     }
 }
 
-// chunk partials (log2 domain) -> natural-log sum-exp per row; one thread per (group problem, row)
-__global__ void score_mfma_combine(int n_rows, int n_chunks, int p0, const float *partial, float *lse)
+// ------------------------------------------------------------------ pass 2
+// acc = <q,k> - (lse2 + log2 G)/c1 per (head, query), so exp2(c1 * acc) = A / G
+template <bool EDGE, bool ASSIGN>
+__device__ __forceinline__ void columns_head(const floatx16 &acc, float (&ab)[16], float c1, int t, int hf, int T, int L)
 {
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (gid >= n_rows) return;
-    const int pl = gid / M_ROWS, row = gid - pl * M_ROWS;
-    float m = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, partial[(((int64_t)pl * n_chunks + c) * M_ROWS + row) * 2]);
-    float zz = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-        const float *o = partial + (((int64_t)pl * n_chunks + c) * M_ROWS + row) * 2;
-        if (o[0] != -INFINITY) zz += o[1] * exp2f(o[0] - m);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        float v = __builtin_amdgcn_exp2f(acc[i] * c1);
+        if (EDGE && !(t < L && t <= T + query_of(i, hf))) v = 0.f;      // causal inside the window
+        ab[i] = ASSIGN ? v : ab[i] + v;                                   // Eq. barA, accumulated over the heads
     }
-    lse[(int64_t)(p0 + pl) * M_ROWS + row] = (m + log2f(zz)) * LN2;
 }
 
-// ------------------------------------------------------------------ pass 2
+// column sum (Eq. st, lane half 0) or entropy term (inner sum of Eq. Dk, lane half 1) from the lane's 16 Abar values
+__device__ __forceinline__ float columns_finish(const float (&ab)[16], float eps, int hf)
+{
+    float s_part = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_part += ab[i];
+    const float s = s_part + __shfl_xor(s_part, 32);
+    const float inv_s = s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f;
+    float e_part = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const float ah = ab[i] * inv_s;
+        e_part = fmaf(ah, __builtin_amdgcn_logf(ah + eps), e_part);
+    }
+    const float ent = -LN2 * (e_part + __shfl_xor(e_part, 32));
+    return hf == 0 ? s : ent;
+}
+
+// One subtile: head h is multiplied into acc[h & 1] while head h-1 is exponentiated from the other accumulator;
+// returns the output value of the PREVIOUS subtile.
+template <bool EDGE>
+__device__ __forceinline__ float columns_body(const bf16x8 (&qa)[4][8], const bf16x8 (&kb)[8], const floatx16 (&cinit)[4],
+                                              floatx16 (&acc)[2], float (&ab)[16], float c1, float eps, int t_prev, int t_cur,
+                                              int hf, int T, int L)
+{
+    acc[0] = chain<0, 8>(qa[0], kb, cinit[0]);
+    columns_head<EDGE, false>(acc[1], ab, c1, t_prev, hf, T, L);       // last head of the previous subtile
+    const float prev = columns_finish(ab, eps, hf);
+    acc[1] = chain<0, 8>(qa[1], kb, cinit[1]);
+    columns_head<EDGE, true>(acc[0], ab, c1, t_cur, hf, T, L);
+    acc[0] = chain<0, 8>(qa[2], kb, cinit[2]);
+    columns_head<EDGE, false>(acc[1], ab, c1, t_cur, hf, T, L);
+    acc[1] = chain<0, 8>(qa[3], kb, cinit[3]);
+    columns_head<EDGE, false>(acc[0], ab, c1, t_cur, hf, T, L);
+    return prev;
+}
+
 __global__ void __launch_bounds__(WAVES * 64)
 score_mfma_columns(ScoreArgs a)
 {
-    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    extern __shared__ __attribute__((aligned(8192))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hf = lane >> 5;
     const Dims &d = a.d;
-    char *ring = lds + wave * RING_BYTES;
+    char *ring = lds + __builtin_amdgcn_readfirstlane(wave) * RING_BYTES;
+    float *lse2 = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [128] log2-domain lse + log2 G
+    float *comb = lse2 + M_ROWS;                                             // [256][2] combine scratch
     const WaveWork w = wave_work(a, wave);
 
+    KeyStream<NBUF> ks;
+    ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
+    ks.prime();
+
+    // row log-sum-exp: given by the caller, or combined here from the chunk partials of pass 1 (two threads per
+    // row, each folding every other chunk with an online max / rescaled sum)
+    {
+        const int row = threadIdx.x & (M_ROWS - 1), half = threadIdx.x >> 7;
+        float m = -INFINITY, zz = 0.f;
+        if (a.lse) {
+            m = a.lse[(int64_t)w.p * M_ROWS + row] * LOG2E;
+            zz = half == 0 ? 1.f : 0.f;
+        } else {
+            const float *pp = a.partial + ((int64_t)w.p * a.n_chunks * M_ROWS + row) * 2;
+#pragma unroll 4
+            for (int c = half; c < a.n_chunks; c += 2) {
+                const float2 e = *reinterpret_cast<const float2 *>(pp + (int64_t)c * M_ROWS * 2);
+                if (e.y > 0.f) {
+                    const float mn = fmaxf(m, e.x);
+                    zz = zz * __builtin_amdgcn_exp2f(m - mn) + e.y * __builtin_amdgcn_exp2f(e.x - mn);
+                    m = mn;
+                }
+            }
+        }
+        comb[threadIdx.x * 2] = m;
+        comb[threadIdx.x * 2 + 1] = zz;
+    }
+    __syncthreads();
+    if (threadIdx.x < M_ROWS) {
+        const float m0 = comb[threadIdx.x * 2], z0 = comb[threadIdx.x * 2 + 1];
+        const float m1 = comb[(threadIdx.x + M_ROWS) * 2], z1 = comb[(threadIdx.x + M_ROWS) * 2 + 1];
+        const float mn = fmaxf(m0, m1);
+        float zz = 0.f;
+        if (z0 > 0.f) zz += z0 * __builtin_amdgcn_exp2f(m0 - mn);
+        if (z1 > 0.f) zz += z1 * __builtin_amdgcn_exp2f(m1 - mn);
+        lse2[threadIdx.x] = mn + __builtin_amdgcn_logf(zz) + 2.0f;        // + log2(G): exp2 then yields A / G
+    }
+    __syncthreads();
+
     bf16x8 qa[4][8];
-    load_q(d, a.q, w.p, lane, qa);
-    uint32_t xoff[8];
+    floatx16 cinit[4], acc[2];
+    const float inv_c1 = 1.0f / a.c1;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) xoff[s] = n * ROW_BYTES + (((2 * s + hf) ^ (n & 15)) << 4);
-    const uint32_t ring_addr = lds_addr(ring);
-
-    // exponent offsets of this lane's rows: log2-domain lse plus log2(G), so that exp2 yields A / G
-    float l2[4][16];
+    for (int h = 0; h < 4; ++h) {
+        const uint16_t *row = a.q + q_row_offset(d, w.p, h, n);
 #pragma unroll
-    for (int h = 0; h < 4; ++h)
+        for (int s = 0; s < 8; ++s) {
+            qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+            asm volatile("" : "+a"(qa[h][s]));               // A operands live in accumulation registers
+        }
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-            l2[h][i] = a.lse[(int64_t)w.p * M_ROWS + h * 32 + query_of(i, hf)] * LOG2E + 2.0f;
-
+        for (int i = 0; i < 16; ++i) {
+            cinit[h][i] = -lse2[h * 32 + query_of(i, hf)] * inv_c1;
+            acc[h & 1][i] = -INFINITY;                         // makes the "previous subtile" of iteration 0 a no-op
+        }
+    }
+    float ab[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) ab[i] = 0.f;
     float *out = (hf == 0 ? a.s_out : a.e_out) + (int64_t)w.p * d.L;
-    const int stride = WAVES * SUB;
-    for (int u = 0; u < min(NBUF - 1, w.n_sub); ++u)
-        issue_subtile(w.kp, d.ks[3], w.first + u * stride, d.L, ring + u * BUF_BYTES, lane);
 
-    float pending = 0.f;          // result of the previous subtile, stored one iteration late
+    // results are stored one iteration late, at the top of the loop, so that the multiply/exponentiate
+    // section of an iteration is a single straight-line region
+    float pending = 0.f;
     int pending_t = -1;
     for (int u = 0; u < w.n_sub; ++u) {
-        wait_loads(min(NBUF - 2, w.n_sub - 1 - u));
-        bf16x8 kb[8];
-        read_subtile(ring_addr + (u % NBUF) * BUF_BYTES, xoff, kb);
         if (pending_t >= 0 && pending_t < d.L) out[pending_t] = pending;
-        if (u + NBUF - 1 < w.n_sub)
-            issue_subtile(w.kp, d.ks[3], w.first + (u + NBUF - 1) * stride, d.L,
-                          ring + ((u + NBUF - 1) % NBUF) * BUF_BYTES, lane);
-        floatx16 acc[4];
-        qk_tile(qa, kb, acc);
-
-        const int t = w.first + u * stride + n;
-        const bool edge = w.first + u * stride + SUB > d.T;
-        float ab[16];                                          // Abar of this lane's 16 queries (Eq. barA)
-        float s_part = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            float v = 0.f;
-#pragma unroll
-            for (int h = 0; h < 4; ++h) v += __builtin_amdgcn_exp2f(fmaf(acc[h][i], a.c1, -l2[h][i]));
-            if (edge && !(t < d.L && t <= d.T + query_of(i, hf))) v = 0.f;
-            ab[i] = v;
-            s_part += v;
-        }
-        const float s = s_part + __shfl_xor(s_part, 32);      // Eq. st
-        const float inv_s = s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f;
-        float e_part = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float ah = ab[i] * inv_s;
-            e_part = fmaf(ah, __builtin_amdgcn_logf(ah + a.eps), e_part);
-        }
-        const float ent = -LN2 * (e_part + __shfl_xor(e_part, 32));   // inner sum of Eq. Dk
-        pending = hf == 0 ? s : ent;
-        pending_t = t;
+        bf16x8 kb[8];
+        ks.fetch(u, kb);
+        const int t_cur = w.first + u * STRIDE + n;
+        const int t_prev = t_cur - STRIDE;
+        if (w.first + u * STRIDE + SUB > d.T)
+            pending = columns_body<true>(qa, kb, cinit, acc, ab, a.c1, a.eps, t_prev, t_cur, hf, d.T, d.L);
+        else
+            pending = columns_body<false>(qa, kb, cinit, acc, ab, a.c1, a.eps, t_prev, t_cur, hf, d.T, d.L);
+        pending_t = u > 0 ? t_prev : -1;
     }
     if (pending_t >= 0 && pending_t < d.L) out[pending_t] = pending;
+    if (w.n_sub > 0) {
+        const int t_last = w.first + (w.n_sub - 1) * STRIDE + n;
+        columns_head<true, false>(acc[1], ab, a.c1, t_last, hf, d.T, d.L);
+        const float v = columns_finish(ab, a.eps, hf);
+        if (t_last < d.L) out[t_last] = v;
+    }
 }
 
 struct Plan {
-    int group;        // problems per launch pair
-    int chunk_len;
-    int n_chunks;
+    int chunk_len;    // keys per workgroup
+    int n_chunks;     // workgroups per problem
 };
 
 Plan make_plan(const Dims &d)
 {
-    // One launch covers `group` problems with about one workgroup per CU (256 of them), all of equal
-    // length, so that no second, partial wave of workgroups trails the first.  group is a power of two.
+    // One launch per pass covers every problem.  A workgroup owns chunk_len consecutive keys of one problem;
+    // long chunks amortise its prologue (window queries into registers, first loads), but there should be at
+    // least a few workgroups per CU so that the 256 CUs stay evenly loaded.
     Plan pl;
-    const int64_t bytes_per_problem = (int64_t)d.L * ROW_BYTES;
-    int64_t cache_target = (int64_t)128 << 20;                // keys of one group: inside the memory-side cache
-    if (const char *e = getenv("SABLOCK_SCORE_GROUP_MB")) { long v = atol(e); if (v > 0) cache_target = (int64_t)v << 20; }
-    int g = 1;
-    while (g * 2 <= 256 && g * 2 <= d.P && (int64_t)g * 2 * bytes_per_problem <= cache_target) g *= 2;
-    pl.group = g;
-    const int unit = WAVES * SUB;
-    const int want_chunks = 256 / g;
-    int len = (d.L + want_chunks - 1) / want_chunks;
-    len = ((len + unit - 1) / unit) * unit;
+    int len = 8192;
+    if (const char *e = getenv("SABLOCK_SCORE_CHUNK")) { int v = atoi(e); if (v >= STRIDE) len = (v / STRIDE) * STRIDE; }
+    else while (len > STRIDE && (int64_t)d.P * ((d.L + len - 1) / len) < 1024) len /= 2;
     pl.chunk_len = len;
     pl.n_chunks = (d.L + len - 1) / len;
     return pl;
@@ -381,7 +535,7 @@ bool score_mfma_supported(const Dims &d)
 size_t score_mfma_ws_bytes(const Dims &d)
 {
     Plan pl = make_plan(d);
-    return align256((size_t)d.P * M_ROWS * 4) + align256((size_t)pl.group * pl.n_chunks * M_ROWS * 2 * 4);
+    return align256((size_t)d.P * pl.n_chunks * M_ROWS * 2 * 4);
 }
 
 hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
@@ -390,10 +544,10 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, P1_LDS);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+                                hipFuncAttributeMaxDynamicSharedMemorySize, P2_LDS);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
@@ -408,21 +562,12 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.eps = eps;
     a.s_out = s_out;
     a.e_out = ent_out;
-    float *lse_ws = static_cast<float *>(ws);
-    a.partial = ws ? reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.P * M_ROWS * 4)) : nullptr;
-    a.lse = row_lse ? row_lse : lse_ws;
-    for (int p0 = 0; p0 < d.P; p0 += pl.group) {
-        const int g = (d.P - p0 < pl.group) ? d.P - p0 : pl.group;
-        a.p0 = p0;
-        dim3 grid(g * pl.n_chunks);
-        if (!row_lse) {
-            hipLaunchKernelGGL(score_mfma_stats, grid, dim3(WAVES * 64), LDS_BYTES, st, a);
-            const int rows = g * M_ROWS;
-            hipLaunchKernelGGL(score_mfma_combine, dim3((rows + 255) / 256), dim3(256), 0, st, rows, pl.n_chunks, p0,
-                               a.partial, lse_ws);
-        }
-        hipLaunchKernelGGL(score_mfma_columns, grid, dim3(WAVES * 64), LDS_BYTES, st, a);
-    }
+    a.partial = static_cast<float *>(ws);
+    a.lse = row_lse;
+    a.p0 = 0;
+    dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
+    if (!row_lse) hipLaunchKernelGGL(score_mfma_stats, grid, dim3(WAVES * 64), P1_LDS, st, a);
+    hipLaunchKernelGGL(score_mfma_columns, grid, dim3(WAVES * 64), P2_LDS, st, a);
     return hipGetLastError();
 }
 
