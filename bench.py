@@ -23,9 +23,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
-# HBM traffic of the scoring kernels per step from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (bytes; see profiles/); None until measured for the workload.
-MEASURED_TRAFFIC = {}
+# HBM traffic of the scoring kernels per step (bytes) from two rocprofv3 --pmc runs, FETCH_SIZE then WRITE_SIZE,
+# each scaled by what the counter reads for a plain copy of known size
+# (profiles/score_mfma_llama8b_128k_hbm_traffic.md); None for workloads that were not measured.
+MEASURED_TRAFFIC = {"llama8b_128k": 17.66e9}
 
 
 def algorithmic_bytes(w, budget, append_window=True):
@@ -87,9 +88,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b_128k")
     ap.add_argument("--budget-index", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count (profiling runs only)")
     ap.add_argument("--cpu-layers", type=int, default=1, help="layers of the oracle sample (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=8)
     ap.add_argument("--row-lse", action="store_true", help="also time the variant that is handed the rows' log-sum-exp")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="first run a plain device copy of this many MiB (reference point for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -104,6 +108,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
+    if args.layers > 0:
+        import dataclasses
+        w = dataclasses.replace(w, n_layers=args.layers, name=f"{w.name}[{args.layers} layers]")
     budget = w.budget(args.budget_index)
     q, k, v = synth.device_tensors(w, dev)
     off, ptr = synth.workload_segments(w)
@@ -112,7 +119,13 @@ def main():
     buf = B.Buffers(shape, seg, budget, dev, append_window=True)
     torch.cuda.synchronize()
 
-    hp = dict(eps=w.eps, alpha=w.alpha, eta=w.eta, tau=w.tau)
+    if args.calibrate_copy > 0:
+        src = torch.empty((args.calibrate_copy << 20,), dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # elementwise copy kernel: reads and writes calibrate_copy MiB each
+        torch.cuda.synchronize()
+        del src, dst
     names = ["score", "refine", "search", "select", "compact"]
 
     def step(events=None):
