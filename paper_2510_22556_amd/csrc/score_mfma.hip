@@ -16,15 +16,16 @@
 //
 // Softmax over all keys needs each row's log-sum-exp before any column is
 // final, so scoring is two kernels unless the caller supplies row_lse:
-//   pass 1  (8 wavefronts, two per SIMD, each two query heads x its own keys)
-//           per-lane running reference and sum of exp2 per row; the reference
+//   pass 1  per row a reference (kept in LDS, shared by the 32 lanes that hold
+//           the row) and per lane the sum of exp2 relative to it; the reference
 //           enters the MFMA as its C operand, so the exponent is one multiply;
-//   pass 2  (4 wavefronts, all four heads each) the chunk partials are combined
-//           into the row log-sum-exp in the prologue and fed as the MFMA C
-//           operand; accumulators are double-buffered so the MFMAs of the next
-//           subtile overlap the exp/log work of the current one.
-// Problems are processed in groups whose keys fit the memory-side cache, so the
-// second read of K is served from it rather than from HBM.
+//   pass 2  the chunk partials are combined into the row log-sum-exp in the
+//           prologue and fed as the MFMA C operand; probabilities, head mean,
+//           column sum and entropy term follow in registers.
+// In both passes the four heads rotate through two accumulators: head h is
+// multiplied while head h-1 is exponentiated, which overlaps the matrix pipe
+// with the exp/log work inside one wavefront (one wavefront per SIMD).
+// One launch per pass covers every problem of the call.
 #include "sablock_internal.h"
 
 #include <cstdlib>
