@@ -58,14 +58,12 @@ def cpu_baseline(w, q, k, v, off, ptr, budget, n_layers_sample, threads):
     jobs = []
     for layer in range(n_layers_sample):
         for h in range(w.n_kv_heads):
-            qr = H.widen(H.to_np(q[0, layer, h * w.G:(h + 1) * w.G]))
-            kraw, vraw = H.to_np(k[0, layer, h]), H.to_np(v[0, layer, h])
-            jobs.append((qr, H.widen(kraw), kraw, vraw))
+            jobs.append((H.to_np(q[0, layer, h * w.G:(h + 1) * w.G]), H.to_np(k[0, layer, h]), H.to_np(v[0, layer, h])))
 
     def one(job):
-        qr, kd, kraw, vraw = job
-        return oracle.pipeline_head(qr, kd, None, so, w.cand, budget, w.eps, w.alpha, w.eta, w.tau,
-                                    k_raw=kraw, v_raw=vraw)["n_sel"]
+        qraw, kraw, vraw = job          # raw bits as the kernels saw them; widened to fp64 inside the timed region
+        return oracle.pipeline_head(H.widen(qraw), H.widen(kraw), None, so, w.cand, budget, w.eps, w.alpha, w.eta,
+                                    w.tau, k_raw=kraw, v_raw=vraw)["n_sel"]
 
     t0 = time.perf_counter()
     with ThreadPoolExecutor(max_workers=threads) as ex:
@@ -89,7 +87,7 @@ def main():
     ap.add_argument("--workload", default="llama8b_128k")
     ap.add_argument("--budget-index", type=int, default=0)
     ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count (profiling runs only)")
-    ap.add_argument("--cpu-layers", type=int, default=1, help="layers of the oracle sample (0: skip)")
+    ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle sample (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=8)
     ap.add_argument("--row-lse", action="store_true", help="also time the variant that is handed the rows' log-sum-exp")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",

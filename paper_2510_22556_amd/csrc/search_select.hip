@@ -19,8 +19,9 @@
 namespace sablock {
 namespace {
 
-constexpr int WAVES = 4;            // wavefronts (segments) per workgroup in search/select
-constexpr int CAPB = 1024;          // blocks per segment whose Phi/class fit the wave's LDS slice
+constexpr int WAVES = 1;            // wavefronts (segments) per workgroup in search/select: a slow segment holds no others back
+constexpr int CAPB = 512;           // blocks per segment whose Phi/class fit the wave's LDS slice
+constexpr int CAPT = 1024;          // tokens per segment whose scores are staged in the wave's LDS slice
 constexpr int MAX_G = 64;           // largest candidate block size
 
 __device__ inline int wave_sum_i(int v)
@@ -69,9 +70,16 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr)
         const int nbins = 1 << bits[pass], shift = shifts[pass];
         for (int i = tid; i < nbins; i += TB_THREADS) hist[i] = 0;
         __syncthreads();
-        for (int t = tid; t < T; t += TB_THREADS) {
-            uint32_t key = ordered_key(sp[t]);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (nbins - 1)], 1u);
+        // eight independent loads in flight per thread: the pass is latency-bound otherwise
+        for (int t0 = tid; t0 < T; t0 += 8 * TB_THREADS) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { const int t = t0 + j * TB_THREADS; v[j] = sp[t < T ? t : T - 1]; }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t key = ordered_key(v[j]);
+                if (t0 + j * TB_THREADS < T && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (nbins - 1)], 1u);
+            }
         }
         __syncthreads();
         if (wave == 0) {
@@ -131,22 +139,25 @@ struct WaveScratch {
     uint8_t *cls;       // CAPB block classes: 0 not taken, 1 taken whole, 2 cut to its best tokens
 };
 
-// Phi of block m of segment [a,b) with block size g: ascending fp64 sum
-__device__ inline double block_sum(const float *sp, int a, int b, int g, int m)
+// Phi of block m of segment [a,b) with block size g: ascending fp64 sum.  `val(t)` yields s_tilde of token t
+// (from the wave's LDS copy of the segment when it fits, else from global memory).
+template <typename V>
+__device__ inline double block_sum(V val, int a, int b, int g, int m)
 {
     const int lo = a + m * g, hi = min(lo + g, b);
     double phi = 0.0;
-    for (int t = lo; t < hi; ++t) phi += (double)sp[t];
+    for (int t = lo; t < hi; ++t) phi += (double)val(t);
     return phi;
 }
 
 // number of blocks ranked before block m
-__device__ inline int block_rank(const float *sp, int a, int b, int g, int nb, int m, double phi_m,
+template <typename V>
+__device__ inline int block_rank(V val, int a, int b, int g, int nb, int m, double phi_m,
                                  const double *phi_lds, bool fast)
 {
     int r = 0;
     for (int o = 0; o < nb; ++o) {
-        double po = fast ? phi_lds[o] : block_sum(sp, a, b, g, o);
+        double po = fast ? phi_lds[o] : block_sum(val, a, b, g, o);
         r += (po > phi_m || (po == phi_m && o < m)) ? 1 : 0;
     }
     return r;
@@ -156,8 +167,8 @@ __device__ inline int block_rank(const float *sp, int a, int b, int g, int nb, i
 // emit(c0, taken_mask, value) for each 64-token chunk in ascending order; lane l
 // of the chunk starting at token c0 holds the value of token c0 + l.
 // Requires 1 <= g <= MAX_G, g <= min(b - a, bk); all arguments wave-uniform.
-template <typename F>
-__device__ inline void segment_fill(const float *sp, int a, int b, int g, int bk, WaveScratch ws, F &&emit)
+template <typename V, typename F>
+__device__ inline void segment_fill(V val, int a, int b, int g, int bk, WaveScratch ws, F &&emit)
 {
     const int lane = threadIdx.x & 63;
     const int len = b - a;
@@ -167,7 +178,7 @@ __device__ inline void segment_fill(const float *sp, int a, int b, int g, int bk
     const int mt = nb - 1;
 
     if (fast) {
-        for (int m = lane; m < nb; m += 64) ws.phi[m] = block_sum(sp, a, b, g, m);
+        for (int m = lane; m < nb; m += 64) ws.phi[m] = block_sum(val, a, b, g, m);
         __builtin_amdgcn_wave_barrier();
     }
     // blocks taken whole: the first rstar in rank order; all blocks have g tokens except a short last one,
@@ -177,10 +188,10 @@ __device__ inline void segment_fill(const float *sp, int a, int b, int g, int bk
         rstar = min(nb, bk / g);
         nwhole = rstar * g;
     } else {
-        const double phi_t = fast ? ws.phi[mt] : block_sum(sp, a, b, g, mt);
+        const double phi_t = fast ? ws.phi[mt] : block_sum(val, a, b, g, mt);
         int cnt = 0;
         for (int o = lane; o < mt; o += 64) {
-            double po = fast ? ws.phi[o] : block_sum(sp, a, b, g, o);
+            double po = fast ? ws.phi[o] : block_sum(val, a, b, g, o);
             cnt += (po >= phi_t) ? 1 : 0;                // o < mt: an equal sum ranks first
         }
         const int q = wave_sum_i(cnt);
@@ -200,7 +211,7 @@ __device__ inline void segment_fill(const float *sp, int a, int b, int g, int bk
     int mp_local = -1;
     if (fast) {
         for (int m = lane; m < nb; m += 64) {
-            int rk = (rstar >= nb) ? 0 : block_rank(sp, a, b, g, nb, m, ws.phi[m], ws.phi, true);
+            int rk = (rstar >= nb) ? 0 : block_rank(val, a, b, g, nb, m, ws.phi[m], ws.phi, true);
             uint8_t c = (rk < rstar) ? 1 : ((rk == rstar && rem > 0) ? 2 : 0);
             ws.cls[m] = c;
             if (c == 2) mp_local = m;
@@ -208,7 +219,7 @@ __device__ inline void segment_fill(const float *sp, int a, int b, int g, int bk
         __builtin_amdgcn_wave_barrier();
     } else if (rem > 0 && rstar < nb) {
         for (int m = lane; m < nb; m += 64) {
-            int rk = block_rank(sp, a, b, g, nb, m, block_sum(sp, a, b, g, m), nullptr, false);
+            int rk = block_rank(val, a, b, g, nb, m, block_sum(val, a, b, g, m), nullptr, false);
             if (rk == rstar) mp_local = m;
         }
     }
@@ -223,10 +234,10 @@ __device__ inline void segment_fill(const float *sp, int a, int b, int g, int bk
         const int sz = phi_hi - plo;
         bool tk = false;
         if (lane < sz) {
-            const float v = sp[plo + lane];
+            const float v = val(plo + lane);
             int rk = 0;
             for (int j = 0; j < sz; ++j) {
-                float o = sp[plo + j];
+                float o = val(plo + j);
                 rk += (o > v || (o == v && j < lane)) ? 1 : 0;
             }
             tk = rk < rem;
@@ -240,13 +251,13 @@ __device__ inline void segment_fill(const float *sp, int a, int b, int g, int bk
         float v = 0.f;
         bool take = false;
         if (live) {
-            v = sp[t];
+            v = val(t);
             const int m = (t - a) / g;
             int c;
             if (fast) {
                 c = ws.cls[m];
             } else {
-                int rk = (rstar >= nb) ? 0 : block_rank(sp, a, b, g, nb, m, block_sum(sp, a, b, g, m), nullptr, false);
+                int rk = (rstar >= nb) ? 0 : block_rank(val, a, b, g, nb, m, block_sum(val, a, b, g, m), nullptr, false);
                 c = (rk < rstar) ? 1 : ((m == mp) ? 2 : 0);
             }
             take = (c == 1) || (c == 2 && ((pmask >> (t - plo)) & 1ull));
@@ -269,6 +280,7 @@ search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau
               int32_t *seg_budget, int32_t *block_size)
 {
     __shared__ double sh_phi[WAVES][CAPB];
+    __shared__ float sh_val[WAVES][CAPT];
     __shared__ uint8_t sh_cls[WAVES][CAPB];
     const int p = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -287,32 +299,44 @@ search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau
     const uint32_t thr_key = (uint32_t)thr[2 * p];
     const int thr_cut = thr[2 * p + 1];
 
-    // implicit budget b_k (Eq. implicit_budget) and token-level baseline Score_base
+    // implicit budget b_k (Eq. implicit_budget) and token-level baseline Score_base; segments that fit are
+    // copied to LDS on the way so that the candidate loop never goes back to global memory
+    const bool staged = b - a <= CAPT;
+    float *lv = sh_val[wave];
     int bk = 0;
     double base = 0.0;
     for (int c0 = a; c0 < b; c0 += 64) {
         const int t = c0 + lane;
         float v = 0.f;
         bool in = false;
-        if (t < b) { v = sp[t]; in = in_topb(v, t, thr_key, thr_cut); }
+        if (t < b) {
+            v = sp[t];
+            in = in_topb(v, t, thr_key, thr_cut);
+            if (staged) lv[t - a] = v;
+        }
         const unsigned long long m = __ballot(in);
         bk += __popcll(m);
         base = add_in_order(base, m, v);
     }
+    __builtin_amdgcn_wave_barrier();
     int gstar = 0;
     if (bk > 0) {
         const int gcap = min(b - a, bk);                    // G_k: g <= min(|S_k|, b_k, g_max)
         const double need = (double)tau * base;            // R_k(g) >= tau  <=>  Score_k(g) >= tau * Score_base
         WaveScratch ws{sh_phi[wave], sh_cls[wave]};
-        for (int c = cand.n - 1; c >= 0; --c) {
-            const int g = cand.g[c];
-            if (g > gcap) continue;
-            if (g == 1) { gstar = 1; break; }               // token level: the unconditional last resort
-            double score = 0.0;
-            segment_fill(sp, a, b, g, bk, ws,
-                         [&](int, unsigned long long m, float v) { score = add_in_order(score, m, v); });
-            if (score >= need) { gstar = g; break; }        // Eq. gk_star: first accepted, largest first
-        }
+        auto run = [&](auto val) {
+            for (int c = cand.n - 1; c >= 0; --c) {
+                const int g = cand.g[c];
+                if (g > gcap) continue;
+                if (g == 1) { gstar = 1; break; }           // token level: the unconditional last resort
+                double score = 0.0;
+                segment_fill(val, a, b, g, bk, ws,
+                             [&](int, unsigned long long m, float v) { score = add_in_order(score, m, v); });
+                if (score >= need) { gstar = g; break; }    // Eq. gk_star: first accepted, largest first
+            }
+        };
+        if (staged) run([lv, a](int t) { return lv[t - a]; });
+        else run([sp](int t) { return sp[t]; });
     }
     if (lane == 0) { seg_budget[o] = bk; block_size[o] = gstar; }
 }
@@ -354,6 +378,7 @@ select_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, cons
               const int32_t *block_size, const int32_t *prefix, int budget, int32_t *idx_out)
 {
     __shared__ double sh_phi[WAVES][CAPB];
+    __shared__ float sh_val[WAVES][CAPT];
     __shared__ uint8_t sh_cls[WAVES][CAPB];
     const int p = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -381,21 +406,36 @@ select_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, cons
         // T_k(1) = T_topB & S_k whenever b_k is the implicit budget; otherwise rank the tokens
         const uint32_t thr_key = (uint32_t)thr[2 * p];
         const int thr_cut = thr[2 * p + 1];
-        int cnt = 0;
-        for (int c0 = a; c0 < b; c0 += 64) {
-            const int t = c0 + lane;
-            cnt += (t < b && in_topb(sp[t], t, thr_key, thr_cut)) ? 1 : 0;
-        }
-        if (wave_sum_i(cnt) == bk) {
+        if (b - a <= 64) {
+            const int t = a + lane;
+            const unsigned long long m = __ballot(t < b && in_topb(sp[t < b ? t : a], t, thr_key, thr_cut));
+            if (__popcll(m) == bk) { put(a, m, 0.f); return; }
+        } else {
+            int cnt = 0;
             for (int c0 = a; c0 < b; c0 += 64) {
                 const int t = c0 + lane;
-                put(c0, __ballot(t < b && in_topb(sp[t], t, thr_key, thr_cut)), 0.f);
+                cnt += (t < b && in_topb(sp[t], t, thr_key, thr_cut)) ? 1 : 0;
             }
-            return;
+            if (wave_sum_i(cnt) == bk) {
+                for (int c0 = a; c0 < b; c0 += 64) {
+                    const int t = c0 + lane;
+                    put(c0, __ballot(t < b && in_topb(sp[t], t, thr_key, thr_cut)), 0.f);
+                }
+                return;
+            }
         }
     }
     WaveScratch ws{sh_phi[wave], sh_cls[wave]};
-    segment_fill(sp, a, b, g, bk, ws, put);
+    if (b - a <= CAPT) {
+        float *lv = sh_val[wave];
+        for (int t = a + lane; t < b; t += 64) lv[t - a] = sp[t];
+        __builtin_amdgcn_wave_barrier();
+        auto val = [lv, a](int t) { return lv[t - a]; };
+        segment_fill(val, a, b, g, bk, ws, put);
+    } else {
+        auto val = [sp](int t) { return sp[t]; };
+        segment_fill(val, a, b, g, bk, ws, put);
+    }
 }
 
 }  // namespace
