@@ -268,3 +268,54 @@ def test_mfma_score_many_problems_and_groups(oracle, torch_cuda):
     run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget())
     _check_all(oracle, w, run, q, k, v, off, ptr, [0, 5, 11, 12, 17, 23])
     assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)        # all 24 problems
+
+
+def test_llama8b_32k_heavy_hitters_three_budgets(oracle, torch_cuda):
+    # configuration 3 (two of its 32 layers): 64 key rows scaled x4 per layer, cache budgets 96 / 256 / 1024
+    import dataclasses
+
+    w = dataclasses.replace(synth.WORKLOADS["llama8b_32k_heavy"], n_layers=2)
+    q, k, v, off, ptr = _device_workload(torch_cuda, w, n_layers=2)
+    mean_g = []
+    for bi in range(3):
+        run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(bi), w.eps, w.alpha, w.eta, w.tau)
+        _check_all(oracle, w, run, q, k, v, off, ptr, [1, 8 + 6], end_to_end=(bi == 2))
+        assert (run.n_sel == w.budget(bi)).all()
+        assert run.k_out.shape[1] == w.cache_budgets[bi]
+        mean_g.append(float((run.g * run.b).sum() / run.b.sum()))
+    assert mean_g[0] <= mean_g[1] <= mean_g[2]          # larger budgets pick larger blocks (Sec. 3.3 trend)
+
+
+def test_llama8b_4x64k_window64_batched(oracle, torch_cuda):
+    # configuration 5 (one of its 32 layers): batch 4, W = 64, per-sequence segment means 16/64/256/16, B = 1984
+    import dataclasses
+
+    w = dataclasses.replace(synth.WORKLOADS["llama8b_4x64k"], n_layers=1)
+    q, k, v, off, ptr = _device_workload(torch_cuda, w, n_layers=1)
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau)
+    assert (run.n_sel == w.budget()).all()
+    assert np.allclose(run.s.sum(axis=1), w.window, rtol=1e-4)
+    _check_all(oracle, w, run, q, k, v, off, ptr, [0, 8 + 3, 16 + 5, 24 + 7], end_to_end=False)
+
+
+def test_llama8b_128k_full_size_sampled(oracle, torch_cuda):
+    # configuration 4 at full size, in the launch configuration bench.py times (32 layers folded into one call):
+    # three sampled problems against the oracle, properties that hold at any size on all 256 problems
+    torch = torch_cuda
+    w = synth.WORKLOADS["llama8b_128k"]
+    q, k, v, off, ptr = _device_workload(torch, w)
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau)
+    B_ = w.budget()
+    assert np.allclose(run.s.sum(axis=1), w.window, rtol=1e-4)                     # softmax rows sum to one
+    assert (run.n_sel == B_).all() and (run.b.sum(axis=1) == B_).all()            # |T*| = B
+    assert (np.diff(run.idx, axis=1) > 0).all() and run.idx.min() >= 0 and run.idx.max() < w.T
+    assert run.k_out.shape[1] == w.cache_budgets[0]                                # retained entries == cache budget
+    idx_t = torch.as_tensor(run.idx.astype(np.int64)).cuda()
+    for p in range(0, 256, 37):                                                    # gather is a bit copy of K[idx], V[idx]
+        kk, vv = k[0, p // 8, p % 8], v[0, p // 8, p % 8]
+        assert torch.equal(run.buf.k_out[p, :B_], kk[idx_t[p]]) and torch.equal(run.buf.v_out[p, B_:], vv[w.T:])
+        assert torch.equal(run.buf.v_out[p, :B_], vv[idx_t[p]])
+    seg_of = np.searchsorted(off, run.idx, side="right") - 1                       # blocks never leave their segment:
+    for p in (0, 100, 255):                                                        # per segment, exactly b_k tokens selected
+        assert (np.bincount(seg_of[p], minlength=len(off) - 1) == run.b[p][:len(off) - 1]).all()
+    _check_all(oracle, w, run, q, k, v, off, ptr, [3, 130, 255])
