@@ -135,9 +135,11 @@ def main():
         mark(1)
         B.sablock_refine(shape, buf.s, buf.ent, seg, buf.s_tilde, buf.ws, w.alpha, w.eta, buf.omega)
         mark(2)
-        B.sablock_search_blocks(shape, buf.s_tilde, seg, w.cand, budget, w.tau, buf.seg_budget, buf.block_size, buf.ws)
+        B.sablock_search_blocks(shape, buf.s_tilde, seg, w.cand, budget, w.tau, buf.seg_budget, buf.block_size, buf.ws,
+                                topb_out=buf.topb)
         mark(3)
-        B.sablock_select(shape, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws)
+        B.sablock_select(shape, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws,
+                         topb=buf.topb)
         mark(4)
         B.sablock_compact(shape, k, v, buf.idx, buf.n_sel, budget, True, buf.k_out, buf.v_out)
         mark(5)

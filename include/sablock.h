@@ -125,6 +125,10 @@ SABLOCK_API sablock_status sablock_refine(const sablock_shape *shape, const floa
  * cand: HOST array, ascending, cand[0] == 1, n_cand <= 16.  budget = the paper's B
  *   (entries chosen from the compressible region; may exceed T, may be 0).
  * seg_budget_out (b_k), block_size_out (g_k*, 0 where b_k == 0): [P][max_segments] int32.
+ * topb_out: optional [P][2] int32, the Top-B set in closed form: (order-preserving key v of the
+ *   min(budget,T)-th best score, index cut c); token t is in T_topB iff key(t) > v or (key(t) == v and
+ *   t <= c), key(x) = bits(x) ^ (x < 0 ? 0xFFFFFFFF : 0x80000000).  sablock_select accepts it back and then
+ *   skips recomputing it.
  * Block sums, scores and the accept test are evaluated in fp64 on the fp32 inputs. */
 SABLOCK_API sablock_status sablock_search_blocks(const sablock_shape *shape, const float *s_tilde,
                                      const int32_t *seg_off, const int32_t *seg_ptr /* host */,
@@ -132,16 +136,20 @@ SABLOCK_API sablock_status sablock_search_blocks(const sablock_shape *shape, con
                                      const int32_t *cand /* host */, int32_t n_cand,
                                      int32_t budget, float tau,
                                      int32_t *seg_budget_out, int32_t *block_size_out,
+                                     int32_t *topb_out /* nullable */,
                                      void *ws, size_t ws_bytes, void *stream);
 
 /* Selection (Alg. 2, Eq. final_selection): T_k* = T_k(g_k*) per segment, T* their union.
  * seg_budget, block_size: as written by sablock_search_blocks for the same s_tilde.
+ * topb: optional [P][2] int32 as written by sablock_search_blocks for the same s_tilde and budget
+ *   (NULL: recomputed here).
  * idx_out: [P][budget] int32, token indices in ascending order, entries past n_sel = -1.
  * n_sel_out: [P] int32 (= min(budget, T)). */
 SABLOCK_API sablock_status sablock_select(const sablock_shape *shape, const float *s_tilde,
                               const int32_t *seg_off, const int32_t *seg_ptr /* host */,
                               int32_t max_segments,
-                              const int32_t *seg_budget, const int32_t *block_size, int32_t budget,
+                              const int32_t *seg_budget, const int32_t *block_size,
+                              const int32_t *topb /* nullable */, int32_t budget,
                               int32_t *idx_out, int32_t *n_sel_out,
                               void *ws, size_t ws_bytes, void *stream);
 

@@ -60,8 +60,8 @@ def load():
         lib.sablock_refine.argtypes = [sp, vp, vp, vp, ctypes.POINTER(i32), i32, ctypes.POINTER(CHparams),
                                        vp, vp, vp, ctypes.c_size_t, vp]
         lib.sablock_search_blocks.argtypes = [sp, vp, vp, ctypes.POINTER(i32), i32, ctypes.POINTER(i32), i32,
-                                              i32, f32, vp, vp, vp, ctypes.c_size_t, vp]
-        lib.sablock_select.argtypes = [sp, vp, vp, ctypes.POINTER(i32), i32, vp, vp, i32, vp, vp, vp,
+                                              i32, f32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.sablock_select.argtypes = [sp, vp, vp, ctypes.POINTER(i32), i32, vp, vp, vp, i32, vp, vp, vp,
                                        ctypes.c_size_t, vp]
         lib.sablock_compact.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
         for n in EXPORTS[2:]:
@@ -150,19 +150,20 @@ def sablock_refine(shape: CShape, s, ent, seg: Segments, s_tilde_out, ws, alpha=
 
 
 def sablock_search_blocks(shape: CShape, s_tilde, seg: Segments, cand: Sequence[int], budget: int, tau: float,
-                          seg_budget_out, block_size_out, ws, stream=None):
+                          seg_budget_out, block_size_out, ws, stream=None, topb_out=None):
     c = (ctypes.c_int32 * len(cand))(*[int(x) for x in cand])
     _check(load().sablock_search_blocks(ctypes.byref(shape), _ptr(s_tilde), _ptr(seg.seg_off), seg.c_ptr(),
                                         seg.max_segments, c, len(cand), budget, tau, _ptr(seg_budget_out),
-                                        _ptr(block_size_out), _ptr(ws), ws.numel() * ws.element_size(),
-                                        _stream(stream)))
+                                        _ptr(block_size_out), _ptr(topb_out), _ptr(ws),
+                                        ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def sablock_select(shape: CShape, s_tilde, seg: Segments, seg_budget, block_size, budget: int,
-                   idx_out, n_sel_out, ws, stream=None):
+                   idx_out, n_sel_out, ws, stream=None, topb=None):
     _check(load().sablock_select(ctypes.byref(shape), _ptr(s_tilde), _ptr(seg.seg_off), seg.c_ptr(),
-                                 seg.max_segments, _ptr(seg_budget), _ptr(block_size), budget, _ptr(idx_out),
-                                 _ptr(n_sel_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+                                 seg.max_segments, _ptr(seg_budget), _ptr(block_size), _ptr(topb), budget,
+                                 _ptr(idx_out), _ptr(n_sel_out), _ptr(ws), ws.numel() * ws.element_size(),
+                                 _stream(stream)))
 
 
 def sablock_compact(shape: CShape, k, v, idx, n_sel, budget: int, append_window: bool, k_out, v_out,
@@ -194,6 +195,7 @@ class Buffers:
         self.block_size = torch.empty((P, ms), dtype=torch.int32, device=device)
         self.idx = torch.empty((P, max(budget, 1)), dtype=torch.int32, device=device)
         self.n_sel = torch.empty((P,), dtype=torch.int32, device=device)
+        self.topb = torch.empty((P, 2), dtype=torch.int32, device=device)
         rows = budget + (W if append_window else 0)
         self.k_out = torch.empty((P, max(rows, 1), D), dtype=dt, device=device)
         self.v_out = torch.empty((P, max(rows, 1), D), dtype=dt, device=device)
@@ -206,7 +208,9 @@ def compress(shape: CShape, q, k, v, seg: Segments, cand: Sequence[int], budget:
     """The whole hot path: score, refine, search_blocks, select, compact (five ABI calls, in order)."""
     sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, eps, row_lse, stream)
     sablock_refine(shape, buf.s, buf.ent, seg, buf.s_tilde, buf.ws, alpha, eta, buf.omega, stream)
-    sablock_search_blocks(shape, buf.s_tilde, seg, cand, budget, tau, buf.seg_budget, buf.block_size, buf.ws, stream)
-    sablock_select(shape, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws, stream)
+    sablock_search_blocks(shape, buf.s_tilde, seg, cand, budget, tau, buf.seg_budget, buf.block_size, buf.ws, stream,
+                          topb_out=buf.topb)
+    sablock_select(shape, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws, stream,
+                   topb=buf.topb)
     sablock_compact(shape, k, v, buf.idx, buf.n_sel, budget, buf.append_window, buf.k_out, buf.v_out, stream)
     return buf

@@ -82,7 +82,6 @@ size_t score_ws(const Dims &d)
     if (score_mfma_supported(d)) { size_t b = score_mfma_ws_bytes(d); if (b > a) a = b; }
     return a;
 }
-size_t search_ws(const Dims &d) { return align256((size_t)d.P * 2 * 4); }
 
 sablock_status dev(hipError_t e, const char *what)
 {
@@ -106,8 +105,8 @@ sablock_status sablock_workspace_bytes(const sablock_shape *shape, int32_t max_s
     if (!bytes_out) return fail(SABLOCK_ERR_INVALID_ARG, "bytes_out is NULL");
     if (max_segments < 0 || budget < 0) return fail(SABLOCK_ERR_INVALID_ARG, "max_segments or budget < 0");
     size_t b = score_ws(d);
-    size_t c = search_ws(d); if (c > b) b = c;
-    c = select_ws_bytes(d, max_segments); if (c > b) b = c;
+    size_t c = search_ws_bytes(d, max_segments, budget); if (c > b) b = c;
+    c = select_ws_bytes(d, max_segments, budget); if (c > b) b = c;
     *bytes_out = b + 256;
     return SABLOCK_OK;
 }
@@ -153,7 +152,7 @@ sablock_status sablock_refine(const sablock_shape *shape, const float *s, const 
 sablock_status sablock_search_blocks(const sablock_shape *shape, const float *s_tilde,
                                      const int32_t *seg_off, const int32_t *seg_ptr, int32_t max_segments,
                                      const int32_t *cand, int32_t n_cand, int32_t budget, float tau,
-                                     int32_t *seg_budget_out, int32_t *block_size_out,
+                                     int32_t *seg_budget_out, int32_t *block_size_out, int32_t *topb_out,
                                      void *ws, size_t ws_bytes, void *stream)
 {
     Dims d;
@@ -176,20 +175,19 @@ sablock_status sablock_search_blocks(const sablock_shape *shape, const float *s_
     SegView sv;
     st = make_segview(d, seg_off, seg_ptr, max_segments, &sv);
     if (st != SABLOCK_OK) return st;
-    const size_t need = search_ws(d);
+    const size_t need = search_ws_bytes(d, max_segments, budget);
     if (!ws || ws_bytes < need)
         return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_search_blocks: workspace %zu < %zu bytes", ws_bytes, need);
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    int32_t *thr = static_cast<int32_t *>(ws);
-    hipError_t e = launch_topb(d, s_tilde, budget, thr, hs);
-    if (e == hipSuccess) e = launch_search(d, s_tilde, sv, cl, tau, thr, seg_budget_out, block_size_out, hs);
+    hipError_t e = launch_search(d, s_tilde, sv, cl, budget, tau, seg_budget_out, block_size_out, topb_out, ws,
+                                 static_cast<hipStream_t>(stream));
     return dev(e, "sablock_search_blocks");
 }
 
 sablock_status sablock_select(const sablock_shape *shape, const float *s_tilde,
                               const int32_t *seg_off, const int32_t *seg_ptr, int32_t max_segments,
-                              const int32_t *seg_budget, const int32_t *block_size, int32_t budget,
-                              int32_t *idx_out, int32_t *n_sel_out, void *ws, size_t ws_bytes, void *stream)
+                              const int32_t *seg_budget, const int32_t *block_size, const int32_t *topb,
+                              int32_t budget, int32_t *idx_out, int32_t *n_sel_out, void *ws, size_t ws_bytes,
+                              void *stream)
 {
     Dims d;
     sablock_status st = make_dims(shape, &d);
@@ -200,10 +198,10 @@ sablock_status sablock_select(const sablock_shape *shape, const float *s_tilde,
     SegView sv;
     st = make_segview(d, seg_off, seg_ptr, max_segments, &sv);
     if (st != SABLOCK_OK) return st;
-    const size_t need = select_ws_bytes(d, max_segments);
+    const size_t need = select_ws_bytes(d, max_segments, budget);
     if (!ws || ws_bytes < need)
         return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_select: workspace %zu < %zu bytes", ws_bytes, need);
-    return dev(launch_select(d, s_tilde, sv, seg_budget, block_size, budget, idx_out, n_sel_out, ws,
+    return dev(launch_select(d, s_tilde, sv, seg_budget, block_size, topb, budget, idx_out, n_sel_out, ws,
                              static_cast<hipStream_t>(stream)), "sablock_select");
 }
 

@@ -83,14 +83,15 @@ hipError_t launch_refine(const Dims &d, const float *s, const float *ent, const 
 // Top-B threshold per problem: thr[p] = {ordered key of the B-th best score, index cut among its ties}
 hipError_t launch_topb(const Dims &d, const float *s_tilde, int32_t budget, int32_t *thr, hipStream_t st);
 
+size_t search_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget);
 hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
-                         float tau, const int32_t *thr, int32_t *seg_budget, int32_t *block_size,
-                         hipStream_t st);
-
-size_t select_ws_bytes(const Dims &d, int32_t max_segments);
-hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv, const int32_t *seg_budget,
-                         const int32_t *block_size, int32_t budget, int32_t *idx_out, int32_t *n_sel_out,
+                         int32_t budget, float tau, int32_t *seg_budget, int32_t *block_size, int32_t *topb_out,
                          void *ws, hipStream_t st);
+
+size_t select_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget);
+hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv, const int32_t *seg_budget,
+                         const int32_t *block_size, const int32_t *topb, int32_t budget, int32_t *idx_out,
+                         int32_t *n_sel_out, void *ws, hipStream_t st);
 
 hipError_t launch_compact(const Dims &d, const void *k, const void *v, const int32_t *idx,
                           const int32_t *n_sel, int32_t budget, int32_t append_window,

@@ -518,7 +518,7 @@ Plan make_plan(const Dims &d)
     // long chunks amortise its prologue (window queries into registers, first loads), but there should be at
     // least a few workgroups per CU so that the 256 CUs stay evenly loaded.
     Plan pl;
-    int len = 8192;
+    int len = 32768;
     if (const char *e = getenv("SABLOCK_SCORE_CHUNK")) { int v = atoi(e); if (v >= STRIDE) len = (v / STRIDE) * STRIDE; }
     else while (len > STRIDE && (int64_t)d.P * ((d.L + len - 1) / len) < 1024) len /= 2;
     pl.chunk_len = len;

@@ -5,10 +5,15 @@
 //                 the min(B,T)-th best score, ties resolved by ascending index.
 //                 Result: (ordered key v, index cut c); token t is in T_topB iff
 //                 key(t) > v or (key(t) == v and t <= c).
-// search_kernel   one wavefront per (problem, segment): b_k, Score_base, then the
+// seg_count_kernel  one thread per token: every Top-B token adds 1 to its segment's b_k.
+// heavy_list_kernel one workgroup per problem: segments with b_k >= 2 are listed (only
+//                 they need a search; b_k == 1 means g_k* = 1, b_k == 0 means g_k* = 0).
+// search_kernel   one wavefront per listed (problem, segment): Score_base, then the
 //                 candidates largest first.
-// select_kernel   one wavefront per (problem, segment): T_k(g_k*) written in
-//                 ascending order at the segment's offset (prefix sum of b_k).
+// seg_prefix_kernel one workgroup per problem: prefix sum of b_k (output offsets) and the
+//                 list of segments that retain anything.
+// select_kernel   one wavefront per listed (problem, segment): T_k(g_k*) written in
+//                 ascending order at the segment's offset.
 //
 // All quantities that decide an integer (block sums Phi, Score_k(g), Score_base,
 // tau * Score_base) are fp64 and summed in ascending token order, one addition at
@@ -50,7 +55,7 @@ __device__ inline double add_in_order(double acc, unsigned long long mask, float
 constexpr int TB_THREADS = 1024;
 
 __global__ void __launch_bounds__(TB_THREADS)
-topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr)
+topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, int32_t *zero_a, int32_t *zero_b, int row_len)
 {
     __shared__ uint32_t hist[2048];
     __shared__ uint32_t sh_bin, sh_above;
@@ -60,6 +65,9 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *sp = s_tilde + (int64_t)p * T;
     const int k = min(budget, T);
+    if (zero_a) {            // the search counts into / writes these rows later in the stream
+        for (int i = tid; i < row_len; i += TB_THREADS) { zero_a[(int64_t)p * row_len + i] = 0; zero_b[(int64_t)p * row_len + i] = 0; }
+    }
     if (k <= 0) { if (tid == 0) { thr[2 * p] = (int32_t)0xFFFFFFFFu; thr[2 * p + 1] = -1; } return; }
     if (k >= T) { if (tid == 0) { thr[2 * p] = 0; thr[2 * p + 1] = T - 1; } return; }
 
@@ -156,6 +164,7 @@ __device__ inline int block_rank(V val, int a, int b, int g, int nb, int m, doub
                                  const double *phi_lds, bool fast)
 {
     int r = 0;
+#pragma unroll 4
     for (int o = 0; o < nb; ++o) {
         double po = fast ? phi_lds[o] : block_sum(val, a, b, g, o);
         r += (po > phi_m || (po == phi_m && o < m)) ? 1 : 0;
@@ -274,36 +283,104 @@ __device__ inline bool in_topb(float v, int t, uint32_t thr_key, int thr_cut)
 }
 
 // ------------------------------------------------------------------ search
-// grid (ceil(max_segments / WAVES), P)
-__global__ void __launch_bounds__(WAVES * 64)
-search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau, const int32_t *thr,
-              int32_t *seg_budget, int32_t *block_size)
+// segment of token t: the k with seg_off[k] <= t < seg_off[k+1], 0 <= k < K
+__device__ inline int segment_of(const int32_t *off, int K, int t)
 {
-    __shared__ double sh_phi[WAVES][CAPB];
-    __shared__ float sh_val[WAVES][CAPT];
-    __shared__ uint8_t sh_cls[WAVES][CAPB];
+    int lo = 0, hi = K;                       // invariant: off[lo] <= t < off[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (off[mid] <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// implicit budgets (Eq. implicit_budget): grid (ceil(T / (256 * 8)), P); seg_budget rows are zero on entry.
+// A workgroup covers 2048 consecutive tokens; the segments they fall in form a short range that is located once
+// per workgroup, so a Top-B token finds its segment in a few steps.
+__global__ void __launch_bounds__(256)
+seg_count_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, int32_t *seg_budget)
+{
+    __shared__ int sh_range[2];
+    const int p = blockIdx.y, T = d.T;
+    const float *sp = s_tilde + (int64_t)p * T;
+    const uint32_t thr_key = (uint32_t)thr[2 * p];
+    const int thr_cut = thr[2 * p + 1];
+    const int seq = seq_of_problem(d, p);
+    const int32_t *off = sv.seg_off + sv.seq_ptr[seq];
+    const int K = sv.seq_ptr[seq + 1] - sv.seq_ptr[seq] - 1;
+    const int base_t = blockIdx.x * (256 * 8);
+    if (threadIdx.x < 2) sh_range[threadIdx.x] = segment_of(off, K, threadIdx.x == 0 ? base_t : min(base_t + 256 * 8, T) - 1);
+    const int t0 = base_t + threadIdx.x;
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { const int t = t0 + j * 256; v[j] = sp[t < T ? t : T - 1]; }
+    __syncthreads();
+    const int k_lo = sh_range[0], k_hi = sh_range[1] + 1;          // off[k_lo] <= t < off[k_hi] for every token here
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int t = t0 + j * 256;
+        if (t < T && in_topb(v[j], t, thr_key, thr_cut))
+            atomicAdd(&seg_budget[(int64_t)p * sv.max_segments + k_lo + segment_of(off + k_lo, k_hi - k_lo, t)], 1);
+    }
+}
+
+// one workgroup per problem: ordered list of the segments with b_k >= 2, and g_k* = 1 where b_k == 1
+__global__ void __launch_bounds__(256)
+heavy_list_kernel(Dims d, SegView sv, const int32_t *seg_budget, int32_t *block_size, int32_t *heavy,
+                  int32_t *n_heavy, int max_heavy)
+{
+    __shared__ int sh_w[4];
+    const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seq = seq_of_problem(d, p);
+    const int K = sv.seq_ptr[seq + 1] - sv.seq_ptr[seq] - 1;
+    const int64_t row = (int64_t)p * sv.max_segments;
+    int carry = 0;
+    for (int c0 = 0; c0 < K; c0 += 256) {
+        const int k = c0 + tid;
+        const int bk = k < K ? seg_budget[row + k] : 0;
+        if (k < K && bk == 1) block_size[row + k] = 1;
+        const bool hv = bk >= 2;
+        const unsigned long long bal = __ballot(hv);
+        if (lane == 0) sh_w[wave] = __popcll(bal);
+        __syncthreads();
+        int before = 0, total = 0;
+        for (int w = 0; w < 4; ++w) { if (w < wave) before += sh_w[w]; total += sh_w[w]; }
+        const int pos = carry + before + __popcll(bal & ((1ull << lane) - 1ull));
+        if (hv && pos < max_heavy) heavy[(int64_t)p * max_heavy + pos] = k;
+        carry += total;
+        __syncthreads();
+    }
+    if (tid == 0) n_heavy[p] = min(carry, max_heavy);
+}
+
+// grid (SEARCH_GRID, P), one wavefront each, striding over the problem's list of segments with b_k >= 2
+constexpr int SEARCH_GRID = 1024;
+
+__global__ void __launch_bounds__(64)
+search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau, const int32_t *thr,
+              const int32_t *heavy, const int32_t *n_heavy, int max_heavy, const int32_t *seg_budget,
+              int32_t *block_size)
+{
+    __shared__ double sh_phi[CAPB];
+    __shared__ float sh_val[CAPT];
+    __shared__ uint8_t sh_cls[CAPB];
     const int p = blockIdx.y;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int k = blockIdx.x * WAVES + wave;
-    if (k >= sv.max_segments) return;
+    const int lane = threadIdx.x;
+    const int n_list = n_heavy[p];
+    for (int j = blockIdx.x; j < n_list; j += gridDim.x) {
+    const int k = heavy[(int64_t)p * max_heavy + j];
     const int seq = seq_of_problem(d, p);
     const int sbase = sv.seq_ptr[seq];
-    const int K = sv.seq_ptr[seq + 1] - sbase - 1;
     const int64_t o = (int64_t)p * sv.max_segments + k;
-    if (k >= K) {
-        if (lane == 0) { seg_budget[o] = 0; block_size[o] = 0; }
-        return;
-    }
     const int a = sv.seg_off[sbase + k], b = sv.seg_off[sbase + k + 1];
+    const int bk = seg_budget[o];
     const float *sp = s_tilde + (int64_t)p * d.T;
     const uint32_t thr_key = (uint32_t)thr[2 * p];
     const int thr_cut = thr[2 * p + 1];
 
-    // implicit budget b_k (Eq. implicit_budget) and token-level baseline Score_base; segments that fit are
-    // copied to LDS on the way so that the candidate loop never goes back to global memory
+    // token-level baseline Score_base = sum over T_topB & S_k, ascending; segments that fit are copied to LDS
+    // on the way so that the candidate loop never goes back to global memory
     const bool staged = b - a <= CAPT;
-    float *lv = sh_val[wave];
-    int bk = 0;
     double base = 0.0;
     for (int c0 = a; c0 < b; c0 += 64) {
         const int t = c0 + lane;
@@ -312,42 +389,43 @@ search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau
         if (t < b) {
             v = sp[t];
             in = in_topb(v, t, thr_key, thr_cut);
-            if (staged) lv[t - a] = v;
+            if (staged) sh_val[t - a] = v;
         }
-        const unsigned long long m = __ballot(in);
-        bk += __popcll(m);
-        base = add_in_order(base, m, v);
+        base = add_in_order(base, __ballot(in), v);
     }
     __builtin_amdgcn_wave_barrier();
     int gstar = 0;
-    if (bk > 0) {
-        const int gcap = min(b - a, bk);                    // G_k: g <= min(|S_k|, b_k, g_max)
-        const double need = (double)tau * base;            // R_k(g) >= tau  <=>  Score_k(g) >= tau * Score_base
-        WaveScratch ws{sh_phi[wave], sh_cls[wave]};
-        auto run = [&](auto val) {
-            for (int c = cand.n - 1; c >= 0; --c) {
-                const int g = cand.g[c];
-                if (g > gcap) continue;
-                if (g == 1) { gstar = 1; break; }           // token level: the unconditional last resort
-                double score = 0.0;
-                segment_fill(val, a, b, g, bk, ws,
-                             [&](int, unsigned long long m, float v) { score = add_in_order(score, m, v); });
-                if (score >= need) { gstar = g; break; }    // Eq. gk_star: first accepted, largest first
-            }
-        };
-        if (staged) run([lv, a](int t) { return lv[t - a]; });
-        else run([sp](int t) { return sp[t]; });
+    const int gcap = min(b - a, bk);                        // G_k: g <= min(|S_k|, b_k, g_max)
+    const double need = (double)tau * base;                // R_k(g) >= tau  <=>  Score_k(g) >= tau * Score_base
+    WaveScratch ws{sh_phi, sh_cls};
+    auto run = [&](auto val) {
+        for (int c = cand.n - 1; c >= 0; --c) {
+            const int g = cand.g[c];
+            if (g > gcap) continue;
+            if (g == 1) { gstar = 1; break; }               // token level: the unconditional last resort
+            double score = 0.0;
+            segment_fill(val, a, b, g, bk, ws,
+                         [&](int, unsigned long long m, float v) { score = add_in_order(score, m, v); });
+            if (score >= need) { gstar = g; break; }        // Eq. gk_star: first accepted, largest first
+        }
+    };
+    float *lv = sh_val;
+    if (staged) run([lv, a](int t) { return lv[t - a]; });
+    else run([sp](int t) { return sp[t]; });
+    if (lane == 0) block_size[o] = gstar;
+    __builtin_amdgcn_wave_barrier();                        // the LDS slices are reused by the next segment
     }
-    if (lane == 0) { seg_budget[o] = bk; block_size[o] = gstar; }
 }
 
 // ------------------------------------------------------------------ select
-// exclusive prefix of b_k over the segments of one problem; also n_sel and the -1 padding of idx_out
+// exclusive prefix of b_k over the segments of one problem, the ordered list of segments that retain anything,
+// n_sel and the -1 padding of idx_out
 __global__ void __launch_bounds__(256)
-seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, int budget, int32_t *prefix,
-                  int32_t *idx_out, int32_t *n_sel_out)
+seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *block_size, int budget, int32_t *prefix,
+                  int32_t *act, int32_t *n_act, int max_act, int32_t *idx_out, int32_t *n_sel_out)
 {
-    __shared__ int sh_w[4];
+    __shared__ int sh_w[4], sh_a[4];
+    int carry_a = 0;
     const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = seq_of_problem(d, p);
     const int K = sv.seq_ptr[seq + 1] - sv.seq_ptr[seq] - 1;
@@ -357,36 +435,39 @@ seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, int budget, int
     for (int c0 = 0; c0 < K; c0 += 256) {
         const int k = c0 + tid;
         const int v = (k < K) ? bp[k] : 0;
+        const bool active = v > 0 && block_size[(int64_t)p * sv.max_segments + (k < K ? k : 0)] > 0;
+        const unsigned long long bal = __ballot(active);
         int incl = v;
         for (int off = 1; off < 64; off <<= 1) { int o = __shfl_up(incl, off); if (lane >= off) incl += o; }
         if (lane == 63) sh_w[wave] = incl;
+        if (lane == 0) sh_a[wave] = __popcll(bal);
         __syncthreads();
-        int before = 0, total = 0;
-        for (int w = 0; w < 4; ++w) { if (w < wave) before += sh_w[w]; total += sh_w[w]; }
+        int before = 0, total = 0, before_a = 0, total_a = 0;
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) { before += sh_w[w]; before_a += sh_a[w]; }
+            total += sh_w[w]; total_a += sh_a[w];
+        }
         if (k < K) pp[k] = carry + before + incl - v;
+        const int pa = carry_a + before_a + __popcll(bal & ((1ull << lane) - 1ull));
+        if (active && pa < max_act) act[(int64_t)p * max_act + pa] = k;
         carry += total;
+        carry_a += total_a;
         __syncthreads();
     }
     const int n = min(carry, budget);
-    if (tid == 0) n_sel_out[p] = n;
+    if (tid == 0) { n_sel_out[p] = n; n_act[p] = min(carry_a, max_act); }
     for (int j = n + tid; j < budget; j += 256) idx_out[(int64_t)p * budget + j] = -1;
 }
 
-// grid (ceil(max_segments / WAVES), P)
-__global__ void __launch_bounds__(WAVES * 64)
-select_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, const int32_t *seg_budget,
-              const int32_t *block_size, const int32_t *prefix, int budget, int32_t *idx_out)
+// T_k(g_k*) of one segment, written in ascending order from its offset in idx_out
+__device__ inline void select_segment(const Dims &d, const float *s_tilde, const SegView &sv, const int32_t *thr,
+                                      const int32_t *seg_budget, const int32_t *block_size, const int32_t *prefix,
+                                      int budget, int32_t *idx_out, int p, int k, double (&sh_phi)[WAVES][CAPB],
+                                      float (&sh_val)[WAVES][CAPT], uint8_t (&sh_cls)[WAVES][CAPB])
 {
-    __shared__ double sh_phi[WAVES][CAPB];
-    __shared__ float sh_val[WAVES][CAPT];
-    __shared__ uint8_t sh_cls[WAVES][CAPB];
-    const int p = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int k = blockIdx.x * WAVES + wave;
     const int seq = seq_of_problem(d, p);
     const int sbase = sv.seq_ptr[seq];
-    const int K = sv.seq_ptr[seq + 1] - sbase - 1;
-    if (k >= K) return;
     const int64_t o = (int64_t)p * sv.max_segments + k;
     const int a = sv.seg_off[sbase + k], b = sv.seg_off[sbase + k + 1];
     const int bk = min(seg_budget[o], b - a);
@@ -438,46 +519,113 @@ select_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, cons
     }
 }
 
+// grid (SELECT_GRID, P), one wavefront each, striding over the problem's list of segments that retain anything
+constexpr int SELECT_GRID = 2048;
+
+__global__ void __launch_bounds__(WAVES * 64)
+select_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, const int32_t *seg_budget,
+              const int32_t *block_size, const int32_t *prefix, const int32_t *act, const int32_t *n_act, int max_act,
+              int budget, int32_t *idx_out)
+{
+    __shared__ double sh_phi[WAVES][CAPB];
+    __shared__ float sh_val[WAVES][CAPT];
+    __shared__ uint8_t sh_cls[WAVES][CAPB];
+    const int p = blockIdx.y;
+    const int n_list = n_act[p];
+    for (int j = blockIdx.x; j < n_list; j += gridDim.x) {
+        select_segment(d, s_tilde, sv, thr, seg_budget, block_size, prefix, budget, idx_out, p,
+                       act[(int64_t)p * max_act + j], sh_phi, sh_val, sh_cls);
+        __builtin_amdgcn_wave_barrier();                    // the LDS slices are reused by the next segment
+    }
+}
+
 }  // namespace
 
 hipError_t launch_topb(const Dims &d, const float *s_tilde, int32_t budget, int32_t *thr, hipStream_t st)
 {
     if (d.P <= 0) return hipSuccess;
-    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr);
+    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr,
+                       (int32_t *)nullptr, (int32_t *)nullptr, 0);
     return hipGetLastError();
+}
+
+static int max_heavy_segments(const Dims &d, int32_t max_segments, int32_t budget)
+{
+    const int k = budget < d.T ? budget : d.T;             // |T_topB|; a listed segment holds at least two of them
+    const int h = k / 2 < max_segments ? k / 2 : max_segments;
+    return h > 0 ? h : 0;
+}
+
+size_t search_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget)
+{
+    const int mh = max_heavy_segments(d, max_segments, budget);
+    return align256((size_t)d.P * 2 * 4) + align256((size_t)d.P * (size_t)(mh > 0 ? mh : 1) * 4) + align256((size_t)d.P * 4);
 }
 
 hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
-                         float tau, const int32_t *thr, int32_t *seg_budget, int32_t *block_size,
-                         hipStream_t st)
+                         int32_t budget, float tau, int32_t *seg_budget, int32_t *block_size, int32_t *topb_out,
+                         void *ws, hipStream_t st)
 {
     if (d.P <= 0 || sv.max_segments <= 0) return hipSuccess;
-    dim3 grid((sv.max_segments + WAVES - 1) / WAVES, d.P);
-    hipLaunchKernelGGL(search_kernel, grid, dim3(WAVES * 64), 0, st, d, s_tilde, sv, cand, tau, thr,
-                       seg_budget, block_size);
+    const int mh = max_heavy_segments(d, sv.max_segments, budget);
+    char *w = static_cast<char *>(ws);
+    int32_t *thr = topb_out ? topb_out : reinterpret_cast<int32_t *>(w);
+    int32_t *heavy = reinterpret_cast<int32_t *>(w + align256((size_t)d.P * 2 * 4));
+    int32_t *n_heavy = reinterpret_cast<int32_t *>(w + align256((size_t)d.P * 2 * 4) + align256((size_t)d.P * (size_t)(mh > 0 ? mh : 1) * 4));
+    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, seg_budget,
+                       block_size, sv.max_segments);
+    if (budget > 0 && d.T > 0) {
+        dim3 gc((d.T + 256 * 8 - 1) / (256 * 8), d.P);
+        hipLaunchKernelGGL(seg_count_kernel, gc, dim3(256), 0, st, d, s_tilde, sv, thr, seg_budget);
+        hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(256), 0, st, d, sv, seg_budget, block_size, heavy,
+                           n_heavy, mh);
+        if (mh > 0)
+            hipLaunchKernelGGL(search_kernel, dim3(mh < SEARCH_GRID ? mh : SEARCH_GRID, d.P), dim3(64), 0, st, d, s_tilde, sv, cand, tau, thr, heavy,
+                               n_heavy, mh, seg_budget, block_size);
+    }
     return hipGetLastError();
 }
 
-size_t select_ws_bytes(const Dims &d, int32_t max_segments)
+static int max_active_segments(int32_t max_segments, int32_t budget)
 {
-    return align256((size_t)d.P * 2 * 4) + align256((size_t)d.P * (size_t)(max_segments > 0 ? max_segments : 1) * 4);
+    const int a = budget < max_segments ? budget : max_segments;   // a listed segment retains at least one token
+    return a > 0 ? a : 1;
+}
+
+size_t select_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget)
+{
+    const size_t ms = (size_t)(max_segments > 0 ? max_segments : 1);
+    return align256((size_t)d.P * 2 * 4) + align256((size_t)d.P * ms * 4) +
+           align256((size_t)d.P * (size_t)max_active_segments(max_segments, budget) * 4) + align256((size_t)d.P * 4);
 }
 
 hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv, const int32_t *seg_budget,
-                         const int32_t *block_size, int32_t budget, int32_t *idx_out, int32_t *n_sel_out,
-                         void *ws, hipStream_t st)
+                         const int32_t *block_size, const int32_t *topb, int32_t budget, int32_t *idx_out,
+                         int32_t *n_sel_out, void *ws, hipStream_t st)
 {
     if (d.P <= 0) return hipSuccess;
-    int32_t *thr = static_cast<int32_t *>(ws);
-    int32_t *prefix = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + align256((size_t)d.P * 2 * 4));
-    hipError_t e = launch_topb(d, s_tilde, budget, thr, st);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(seg_prefix_kernel, dim3(d.P), dim3(256), 0, st, d, sv, seg_budget, budget, prefix,
-                       idx_out, n_sel_out);
+    const size_t ms = (size_t)(sv.max_segments > 0 ? sv.max_segments : 1);
+    const int ma = max_active_segments(sv.max_segments, budget);
+    char *w = static_cast<char *>(ws);
+    int32_t *thr_ws = reinterpret_cast<int32_t *>(w);
+    w += align256((size_t)d.P * 2 * 4);
+    int32_t *prefix = reinterpret_cast<int32_t *>(w);
+    w += align256((size_t)d.P * ms * 4);
+    int32_t *act = reinterpret_cast<int32_t *>(w);
+    w += align256((size_t)d.P * (size_t)ma * 4);
+    int32_t *n_act = reinterpret_cast<int32_t *>(w);
+    const int32_t *thr = topb;
+    if (!thr) {
+        hipError_t e = launch_topb(d, s_tilde, budget, thr_ws, st);
+        if (e != hipSuccess) return e;
+        thr = thr_ws;
+    }
+    hipLaunchKernelGGL(seg_prefix_kernel, dim3(d.P), dim3(256), 0, st, d, sv, seg_budget, block_size, budget, prefix,
+                       act, n_act, ma, idx_out, n_sel_out);
     if (sv.max_segments > 0 && budget > 0) {
-        dim3 grid((sv.max_segments + WAVES - 1) / WAVES, d.P);
+        dim3 grid(ma < SELECT_GRID ? ma : SELECT_GRID, d.P);
         hipLaunchKernelGGL(select_kernel, grid, dim3(WAVES * 64), 0, st, d, s_tilde, sv, thr, seg_budget,
-                           block_size, prefix, budget, idx_out);
+                           block_size, prefix, act, n_act, ma, budget, idx_out);
     }
     return hipGetLastError();
 }

@@ -76,15 +76,15 @@ def test_calls_reject_bad_host_arguments_before_launch(lib):
     assert lib.sablock_score(sp, ctypes.c_void_p(0x1004), fake, None, 1e-6, fake, fake, fake, 1 << 30, None) == 1
     assert lib.sablock_refine(sp, fake, fake, fake, None, 4, ctypes.byref(hp), fake, None, fake, 0, None) == 1
     assert lib.sablock_refine(sp, fake, fake, fake, ptr2, 2, ctypes.byref(hp), fake, None, fake, 0, None) == 1  # 4 segs > 2
-    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_bad, 3, 10, 0.85, fake, fake, fake, 1 << 20, None) == 1
-    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_desc, 3, 10, 0.85, fake, fake, fake, 1 << 20, None) == 1
-    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 3, -1, 0.85, fake, fake, fake, 1 << 20, None) == 1
-    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 0, 10, 0.85, fake, fake, fake, 1 << 20, None) == 1
-    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 3, 10, 0.85, fake, fake, fake, 0, None) == 3
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_bad, 3, 10, 0.85, fake, fake, None, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_desc, 3, 10, 0.85, fake, fake, None, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 3, -1, 0.85, fake, fake, None, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 0, 10, 0.85, fake, fake, None, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 3, 10, 0.85, fake, fake, None, fake, 0, None) == 3
     big = (ctypes.c_int32 * 2)(1, 128)
-    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, big, 2, 10, 0.85, fake, fake, fake, 1 << 20, None) == 2
-    assert lib.sablock_select(sp, fake, fake, ptr2, 4, fake, fake, -5, fake, fake, fake, 1 << 20, None) == 1
-    assert lib.sablock_select(sp, fake, fake, ptr2, 4, fake, fake, 5, fake, fake, fake, 8, None) == 3
+    assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, big, 2, 10, 0.85, fake, fake, None, fake, 1 << 20, None) == 2
+    assert lib.sablock_select(sp, fake, fake, ptr2, 4, fake, fake, None, -5, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.sablock_select(sp, fake, fake, ptr2, 4, fake, fake, None, 5, fake, fake, fake, 8, None) == 3
     assert lib.sablock_compact(sp, fake, None, fake, fake, 8, 1, fake, fake, None) == 1
     assert lib.sablock_compact(sp, fake, fake, fake, fake, -8, 1, fake, fake, None) == 1
     assert lib.sablock_score(None, fake, fake, None, 1e-6, fake, fake, fake, 0, None) == 1
