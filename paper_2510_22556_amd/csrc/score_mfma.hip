@@ -75,7 +75,7 @@ __device__ __forceinline__ int query_of(int i, int hf) { return 8 * (i >> 2) + 4
 // (scalar registers) plus a per-lane 32-bit byte offset; M0 carries the LDS destination of each 1 KiB group.
 __device__ __forceinline__ void dma_1k(uint32_t voff, const char *sbase, uint32_t lds_dst)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(sbase), "s"(lds_dst) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" : : "v"(voff), "s"(sbase), "s"(lds_dst) : "memory", "m0");
 }
 
 // subtile entirely inside [0, L): one of four precomputed lane offsets
@@ -195,6 +195,22 @@ struct KeyStream {
     }
 };
 
+// A operands: the window queries of the four heads, query row `n`, k-slices (2s + hf) * 8 .. +8, into
+// accumulation registers.  All 32 loads are issued before the first is consumed.
+__device__ __forceinline__ void load_queries(bf16x8 (&qa)[4][8], const uint16_t *q, const Dims &d, int p, int n, int hf)
+{
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        const uint16_t *row = q + q_row_offset(d, p, h, n);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+    }
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qa[h][s]));
+}
+
 constexpr int NBUF = 4;
 constexpr int WAVES = 4;
 constexpr int RING_BYTES = NBUF * BUF_BYTES;
@@ -206,18 +222,29 @@ constexpr int RING_BYTES = NBUF * BUF_BYTES;
 // anchored at the maximum over the wavefront's first 32 keys and re-anchored (rarely) when a later logit exceeds
 // the reference by more than RESCALE_AT, so any finite logits are handled without overflow or total underflow.
 //
-// stats_head reduces one head of one subtile; `tail` (the second half of the NEXT head's MFMAs) is issued between
-// its two halves so that the matrix pipe stays busy across the rare re-anchor branch.
-template <bool EDGE, typename Tail>
-__device__ __forceinline__ void stats_head(const floatx16 &acc, float (&z)[16], float *cref_h, float c1, bool first,
-                                           int t, int hf, int n, int T, int L, Tail &&tail)
+// The loop over subtiles has two bodies.  The fast one assumes keys before the window (no causal mask) and no
+// re-anchoring: per head a maximum over the raw accumulators guards the exponentials, and a head that fails the
+// guard leaves the fast body BEFORE anything of it was added.  The careful one (first subtile, subtiles touching
+// the window or the end of the sequence, and the rest of a subtile after a failed guard) masks, re-anchors and
+// runs the heads one after the other.  Keeping the careful code out of the fast body keeps the fast body free
+// of register copies at control-flow joins.
+
+// C operand of head h for this lane half: 16 consecutive floats
+__device__ __forceinline__ floatx16 load_cref(const float *cref, int h, int hf)
+{
+    return *reinterpret_cast<const floatx16 *>(cref + h * 32 + hf * 16);
+}
+
+// careful reduction of one head tile of the subtile whose lane key is t
+__device__ __forceinline__ void stats_head_careful(const floatx16 &acc, float (&z)[16], float *cref_h, float c1, bool first,
+                                                   int t, int hf, int n, int T, int L)
 {
     float dd[16];
     float dmax = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         float v = acc[i] * c1;
-        if (EDGE && !(t < L && t <= T + query_of(i, hf))) v = -INFINITY;     // causal inside the window
+        if (!(t < L && t <= T + query_of(i, hf))) v = -INFINITY;         // causal inside the window
         dd[i] = v;
         dmax = fmaxf(dmax, v);
     }
@@ -236,40 +263,74 @@ __device__ __forceinline__ void stats_head(const floatx16 &acc, float (&z)[16], 
             if (n == 0 && move) cref_h[hf * 16 + i] -= cshift;
         }
     }
-    tail();
 #pragma unroll
     for (int i = 0; i < 16; ++i) z[i] += __builtin_amdgcn_exp2f(dd[i]);
+}
+
+// guard of the fast body: true when some accumulator of the wavefront exceeds `lim` (= RESCALE_AT / c1)
+__device__ __forceinline__ bool stats_guard(const floatx16 &acc, float lim)
+{
+    float m = fmaxf(acc[0], acc[1]);
+#pragma unroll
+    for (int i = 2; i < 16; i += 2) m = fmaxf(fmaxf(m, acc[i]), acc[i + 1]);
+    return __any(m > lim);
+}
+
+__device__ __forceinline__ void stats_add(const floatx16 &acc, float (&z)[16], float c1)
+{
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] += __builtin_amdgcn_exp2f(acc[i] * c1);
     // materialise the sums here: keeps the compiler from sinking this head's exponentials past the next heads
     asm volatile("" : "+v"(z[0]), "+v"(z[1]), "+v"(z[2]), "+v"(z[3]), "+v"(z[4]), "+v"(z[5]), "+v"(z[6]), "+v"(z[7]),
                       "+v"(z[8]), "+v"(z[9]), "+v"(z[10]), "+v"(z[11]), "+v"(z[12]), "+v"(z[13]), "+v"(z[14]), "+v"(z[15]));
 }
 
-// C operand of head h for this lane half: 16 consecutive floats
-__device__ __forceinline__ floatx16 load_cref(const float *cref, int h, int hf)
-{
-    return *reinterpret_cast<const floatx16 *>(cref + h * 32 + hf * 16);
-}
+constexpr int STATS_OK = -1;
+constexpr int STATS_PREV = 3;              // the guard failed for head 3 of the previous subtile
 
-// One subtile.  Head h is multiplied into acc[h & 1] while head h-1 (head 3: of the previous subtile) is
-// reduced from the other accumulator, so two accumulators serve the four heads.
-template <bool EDGE>
-__device__ __forceinline__ void stats_body(const bf16x8 (&qa)[4][8], const bf16x8 (&kb)[8], floatx16 (&acc)[2],
-                                           float *cref, float (&z)[4][16], float c1, bool first_prev, bool first_cur,
-                                           int t_prev, int t_cur, int hf, int n, int T, int L)
+// Fast body of one subtile.  Head h is multiplied into acc[h & 1] while head h-1 (head 3: of the previous
+// subtile, waiting in acc[1]) is exponentiated from the other accumulator; the first two k-steps of a head are
+// issued before the guard of the head before it, the other six after it, next to that head's exponentials.
+// Returns STATS_OK, or which head failed its guard: STATS_PREV, or 0..2 = that head of this subtile (the heads
+// before it were added, it and the ones after it were not).  Head 3 of this subtile is left waiting in acc[1].
+__device__ __forceinline__ int stats_fast(const bf16x8 (&qa)[4][8], const bf16x8 (&kb)[8], floatx16 (&acc)[2],
+                                          const float *cref, float (&z)[4][16], float c1, float lim, int hf)
 {
-    // each head's C operand is read from LDS one head ahead of its use
     floatx16 c_cur = load_cref(cref, 0, hf);
     floatx16 c_nxt = load_cref(cref, 1, hf);
-    acc[0] = chain<0, 4>(qa[0], kb, c_cur);
-    stats_head<EDGE>(acc[1], z[3], cref + 96, c1, first_prev, t_prev, hf, n, T, L, [&] { acc[0] = chain<4, 8>(qa[0], kb, acc[0]); });
+    acc[0] = chain<0, 2>(qa[0], kb, c_cur);
+    if (stats_guard(acc[1], lim)) return STATS_PREV;
+    acc[0] = chain<2, 8>(qa[0], kb, acc[0]);
+    stats_add(acc[1], z[3], c1);
     c_cur = load_cref(cref, 2, hf);
-    acc[1] = chain<0, 4>(qa[1], kb, c_nxt);
-    stats_head<EDGE>(acc[0], z[0], cref, c1, first_cur, t_cur, hf, n, T, L, [&] { acc[1] = chain<4, 8>(qa[1], kb, acc[1]); });
-    c_nxt = load_cref(cref, 3, hf);                          // after head 3 of the previous subtile was reduced
-    acc[0] = chain<0, 4>(qa[2], kb, c_cur);
-    stats_head<EDGE>(acc[1], z[1], cref + 32, c1, first_cur, t_cur, hf, n, T, L, [&] { acc[0] = chain<4, 8>(qa[2], kb, acc[0]); });
-    acc[1] = chain<0, 4>(qa[3], kb, c_nxt);
-    stats_head<EDGE>(acc[0], z[2], cref + 64, c1, first_cur, t_cur, hf, n, T, L, [&] { acc[1] = chain<4, 8>(qa[3], kb, acc[1]); });
+    acc[1] = chain<0, 2>(qa[1], kb, c_nxt);
+    if (stats_guard(acc[0], lim)) return 0;
+    acc[1] = chain<2, 8>(qa[1], kb, acc[1]);
+    stats_add(acc[0], z[0], c1);
+    c_nxt = load_cref(cref, 3, hf);
+    acc[0] = chain<0, 2>(qa[2], kb, c_cur);
+    if (stats_guard(acc[1], lim)) return 1;
+    acc[0] = chain<2, 8>(qa[2], kb, acc[0]);
+    stats_add(acc[1], z[1], c1);
+    acc[1] = chain<0, 2>(qa[3], kb, c_nxt);
+    if (stats_guard(acc[0], lim)) return 2;
+    acc[1] = chain<2, 8>(qa[3], kb, acc[1]);
+    stats_add(acc[0], z[2], c1);
+    return STATS_OK;
+}
+
+// Careful body: heads h_from..3 of the subtile in kb, one after the other, each multiplied afresh against the
+// references as they are now.
+__device__ __forceinline__ void stats_careful(const bf16x8 (&qa)[4][8], const bf16x8 (&kb)[8], float *cref, float (&z)[4][16],
+                                              float c1, int h_from, bool first, int t, int hf, int n, int T, int L)
+{
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        if (h >= h_from) {
+            const floatx16 a = chain<0, 8>(qa[h], kb, load_cref(cref, h, hf));
+            stats_head_careful(a, z[h], cref + 32 * h, c1, first, t, hf, n, T, L);
+        }
+    }
 }
 
 __global__ void __launch_bounds__(WAVES * 64)
@@ -290,15 +351,7 @@ score_mfma_stats(ScoreArgs a)
     ks.prime();
 
     bf16x8 qa[4][8];
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-        const uint16_t *row = a.q + q_row_offset(d, w.p, h, n);
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
-            asm volatile("" : "+a"(qa[h][s]));               // A operands live in accumulation registers
-        }
-    }
+    load_queries(qa, a.q, d, w.p, n, hf);
     cref[lane] = 0.f;
     cref[lane + 64] = 0.f;
 
@@ -309,18 +362,27 @@ score_mfma_stats(ScoreArgs a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) { z[h][i] = 0.f; acc[h & 1][i] = -INFINITY; }
 
-    // acc[1] = -inf makes the "previous subtile" work of the first iteration a no-op
+    // `waiting`: head 3 of subtile u-1 sits in acc[1], multiplied but not yet reduced (never of subtile 0, which
+    // the careful body handles whole).  When nothing waits, acc[1] = -inf makes the fast body's first step add zeros.
+    const float lim = RESCALE_AT / a.c1;
+    bool waiting = false;
     for (int u = 0; u < w.n_sub; ++u) {
         bf16x8 kb[8];
         ks.fetch(u, kb);
-        const int t_cur = w.first + u * STRIDE + n;
-        if (w.first + u * STRIDE + SUB > d.T)
-            stats_body<true>(qa, kb, acc, cref, z, a.c1, u == 1, u == 0, t_cur - STRIDE, t_cur, hf, n, d.T, d.L);
-        else
-            stats_body<false>(qa, kb, acc, cref, z, a.c1, u == 1, u == 0, t_cur - STRIDE, t_cur, hf, n, d.T, d.L);
+        const int t0 = w.first + u * STRIDE;
+        int code = 0;
+        const bool plain = u > 0 && t0 + SUB <= d.T;           // neither the anchoring subtile nor a masked one
+        if (plain) code = stats_fast(qa, kb, acc, cref, z, a.c1, lim, hf);
+        if (code == STATS_OK) { waiting = true; continue; }
+        if (waiting && (!plain || code == STATS_PREV))         // the waiting head was not reduced by the fast body
+            stats_head_careful(acc[1], z[3], cref + 96, a.c1, false, t0 - STRIDE + n, hf, n, d.T, d.L);
+        stats_careful(qa, kb, cref, z, a.c1, (plain && code != STATS_PREV) ? code : 0, u == 0, t0 + n, hf, n, d.T, d.L);
+        waiting = false;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[1][i] = -INFINITY;
     }
-    if (w.n_sub > 0)
-        stats_head<true>(acc[1], z[3], cref + 96, a.c1, w.n_sub == 1, w.first + (w.n_sub - 1) * STRIDE + n, hf, n, d.T, d.L, [] {});
+    if (waiting)
+        stats_head_careful(acc[1], z[3], cref + 96, a.c1, false, w.first + (w.n_sub - 1) * STRIDE + n, hf, n, d.T, d.L);
 
     // ---- per row: add the 32 lane sums (same reference) through the wavefront's ring (every load has landed),
     // then combine the four wavefronts' (reference, sum) pairs
@@ -372,13 +434,21 @@ __device__ __forceinline__ void columns_head(const floatx16 &acc, float (&ab)[16
     }
 }
 
+// x of this lane plus x of the lane 32 away: one swap of the upper half of a register with the lower half of
+// its copy, so both results hold (lower-half value, upper-half value) in every lane
+__device__ __forceinline__ float add_other_half(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // column sum (Eq. st, lane half 0) or entropy term (inner sum of Eq. Dk, lane half 1) from the lane's 16 Abar values
 __device__ __forceinline__ float columns_finish(const float (&ab)[16], float eps, int hf)
 {
     float s_part = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) s_part += ab[i];
-    const float s = s_part + __shfl_xor(s_part, 32);
+    const float s = add_other_half(s_part);
     const float inv_s = s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f;
     float e_part = 0.f;
 #pragma unroll
@@ -386,7 +456,7 @@ __device__ __forceinline__ float columns_finish(const float (&ab)[16], float eps
         const float ah = ab[i] * inv_s;
         e_part = fmaf(ah, __builtin_amdgcn_logf(ah + eps), e_part);
     }
-    const float ent = -LN2 * (e_part + __shfl_xor(e_part, 32));
+    const float ent = -LN2 * add_other_half(e_part);
     return hf == 0 ? s : ent;
 }
 
@@ -463,14 +533,9 @@ score_mfma_columns(ScoreArgs a)
     bf16x8 qa[4][8];
     floatx16 cinit[4], acc[2];
     const float inv_c1 = 1.0f / a.c1;
+    load_queries(qa, a.q, d, w.p, n, hf);
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-        const uint16_t *row = a.q + q_row_offset(d, w.p, h, n);
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
-            asm volatile("" : "+a"(qa[h][s]));               // A operands live in accumulation registers
-        }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             cinit[h][i] = -lse2[h * 32 + query_of(i, hf)] * inv_c1;

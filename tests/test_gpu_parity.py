@@ -253,6 +253,39 @@ def test_mfma_score_long_ragged_with_heavy_rows(oracle, torch_cuda):
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
 
+def test_mfma_score_reference_moves_for_every_head(oracle, torch_cuda, monkeypatch):
+    # Keys planted along chosen query rows give those rows logits far above (> 50 nats) everything seen before,
+    # so the row's running reference has to move in the middle of a wavefront's stream: for each of the four
+    # heads of a group, for two heads in one subtile, twice for one row, in the last subtile of a workgroup's
+    # chunk, in a chunk's first subtile and inside the observation window.  Chunks of 4096 keys make every
+    # wavefront loop over 32 subtiles although there are only two problems.
+    torch = torch_cuda
+    monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "4096")
+    L, W, D, G, Hkv = 3 * 4096 + 77 + 32, 32, 128, 4, 2
+    T = L - W
+    q = synth.normal_torch(515, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(515, 2, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(515, 3, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    plants = [  # (kv head, head in group, window query, key position, scale)
+        (0, 3, 4, 133, 5.0), (0, 0, 5, 700, 5.0), (0, 1, 6, 1500, 5.0), (0, 2, 7, 2300, 5.0),
+        (0, 0, 5, 2000, 9.0),                       # the row of the plant at 700 moves again
+        (1, 0, 1, 3000, 5.0), (1, 2, 2, 3001, 5.0), # two heads in one subtile
+        (1, 3, 9, 4070, 5.0),                       # last subtile of chunk 0
+        (1, 1, 11, 4096 + 40, 5.0),                 # first subtile of a wavefront in chunk 1
+        (0, 2, 20, T + 10, 5.0), (1, 3, 31, 9000, 6.0), (1, 3, 30, 9130, 6.0),
+    ]
+    for g, h, i, t, scale in plants:
+        k[0, 0, g, t, :] = (q[0, 0, g * G + h, i, :].float() * scale).to(torch.bfloat16)
+    off = synth.segment_offsets(7, T, mean=48.0, min_len=1, max_len=300)
+    w = synth.Workload("moves", 0, 1, 1, G * Hkv, Hkv, D, L, W, "bf16", (1, 2, 4, 8, 16, 32), (512,), (48.0,))
+    run = H.GpuRun(q, k, v, off, [0, len(off)], w.cand, w.budget())
+    assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
+    for g, h, i, t, scale in plants:                 # a planted key takes (almost) all of its row: Abar = 1/G
+        if t < T and t != 700:                       # (the plant at 700 loses its row to the one at 2000)
+            assert run.s[g, t] > 0.99 / G
+    _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
+
+
 def test_mfma_score_many_problems_and_groups(oracle, torch_cuda):
     # several launch groups (P = 24 problems of 5000 keys), ragged tail, two sequences with their own segments
     torch = torch_cuda
