@@ -547,21 +547,29 @@ score_mfma_columns(ScoreArgs a)
     for (int i = 0; i < 16; ++i) ab[i] = 0.f;
     float *out = (hf == 0 ? a.s_out : a.e_out) + (int64_t)w.p * d.L;
 
-    // results are stored one iteration late, at the top of the loop, so that the multiply/exponentiate
-    // section of an iteration is a single straight-line region
+    // Results are stored one iteration late, at the top of the next iteration, so that the multiply/exponentiate
+    // section of an iteration is a single straight-line region.  The subtiles before the window (no mask) and
+    // the ones that touch the window or the end of the sequence run in two consecutive loops, which keeps the
+    // masked body and its control-flow joins out of the hot loop.
     float pending = 0.f;
     int pending_t = -1;
-    for (int u = 0; u < w.n_sub; ++u) {
+    const int n_plain = w.first + SUB <= d.T ? min(w.n_sub, (d.T - SUB - w.first) / STRIDE + 1) : 0;
+    int u = 0;
+    for (; u < n_plain; ++u) {
+        if (pending_t >= 0) out[pending_t] = pending;
+        bf16x8 kb[8];
+        ks.fetch(u, kb);
+        const int t_cur = w.first + u * STRIDE + n;
+        pending = columns_body<false>(qa, kb, cinit, acc, ab, a.c1, a.eps, t_cur - STRIDE, t_cur, hf, d.T, d.L);
+        pending_t = u > 0 ? t_cur - STRIDE : -1;
+    }
+    for (; u < w.n_sub; ++u) {
         if (pending_t >= 0 && pending_t < d.L) out[pending_t] = pending;
         bf16x8 kb[8];
         ks.fetch(u, kb);
         const int t_cur = w.first + u * STRIDE + n;
-        const int t_prev = t_cur - STRIDE;
-        if (w.first + u * STRIDE + SUB > d.T)
-            pending = columns_body<true>(qa, kb, cinit, acc, ab, a.c1, a.eps, t_prev, t_cur, hf, d.T, d.L);
-        else
-            pending = columns_body<false>(qa, kb, cinit, acc, ab, a.c1, a.eps, t_prev, t_cur, hf, d.T, d.L);
-        pending_t = u > 0 ? t_prev : -1;
+        pending = columns_body<true>(qa, kb, cinit, acc, ab, a.c1, a.eps, t_cur - STRIDE, t_cur, hf, d.T, d.L);
+        pending_t = u > 0 ? t_cur - STRIDE : -1;
     }
     if (pending_t >= 0 && pending_t < d.L) out[pending_t] = pending;
     if (w.n_sub > 0) {
