@@ -4,16 +4,22 @@
 // topb_kernel     one workgroup per problem: LDS radix select (11+11+10 bits) of
 //                 the min(B,T)-th best score, ties resolved by ascending index.
 //                 Result: (ordered key v, index cut c); token t is in T_topB iff
-//                 key(t) > v or (key(t) == v and t <= c).
-// seg_count_kernel  one thread per token: every Top-B token adds 1 to its segment's b_k.
-// heavy_list_kernel one workgroup per problem: segments with b_k >= 2 are listed (only
-//                 they need a search; b_k == 1 means g_k* = 1, b_k == 0 means g_k* = 0).
-// search_kernel   one wavefront per listed (problem, segment): Score_base, then the
-//                 candidates largest first.
-// seg_prefix_kernel one workgroup per problem: prefix sum of b_k (output offsets) and the
-//                 list of segments that retain anything.
-// select_kernel   one wavefront per listed (problem, segment): T_k(g_k*) written in
+//                 key(t) > v or (key(t) == v and t <= c).  Its last phase counts
+//                 the Top-B tokens of every segment: the implicit budgets b_k.
+// heavy_list_kernel one workgroup per problem: segments with b_k >= 2 are appended to
+//                 ONE list for the whole call (only they need a search; b_k == 1
+//                 means g_k* = 1, b_k == 0 means g_k* = 0).
+// search_kernel   wavefronts stride over that list: Score_base of a segment, then
+//                 the candidates largest first.
+// seg_prefix_kernel one workgroup per problem: prefix sum of b_k (output offsets); the
+//                 segments that retain anything are appended to one of two lists for
+//                 the call: token-level ones (g_k* = 1) and the others.
+// select_light_kernel sixteen lanes per token-level segment: its Top-B tokens in order.
+// select_kernel   wavefronts stride over the other list: T_k(g_k*) written in
 //                 ascending order at the segment's offset.
+// A list entry carries everything its consumer needs (problem, segment bounds, budget,
+// block size, output offset), so a consumer starts with one 32-byte load; the lists
+// are filled through one atomic counter per call, their order does not matter.
 //
 // All quantities that decide an integer (block sums Phi, Score_k(g), Score_base,
 // tau * Score_base) are fp64 and summed in ascending token order, one addition at
@@ -24,7 +30,16 @@
 namespace sablock {
 namespace {
 
-constexpr int WAVES = 1;            // wavefronts (segments) per workgroup in search/select: a slow segment holds no others back
+// one unit of work of search_kernel / select_kernel
+struct __attribute__((aligned(32))) SegRec {
+    int32_t p, k;        // problem, segment
+    int32_t a, b;        // token range of the segment
+    int32_t bk;          // implicit budget b_k
+    int32_t g;           // select: block size g_k*;  search: ordered key of the Top-B threshold
+    int32_t pos;         // select: offset of the segment's tokens in the problem's idx_out row;  search: index cut
+    int32_t pad;
+};
+
 constexpr int CAPB = 512;           // blocks per segment whose Phi/class fit the wave's LDS slice
 constexpr int CAPT = 1024;          // tokens per segment whose scores are staged in the wave's LDS slice
 constexpr int MAX_G = 64;           // largest candidate block size
@@ -53,11 +68,63 @@ __device__ inline double add_in_order(double acc, unsigned long long mask, float
 
 // ------------------------------------------------------------------ Top-B
 constexpr int TB_THREADS = 1024;
+constexpr int TB_OFFS = 4096;              // segment offsets and per-segment counts kept in LDS while the implicit budgets are counted
+constexpr int TB_HITS = 4096;              // Top-B tokens collected in LDS before they are assigned to segments
 
+__device__ inline bool in_topb(float v, int t, uint32_t thr_key, int thr_cut)
+{
+    const uint32_t key = ordered_key(v);
+    return key > thr_key || (key == thr_key && t <= thr_cut);
+}
+
+// segment of token t: the k with seg_off[k] <= t < seg_off[k+1], 0 <= k < K
+__device__ inline int segment_of(const int32_t *off, int K, int t)
+{
+    int lo = 0, hi = K;                       // invariant: off[lo] <= t < off[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (off[mid] <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// f(t, s_tilde[t]) for every token of a row, in no particular order: 16-byte loads, four in flight per thread
+// (the passes over a row are latency-bound), scalar loads for the unaligned head and the tail
+template <typename F>
+__device__ inline void scan_row(const float *sp, int T, int tid, F &&f)
+{
+    const int head = min(T, (int)(((16u - (uint32_t)((uintptr_t)sp & 15u)) & 15u) >> 2));
+    const int nvec = (T - head) >> 2;
+    const float4 *vp = reinterpret_cast<const float4 *>(sp + head);
+    for (int i0 = tid; i0 < nvec; i0 += 4 * TB_THREADS) {
+        float4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { const int i = i0 + j * TB_THREADS; v[j] = vp[i < nvec ? i : nvec - 1]; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = i0 + j * TB_THREADS;
+            if (i < nvec) {
+                const int t = head + 4 * i;
+                f(t, v[j].x); f(t + 1, v[j].y); f(t + 2, v[j].z); f(t + 3, v[j].w);
+            }
+        }
+    }
+    if (tid < head) f(tid, sp[tid]);
+    const int t_tail = head + 4 * nvec + tid;
+    if (t_tail < T) f(t_tail, sp[t_tail]);
+}
+
+// grid (P).  With seg_budget != NULL the kernel also clears the problem's seg_budget / block_size rows, counts
+// the implicit budgets (Eq. implicit_budget) into seg_budget, and workgroup 0 clears `counter`.
 __global__ void __launch_bounds__(TB_THREADS)
-topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, int32_t *zero_a, int32_t *zero_b, int row_len)
+topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, int32_t *seg_budget,
+            int32_t *block_size, int32_t *counter)
 {
     __shared__ uint32_t hist[2048];
+    __shared__ int32_t sh_off[TB_OFFS];
+    __shared__ int32_t sh_cnt[TB_OFFS];
+    __shared__ int32_t sh_hit[TB_HITS];
+    __shared__ int sh_nhit;
     __shared__ uint32_t sh_bin, sh_above;
     __shared__ int sh_wcnt[TB_THREADS / 64];
     __shared__ int sh_cut;
@@ -65,30 +132,28 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, int32_t *zer
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *sp = s_tilde + (int64_t)p * T;
     const int k = min(budget, T);
-    if (zero_a) {            // the search counts into / writes these rows later in the stream
-        for (int i = tid; i < row_len; i += TB_THREADS) { zero_a[(int64_t)p * row_len + i] = 0; zero_b[(int64_t)p * row_len + i] = 0; }
+    const int64_t row = (int64_t)p * sv.max_segments;
+    if (seg_budget) {
+        for (int i = tid; i < sv.max_segments; i += TB_THREADS) { seg_budget[row + i] = 0; block_size[row + i] = 0; }
+        if (counter && p == 0 && tid == 0) *counter = 0;
     }
-    if (k <= 0) { if (tid == 0) { thr[2 * p] = (int32_t)0xFFFFFFFFu; thr[2 * p + 1] = -1; } return; }
-    if (k >= T) { if (tid == 0) { thr[2 * p] = 0; thr[2 * p + 1] = T - 1; } return; }
 
-    uint32_t prefix = 0, mask = 0, krem = (uint32_t)k, n_eq = 0;
+    uint32_t prefix = 0, mask = 0, krem = (uint32_t)max(k, 0), n_eq = 0;
+    int cut = T - 1;
+    if (k <= 0) {
+        prefix = 0xFFFFFFFFu;                 // nothing is inside
+        cut = -1;
+    } else if (k < T) {
     const int shifts[3] = {21, 10, 0};
     const int bits[3] = {11, 11, 10};
     for (int pass = 0; pass < 3; ++pass) {
         const int nbins = 1 << bits[pass], shift = shifts[pass];
         for (int i = tid; i < nbins; i += TB_THREADS) hist[i] = 0;
         __syncthreads();
-        // eight independent loads in flight per thread: the pass is latency-bound otherwise
-        for (int t0 = tid; t0 < T; t0 += 8 * TB_THREADS) {
-            float v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) { const int t = t0 + j * TB_THREADS; v[j] = sp[t < T ? t : T - 1]; }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t key = ordered_key(v[j]);
-                if (t0 + j * TB_THREADS < T && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (nbins - 1)], 1u);
-            }
-        }
+        scan_row(sp, T, tid, [&](int, float v) {
+            const uint32_t key = ordered_key(v);
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (nbins - 1)], 1u);
+        });
         __syncthreads();
         if (wave == 0) {
             // position r counts bins from the top: r = nbins-1-bin; lane owns `per` consecutive positions
@@ -120,7 +185,6 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, int32_t *zer
         __syncthreads();
     }
     // prefix is the key v of the k-th best score; krem of its n_eq ties are inside, lowest indices first
-    int cut = T - 1;
     if (krem < n_eq) {
         int seen = 0;
         for (int c0 = 0; c0 < T; c0 += TB_THREADS) {
@@ -138,7 +202,39 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, int32_t *zer
             seen += total;
         }
     }
+    }   // k < T; for k >= T everything is inside: key 0 is below every score's key, cut = T - 1
     if (tid == 0) { thr[2 * p] = (int32_t)prefix; thr[2 * p + 1] = cut; }
+    if (!seg_budget || k <= 0) return;
+
+    // implicit budgets: every Top-B token adds one to its segment (rows cleared above; the barrier below orders
+    // the clearing stores of all wavefronts before the first atomic)
+    __syncthreads();
+    const int seq = seq_of_problem(d, p);
+    const int32_t *off = sv.seg_off + sv.seq_ptr[seq];
+    const int K = sv.seq_ptr[seq + 1] - sv.seq_ptr[seq] - 1;
+    if (k >= T) {
+        for (int j = tid; j < K; j += TB_THREADS) seg_budget[row + j] = off[j + 1] - off[j];
+        return;
+    }
+    // Fast path (offsets fit in LDS, at most TB_HITS Top-B tokens): the row pass only collects the Top-B tokens;
+    // they are then assigned to segments in parallel (binary search on the LDS copy of the offsets, LDS counters)
+    // and the counts are written out.  Otherwise every Top-B token adds to the cleared row in global memory.
+    if (K + 1 <= TB_OFFS && k <= TB_HITS) {
+        for (int j = tid; j <= K; j += TB_THREADS) { sh_off[j] = off[j]; sh_cnt[j] = 0; }
+        if (tid == 0) sh_nhit = 0;
+        __syncthreads();
+        scan_row(sp, T, tid, [&](int t, float v) {
+            if (in_topb(v, t, prefix, cut)) sh_hit[atomicAdd(&sh_nhit, 1)] = t;      // exactly k of them
+        });
+        __syncthreads();
+        for (int i = tid; i < sh_nhit; i += TB_THREADS) atomicAdd(&sh_cnt[segment_of(sh_off, K, sh_hit[i])], 1);
+        __syncthreads();
+        for (int j = tid; j < K; j += TB_THREADS) seg_budget[row + j] = sh_cnt[j];
+    } else {
+        scan_row(sp, T, tid, [&](int t, float v) {
+            if (in_topb(v, t, prefix, cut)) atomicAdd(&seg_budget[row + segment_of(off, K, t)], 1);
+        });
+    }
 }
 
 // ------------------------------------------------------------------ one segment, one block size
@@ -218,7 +314,30 @@ __device__ inline void segment_fill(V val, int a, int b, int g, int bk, WaveScra
 
     // classify blocks; remember the cut block
     int mp_local = -1;
-    if (fast) {
+    const int picks = rstar + (rem > 0 ? 1 : 0);           // blocks to single out when rstar < nb
+    if (fast && rstar < nb && (picks <= 8 || picks * 512 <= nb * nb)) {
+        // few blocks are taken: pick them one by one, best first (sum descending, index ascending), instead of
+        // ranking every block against every other
+        for (int m = lane; m < nb; m += 64) ws.cls[m] = 0;
+        __builtin_amdgcn_wave_barrier();
+        for (int sel = 0; sel < picks; ++sel) {
+            double bp = -INFINITY;
+            int bm = 0x7fffffff;
+            for (int m = lane; m < nb; m += 64) {
+                const double pm = ws.phi[m];
+                if (ws.cls[m] == 0 && (pm > bp || (pm == bp && m < bm))) { bp = pm; bm = m; }
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const double op = __shfl_xor(bp, o);
+                const int om = __shfl_xor(bm, o);
+                if (op > bp || (op == bp && om < bm)) { bp = op; bm = om; }
+            }
+            if (lane == 0) ws.cls[bm] = sel < rstar ? 1 : 2;
+            if (sel == rstar) mp_local = bm;
+            __builtin_amdgcn_wave_barrier();
+        }
+    } else if (fast) {
         for (int m = lane; m < nb; m += 64) {
             int rk = (rstar >= nb) ? 0 : block_rank(val, a, b, g, nb, m, ws.phi[m], ws.phi, true);
             uint8_t c = (rk < rstar) ? 1 : ((rk == rstar && rem > 0) ? 2 : 0);
@@ -276,65 +395,21 @@ __device__ inline void segment_fill(V val, int a, int b, int g, int bk, WaveScra
     __builtin_amdgcn_wave_barrier();
 }
 
-__device__ inline bool in_topb(float v, int t, uint32_t thr_key, int thr_cut)
-{
-    const uint32_t key = ordered_key(v);
-    return key > thr_key || (key == thr_key && t <= thr_cut);
-}
-
 // ------------------------------------------------------------------ search
-// segment of token t: the k with seg_off[k] <= t < seg_off[k+1], 0 <= k < K
-__device__ inline int segment_of(const int32_t *off, int K, int t)
-{
-    int lo = 0, hi = K;                       // invariant: off[lo] <= t < off[hi]
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (off[mid] <= t) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-// implicit budgets (Eq. implicit_budget): grid (ceil(T / (256 * 8)), P); seg_budget rows are zero on entry.
-// A workgroup covers 2048 consecutive tokens; the segments they fall in form a short range that is located once
-// per workgroup, so a Top-B token finds its segment in a few steps.
+// One workgroup per problem: g_k* = 1 where b_k == 1 (the rows are zero elsewhere), and the segments with
+// b_k >= 2 are appended to the call's search list.
 __global__ void __launch_bounds__(256)
-seg_count_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, int32_t *seg_budget)
+heavy_list_kernel(Dims d, SegView sv, const int32_t *thr, const int32_t *seg_budget, int32_t *block_size,
+                  SegRec *list, int32_t *counter, int capacity)
 {
-    __shared__ int sh_range[2];
-    const int p = blockIdx.y, T = d.T;
-    const float *sp = s_tilde + (int64_t)p * T;
-    const uint32_t thr_key = (uint32_t)thr[2 * p];
-    const int thr_cut = thr[2 * p + 1];
+    __shared__ int sh_w[4];
+    __shared__ int sh_base;
+    const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = seq_of_problem(d, p);
     const int32_t *off = sv.seg_off + sv.seq_ptr[seq];
     const int K = sv.seq_ptr[seq + 1] - sv.seq_ptr[seq] - 1;
-    const int base_t = blockIdx.x * (256 * 8);
-    if (threadIdx.x < 2) sh_range[threadIdx.x] = segment_of(off, K, threadIdx.x == 0 ? base_t : min(base_t + 256 * 8, T) - 1);
-    const int t0 = base_t + threadIdx.x;
-    float v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { const int t = t0 + j * 256; v[j] = sp[t < T ? t : T - 1]; }
-    __syncthreads();
-    const int k_lo = sh_range[0], k_hi = sh_range[1] + 1;          // off[k_lo] <= t < off[k_hi] for every token here
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int t = t0 + j * 256;
-        if (t < T && in_topb(v[j], t, thr_key, thr_cut))
-            atomicAdd(&seg_budget[(int64_t)p * sv.max_segments + k_lo + segment_of(off + k_lo, k_hi - k_lo, t)], 1);
-    }
-}
-
-// one workgroup per problem: ordered list of the segments with b_k >= 2, and g_k* = 1 where b_k == 1
-__global__ void __launch_bounds__(256)
-heavy_list_kernel(Dims d, SegView sv, const int32_t *seg_budget, int32_t *block_size, int32_t *heavy,
-                  int32_t *n_heavy, int max_heavy)
-{
-    __shared__ int sh_w[4];
-    const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int seq = seq_of_problem(d, p);
-    const int K = sv.seq_ptr[seq + 1] - sv.seq_ptr[seq] - 1;
     const int64_t row = (int64_t)p * sv.max_segments;
-    int carry = 0;
+    const int32_t thr_key = thr[2 * p], thr_cut = thr[2 * p + 1];
     for (int c0 = 0; c0 < K; c0 += 256) {
         const int k = c0 + tid;
         const int bk = k < K ? seg_budget[row + k] : 0;
@@ -345,38 +420,37 @@ heavy_list_kernel(Dims d, SegView sv, const int32_t *seg_budget, int32_t *block_
         __syncthreads();
         int before = 0, total = 0;
         for (int w = 0; w < 4; ++w) { if (w < wave) before += sh_w[w]; total += sh_w[w]; }
-        const int pos = carry + before + __popcll(bal & ((1ull << lane) - 1ull));
-        if (hv && pos < max_heavy) heavy[(int64_t)p * max_heavy + pos] = k;
-        carry += total;
+        if (tid == 0 && total > 0) sh_base = atomicAdd(counter, total);
         __syncthreads();
+        const int pos = sh_base + before + __popcll(bal & ((1ull << lane) - 1ull));
+        if (hv && pos < capacity) {
+            SegRec r;
+            r.p = p; r.k = k; r.a = off[k]; r.b = off[k + 1]; r.bk = bk; r.g = thr_key; r.pos = thr_cut; r.pad = 0;
+            list[pos] = r;
+        }
     }
-    if (tid == 0) n_heavy[p] = min(carry, max_heavy);
 }
 
-// grid (SEARCH_GRID, P), one wavefront each, striding over the problem's list of segments with b_k >= 2
-constexpr int SEARCH_GRID = 1024;
+// one wavefront per workgroup, striding over the call's search list
+constexpr int SEARCH_WGS = 65536;
 
 __global__ void __launch_bounds__(64)
-search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau, const int32_t *thr,
-              const int32_t *heavy, const int32_t *n_heavy, int max_heavy, const int32_t *seg_budget,
-              int32_t *block_size)
+search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau,
+              const SegRec *list, const int32_t *counter, int capacity, int32_t *block_size)
 {
     __shared__ double sh_phi[CAPB];
     __shared__ float sh_val[CAPT];
     __shared__ uint8_t sh_cls[CAPB];
-    const int p = blockIdx.y;
     const int lane = threadIdx.x;
-    const int n_list = n_heavy[p];
-    for (int j = blockIdx.x; j < n_list; j += gridDim.x) {
-    const int k = heavy[(int64_t)p * max_heavy + j];
-    const int seq = seq_of_problem(d, p);
-    const int sbase = sv.seq_ptr[seq];
-    const int64_t o = (int64_t)p * sv.max_segments + k;
-    const int a = sv.seg_off[sbase + k], b = sv.seg_off[sbase + k + 1];
-    const int bk = seg_budget[o];
+    int j = blockIdx.x;                                     // < capacity: the grid is no larger than the list can get
+    SegRec r = list[j];                                     // fetched together with the list length
+    const int n_list = min(*counter, capacity);
+    for (; j < n_list; j += gridDim.x, r = list[min(j, capacity - 1)]) {
+    const int p = r.p, a = r.a, b = r.b, bk = r.bk;
+    const int64_t o = (int64_t)p * sv.max_segments + r.k;
     const float *sp = s_tilde + (int64_t)p * d.T;
-    const uint32_t thr_key = (uint32_t)thr[2 * p];
-    const int thr_cut = thr[2 * p + 1];
+    const uint32_t thr_key = (uint32_t)r.g;
+    const int thr_cut = r.pos;
 
     // token-level baseline Score_base = sum over T_topB & S_k, ascending; segments that fit are copied to LDS
     // on the way so that the candidate loop never goes back to global memory
@@ -418,65 +492,113 @@ search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau
 }
 
 // ------------------------------------------------------------------ select
-// exclusive prefix of b_k over the segments of one problem, the ordered list of segments that retain anything,
-// n_sel and the -1 padding of idx_out
-__global__ void __launch_bounds__(256)
-seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *block_size, int budget, int32_t *prefix,
-                  int32_t *act, int32_t *n_act, int max_act, int32_t *idx_out, int32_t *n_sel_out)
+__global__ void reset_counters_kernel(int32_t *counters)
 {
-    __shared__ int sh_w[4], sh_a[4];
-    int carry_a = 0;
+    if (threadIdx.x < 2) counters[threadIdx.x] = 0;
+}
+
+// One workgroup per problem: exclusive prefix of b_k over its segments (where each segment's tokens go in the
+// problem's idx_out row), n_sel, the -1 padding of idx_out.  The segments that retain anything are appended to
+// one of the call's two select lists: token-level ones (g_k* = 1) to `light`, the others to `full`.
+// counters[0] / counters[1] are the lengths of light / full.
+__global__ void __launch_bounds__(256)
+seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *block_size, int budget,
+                  SegRec *light, SegRec *full, int32_t *counters, int capacity, int32_t *idx_out, int32_t *n_sel_out)
+{
+    __shared__ int sh_w[4], sh_l[4], sh_f[4];
+    __shared__ int sh_base[2];
     const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = seq_of_problem(d, p);
+    const int32_t *off = sv.seg_off + sv.seq_ptr[seq];
     const int K = sv.seq_ptr[seq + 1] - sv.seq_ptr[seq] - 1;
-    const int32_t *bp = seg_budget + (int64_t)p * sv.max_segments;
-    int32_t *pp = prefix + (int64_t)p * sv.max_segments;
+    const int64_t row = (int64_t)p * sv.max_segments;
+    const unsigned long long lt = (1ull << lane) - 1ull;
     int carry = 0;
     for (int c0 = 0; c0 < K; c0 += 256) {
         const int k = c0 + tid;
-        const int v = (k < K) ? bp[k] : 0;
-        const bool active = v > 0 && block_size[(int64_t)p * sv.max_segments + (k < K ? k : 0)] > 0;
-        const unsigned long long bal = __ballot(active);
+        const int v = (k < K) ? seg_budget[row + k] : 0;
+        const int g = (k < K) ? block_size[row + k] : 0;
+        const bool is_light = v > 0 && g == 1, is_full = v > 0 && g > 1;
+        const unsigned long long bl = __ballot(is_light), bf = __ballot(is_full);
         int incl = v;
-        for (int off = 1; off < 64; off <<= 1) { int o = __shfl_up(incl, off); if (lane >= off) incl += o; }
+        for (int o = 1; o < 64; o <<= 1) { int x = __shfl_up(incl, o); if (lane >= o) incl += x; }
         if (lane == 63) sh_w[wave] = incl;
-        if (lane == 0) sh_a[wave] = __popcll(bal);
+        if (lane == 0) { sh_l[wave] = __popcll(bl); sh_f[wave] = __popcll(bf); }
         __syncthreads();
-        int before = 0, total = 0, before_a = 0, total_a = 0;
+        int before = 0, total = 0, before_l = 0, total_l = 0, before_f = 0, total_f = 0;
         for (int w = 0; w < 4; ++w) {
-            if (w < wave) { before += sh_w[w]; before_a += sh_a[w]; }
-            total += sh_w[w]; total_a += sh_a[w];
+            if (w < wave) { before += sh_w[w]; before_l += sh_l[w]; before_f += sh_f[w]; }
+            total += sh_w[w]; total_l += sh_l[w]; total_f += sh_f[w];
         }
-        if (k < K) pp[k] = carry + before + incl - v;
-        const int pa = carry_a + before_a + __popcll(bal & ((1ull << lane) - 1ull));
-        if (active && pa < max_act) act[(int64_t)p * max_act + pa] = k;
-        carry += total;
-        carry_a += total_a;
+        if (tid == 0 && total_l > 0) sh_base[0] = atomicAdd(&counters[0], total_l);
+        if (tid == 1 && total_f > 0) sh_base[1] = atomicAdd(&counters[1], total_f);
         __syncthreads();
+        if (is_light || is_full) {
+            const int slot = is_light ? sh_base[0] + before_l + __popcll(bl & lt) : sh_base[1] + before_f + __popcll(bf & lt);
+            if (slot < capacity) {
+                SegRec r;
+                r.p = p; r.k = k; r.a = off[k]; r.b = off[k + 1]; r.bk = v; r.g = g; r.pos = carry + before + incl - v; r.pad = 0;
+                (is_light ? light : full)[slot] = r;
+            }
+        }
+        carry += total;
     }
     const int n = min(carry, budget);
-    if (tid == 0) { n_sel_out[p] = n; n_act[p] = min(carry_a, max_act); }
+    if (tid == 0) n_sel_out[p] = n;
     for (int j = n + tid; j < budget; j += 256) idx_out[(int64_t)p * budget + j] = -1;
 }
 
-// T_k(g_k*) of one segment, written in ascending order from its offset in idx_out
-__device__ inline void select_segment(const Dims &d, const float *s_tilde, const SegView &sv, const int32_t *thr,
-                                      const int32_t *seg_budget, const int32_t *block_size, const int32_t *prefix,
-                                      int budget, int32_t *idx_out, int p, int k, double (&sh_phi)[WAVES][CAPB],
-                                      float (&sh_val)[WAVES][CAPT], uint8_t (&sh_cls)[WAVES][CAPB])
+// Token-level segments, sixteen lanes each (most retaining segments hold one or two Top-B tokens, so a wavefront
+// per segment would mostly idle): T_k(1) = T_topB & S_k when b_k is the implicit budget, written in ascending
+// order.  A segment whose b_k is something else (a caller's own budgets) is passed on to the full list.
+constexpr int LIGHT_GROUP = 16;
+
+__global__ void __launch_bounds__(256)
+select_light_kernel(Dims d, const float *s_tilde, const int32_t *thr, const SegRec *light, SegRec *full,
+                    int32_t *counters, int capacity, int budget, int32_t *idx_out)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int seq = seq_of_problem(d, p);
-    const int sbase = sv.seq_ptr[seq];
-    const int64_t o = (int64_t)p * sv.max_segments + k;
-    const int a = sv.seg_off[sbase + k], b = sv.seg_off[sbase + k + 1];
-    const int bk = min(seg_budget[o], b - a);
-    int g = block_size[o];
+    const int sub = threadIdx.x & (LIGHT_GROUP - 1);
+    const int j = blockIdx.x * (256 / LIGHT_GROUP) + threadIdx.x / LIGHT_GROUP;       // < capacity rounded up
+    const int n_list = min(counters[0], capacity);
+    if (j >= n_list) return;
+    const SegRec r = light[j];
+    const int p = r.p, a = r.a, b = r.b;
+    const int bk = min(r.bk, b - a);
+    const float *sp = s_tilde + (int64_t)p * d.T;
+    int32_t *out = idx_out + (int64_t)p * budget;
+    const uint32_t thr_key = (uint32_t)thr[2 * p];
+    const int thr_cut = thr[2 * p + 1];
+    const int shift = (threadIdx.x & 63) & ~(LIGHT_GROUP - 1);                          // first lane of this group
+    int cnt = 0;
+    // groups of one wavefront may run different trip counts: ballots are taken over the lanes still in the loop
+    for (int c0 = a; c0 < b; c0 += LIGHT_GROUP) {
+        const int t = c0 + sub;
+        const bool in = t < b && in_topb(sp[t < b ? t : a], t, thr_key, thr_cut);
+        const uint32_t gm = (uint32_t)(__ballot(in) >> shift) & ((1u << LIGHT_GROUP) - 1u);
+        const int slot = cnt + __popc(gm & ((1u << sub) - 1u));
+        if (in && slot < bk && r.pos + slot < budget) out[r.pos + slot] = t;
+        cnt += __popc(gm);
+    }
+    if (cnt != bk && sub == 0) {
+        const int slot = atomicAdd(&counters[1], 1);
+        if (slot < capacity) full[slot] = r;
+    }
+}
+
+// T_k(g_k*) of one listed segment, written in ascending order from its offset in idx_out
+__device__ inline void select_segment(const Dims &d, const float *s_tilde, const int32_t *thr, const SegRec &r,
+                                      int budget, int32_t *idx_out, double (&sh_phi)[CAPB], float (&sh_val)[CAPT],
+                                      uint8_t (&sh_cls)[CAPB])
+{
+    const int lane = threadIdx.x & 63;
+    const int p = r.p, a = r.a, b = r.b;
+    const int bk = min(r.bk, b - a);
+    int g = r.g;
     if (bk <= 0 || g <= 0) return;
     g = min(min(g, MAX_G), bk);
     const float *sp = s_tilde + (int64_t)p * d.T;
     int32_t *out = idx_out + (int64_t)p * budget;
-    int pos = prefix[o];
+    int pos = r.pos;
     const unsigned long long lt = (1ull << lane) - 1ull;
     auto put = [&](int c0, unsigned long long m, float) {
         const int j = pos + __popcll(m & lt);
@@ -506,9 +628,9 @@ __device__ inline void select_segment(const Dims &d, const float *s_tilde, const
             }
         }
     }
-    WaveScratch ws{sh_phi[wave], sh_cls[wave]};
+    WaveScratch ws{sh_phi, sh_cls};
     if (b - a <= CAPT) {
-        float *lv = sh_val[wave];
+        float *lv = sh_val;
         for (int t = a + lane; t < b; t += 64) lv[t - a] = sp[t];
         __builtin_amdgcn_wave_barrier();
         auto val = [lv, a](int t) { return lv[t - a]; };
@@ -519,22 +641,21 @@ __device__ inline void select_segment(const Dims &d, const float *s_tilde, const
     }
 }
 
-// grid (SELECT_GRID, P), one wavefront each, striding over the problem's list of segments that retain anything
-constexpr int SELECT_GRID = 2048;
+// one wavefront per workgroup, striding over the call's select list
+constexpr int SELECT_WGS = 32768;
 
-__global__ void __launch_bounds__(WAVES * 64)
-select_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, const int32_t *seg_budget,
-              const int32_t *block_size, const int32_t *prefix, const int32_t *act, const int32_t *n_act, int max_act,
-              int budget, int32_t *idx_out)
+__global__ void __launch_bounds__(64)
+select_kernel(Dims d, const float *s_tilde, const int32_t *thr, const SegRec *list, const int32_t *counter,
+              int capacity, int budget, int32_t *idx_out)
 {
-    __shared__ double sh_phi[WAVES][CAPB];
-    __shared__ float sh_val[WAVES][CAPT];
-    __shared__ uint8_t sh_cls[WAVES][CAPB];
-    const int p = blockIdx.y;
-    const int n_list = n_act[p];
-    for (int j = blockIdx.x; j < n_list; j += gridDim.x) {
-        select_segment(d, s_tilde, sv, thr, seg_budget, block_size, prefix, budget, idx_out, p,
-                       act[(int64_t)p * max_act + j], sh_phi, sh_val, sh_cls);
+    __shared__ double sh_phi[CAPB];
+    __shared__ float sh_val[CAPT];
+    __shared__ uint8_t sh_cls[CAPB];
+    int j = blockIdx.x;                                     // < capacity: the grid is no larger than the list can get
+    SegRec r = list[j];                                     // fetched together with the list length
+    const int n_list = min(*counter, capacity);
+    for (; j < n_list; j += gridDim.x, r = list[min(j, capacity - 1)]) {
+        select_segment(d, s_tilde, thr, r, budget, idx_out, sh_phi, sh_val, sh_cls);
         __builtin_amdgcn_wave_barrier();                    // the LDS slices are reused by the next segment
     }
 }
@@ -544,22 +665,24 @@ select_kernel(Dims d, const float *s_tilde, SegView sv, const int32_t *thr, cons
 hipError_t launch_topb(const Dims &d, const float *s_tilde, int32_t budget, int32_t *thr, hipStream_t st)
 {
     if (d.P <= 0) return hipSuccess;
-    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr,
-                       (int32_t *)nullptr, (int32_t *)nullptr, 0);
+    SegView none{};
+    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, none,
+                       (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr);
     return hipGetLastError();
 }
 
-static int max_heavy_segments(const Dims &d, int32_t max_segments, int32_t budget)
+// upper bound of the search list: a listed segment holds at least two of the |T_topB| tokens
+static size_t max_heavy_segments(const Dims &d, int32_t max_segments, int32_t budget)
 {
-    const int k = budget < d.T ? budget : d.T;             // |T_topB|; a listed segment holds at least two of them
+    const int k = budget < d.T ? budget : d.T;
     const int h = k / 2 < max_segments ? k / 2 : max_segments;
-    return h > 0 ? h : 0;
+    return (size_t)d.P * (size_t)(h > 0 ? h : 0);
 }
 
 size_t search_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget)
 {
-    const int mh = max_heavy_segments(d, max_segments, budget);
-    return align256((size_t)d.P * 2 * 4) + align256((size_t)d.P * (size_t)(mh > 0 ? mh : 1) * 4) + align256((size_t)d.P * 4);
+    const size_t cap = max_heavy_segments(d, max_segments, budget);
+    return align256((size_t)d.P * 2 * 4) + align256(4) + align256((cap > 0 ? cap : 1) * sizeof(SegRec));
 }
 
 hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
@@ -567,36 +690,36 @@ hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv,
                          void *ws, hipStream_t st)
 {
     if (d.P <= 0 || sv.max_segments <= 0) return hipSuccess;
-    const int mh = max_heavy_segments(d, sv.max_segments, budget);
+    const size_t cap = max_heavy_segments(d, sv.max_segments, budget);
     char *w = static_cast<char *>(ws);
     int32_t *thr = topb_out ? topb_out : reinterpret_cast<int32_t *>(w);
-    int32_t *heavy = reinterpret_cast<int32_t *>(w + align256((size_t)d.P * 2 * 4));
-    int32_t *n_heavy = reinterpret_cast<int32_t *>(w + align256((size_t)d.P * 2 * 4) + align256((size_t)d.P * (size_t)(mh > 0 ? mh : 1) * 4));
-    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, seg_budget,
-                       block_size, sv.max_segments);
+    w += align256((size_t)d.P * 2 * 4);
+    int32_t *counter = reinterpret_cast<int32_t *>(w);
+    w += align256(4);
+    SegRec *list = reinterpret_cast<SegRec *>(w);
+    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, sv, seg_budget,
+                       block_size, counter);
     if (budget > 0 && d.T > 0) {
-        dim3 gc((d.T + 256 * 8 - 1) / (256 * 8), d.P);
-        hipLaunchKernelGGL(seg_count_kernel, gc, dim3(256), 0, st, d, s_tilde, sv, thr, seg_budget);
-        hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(256), 0, st, d, sv, seg_budget, block_size, heavy,
-                           n_heavy, mh);
-        if (mh > 0)
-            hipLaunchKernelGGL(search_kernel, dim3(mh < SEARCH_GRID ? mh : SEARCH_GRID, d.P), dim3(64), 0, st, d, s_tilde, sv, cand, tau, thr, heavy,
-                               n_heavy, mh, seg_budget, block_size);
+        hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(256), 0, st, d, sv, thr, seg_budget, block_size, list,
+                           counter, (int)cap);
+        if (cap > 0)
+            hipLaunchKernelGGL(search_kernel, dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64), 0, st, d,
+                               s_tilde, sv, cand, tau, list, counter, (int)cap, block_size);
     }
     return hipGetLastError();
 }
 
-static int max_active_segments(int32_t max_segments, int32_t budget)
+// upper bound of the select list: a listed segment retains at least one token of its problem's budget
+static size_t max_active_segments(const Dims &d, int32_t max_segments, int32_t budget)
 {
-    const int a = budget < max_segments ? budget : max_segments;   // a listed segment retains at least one token
-    return a > 0 ? a : 1;
+    const int a = budget < max_segments ? budget : max_segments;
+    return (size_t)d.P * (size_t)(a > 0 ? a : 0);
 }
 
 size_t select_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget)
 {
-    const size_t ms = (size_t)(max_segments > 0 ? max_segments : 1);
-    return align256((size_t)d.P * 2 * 4) + align256((size_t)d.P * ms * 4) +
-           align256((size_t)d.P * (size_t)max_active_segments(max_segments, budget) * 4) + align256((size_t)d.P * 4);
+    const size_t cap = max_active_segments(d, max_segments, budget);
+    return align256((size_t)d.P * 2 * 4) + align256(8) + 2 * align256((cap > 0 ? cap : 1) * sizeof(SegRec));
 }
 
 hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv, const int32_t *seg_budget,
@@ -604,28 +727,30 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
                          int32_t *n_sel_out, void *ws, hipStream_t st)
 {
     if (d.P <= 0) return hipSuccess;
-    const size_t ms = (size_t)(sv.max_segments > 0 ? sv.max_segments : 1);
-    const int ma = max_active_segments(sv.max_segments, budget);
+    const size_t cap = max_active_segments(d, sv.max_segments, budget);
     char *w = static_cast<char *>(ws);
     int32_t *thr_ws = reinterpret_cast<int32_t *>(w);
     w += align256((size_t)d.P * 2 * 4);
-    int32_t *prefix = reinterpret_cast<int32_t *>(w);
-    w += align256((size_t)d.P * ms * 4);
-    int32_t *act = reinterpret_cast<int32_t *>(w);
-    w += align256((size_t)d.P * (size_t)ma * 4);
-    int32_t *n_act = reinterpret_cast<int32_t *>(w);
+    int32_t *counters = reinterpret_cast<int32_t *>(w);
+    w += align256(8);
+    SegRec *light = reinterpret_cast<SegRec *>(w);
+    w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
+    SegRec *full = reinterpret_cast<SegRec *>(w);
     const int32_t *thr = topb;
     if (!thr) {
         hipError_t e = launch_topb(d, s_tilde, budget, thr_ws, st);
         if (e != hipSuccess) return e;
         thr = thr_ws;
     }
-    hipLaunchKernelGGL(seg_prefix_kernel, dim3(d.P), dim3(256), 0, st, d, sv, seg_budget, block_size, budget, prefix,
-                       act, n_act, ma, idx_out, n_sel_out);
-    if (sv.max_segments > 0 && budget > 0) {
-        dim3 grid(ma < SELECT_GRID ? ma : SELECT_GRID, d.P);
-        hipLaunchKernelGGL(select_kernel, grid, dim3(WAVES * 64), 0, st, d, s_tilde, sv, thr, seg_budget,
-                           block_size, prefix, act, n_act, ma, budget, idx_out);
+    hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, counters);
+    hipLaunchKernelGGL(seg_prefix_kernel, dim3(d.P), dim3(256), 0, st, d, sv, seg_budget, block_size, budget, light,
+                       full, counters, (int)cap, idx_out, n_sel_out);
+    if (cap > 0) {
+        const unsigned per_wg = 256 / LIGHT_GROUP;
+        hipLaunchKernelGGL(select_light_kernel, dim3((unsigned)((cap + per_wg - 1) / per_wg)), dim3(256), 0, st, d,
+                           s_tilde, thr, light, full, counters, (int)cap, budget, idx_out);
+        hipLaunchKernelGGL(select_kernel, dim3((unsigned)(cap < SELECT_WGS ? cap : SELECT_WGS)), dim3(64), 0, st, d,
+                           s_tilde, thr, full, counters + 1, (int)cap, budget, idx_out);
     }
     return hipGetLastError();
 }

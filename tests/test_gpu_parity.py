@@ -172,6 +172,15 @@ def test_search_select_degenerate_cases(oracle, torch_cuda):
     T2 = 2600
     st2 = rng.random((1, T2)) ** 2
     _assert_search_select(oracle, torch, st2, np.array([0, T2], dtype=np.int32), [1, 2, 4], 700, 0.9)
+    # more segments (6001 offsets) and more Top-B tokens (5000) than the counting kernel keeps in LDS, odd row
+    # length (rows start at every alignment), few score levels (ties at the Top-B boundary)
+    T3 = 6007
+    st3 = np.round(rng.random((3, T3)) ** 4 * 512) / 512.0
+    off3 = np.concatenate([np.arange(0, 6000, dtype=np.int32), [T3]]).astype(np.int32)
+    for budget in (5000, 300):
+        _assert_search_select(oracle, torch, st3, off3, cand, budget, 0.85)
+    off4 = np.unique(np.concatenate([[0, T3], rng.integers(1, T3, size=900)])).astype(np.int32)
+    _assert_search_select(oracle, torch, st3, off4, cand, 5000, 0.85)
 
 
 def test_compact_strided_inputs_bit_exact(oracle, torch_cuda):
