@@ -1,16 +1,21 @@
 // Segment-guided score refinement (Alg. 1; Eqs. Ik, Dk, omegak, st_tilde).
 //
-// Sixteen lanes per (problem, segment), four segments per wavefront: lanes stride over the segment's tokens, the
-// two segment sums are accumulated in fp64 and reduced with shuffles inside the 16-lane group, then every lane
-// rescales its tokens.  Traffic is 12 bytes per token; the kernel is latency-bound (a chain of three dependent
-// memory round trips per segment), so several segments share a wavefront and all problems of a call share one launch.
+// A workgroup owns 16 consecutive segments of one problem, i.e. one contiguous token range.  It first streams
+// the range's scores and entropy terms into LDS with fully coalesced loads (all of a thread's loads in flight
+// at once: the kernel is a chain of a few memory round trips, so it is tuned for latency and occupancy), then
+// sixteen lanes per segment accumulate the two segment sums in fp64 from LDS (shuffle reduction inside the
+// 16-lane group) and rescale the segment's tokens.  Traffic is 12 bytes per token.  A range that does not fit
+// in LDS (very long segments) is read from global memory by the lane groups directly.
 #include "sablock_internal.h"
 
 namespace sablock {
 namespace {
 
 constexpr int GROUP = 16;                  // lanes per segment
-constexpr int NT = 256;                    // threads per workgroup: 16 segments
+constexpr int NT = 256;                    // threads per workgroup: 16 segments at a time
+constexpr int RSEG = NT / GROUP;           // segments per workgroup
+constexpr int RPT = 8;                     // staged tokens per thread
+constexpr int RCAP = RPT * NT;             // tokens per workgroup whose inputs are staged in LDS
 
 __device__ inline double group_sum(double v)
 {
@@ -18,27 +23,52 @@ __device__ inline double group_sum(double v)
     return v;
 }
 
-// grid (ceil(max_segments / 16), P)
+// grid (ceil(max_segments / RSEG), P)
 __global__ void __launch_bounds__(NT)
 refine_kernel(Dims d, const float *s, const float *ent, SegView sv, sablock_hparams hp,
               float *s_tilde, float *omega)
 {
+    __shared__ float sh_s[RCAP], sh_e[RCAP];
     const int p = blockIdx.y;
-    const int sub = threadIdx.x & (GROUP - 1);
-    const int k = blockIdx.x * (NT / GROUP) + threadIdx.x / GROUP;
+    const int sub = threadIdx.x & (GROUP - 1), grp = threadIdx.x / GROUP;
     const int seq = seq_of_problem(d, p);
     const int base = sv.seq_ptr[seq];
     const int K = sv.seq_ptr[seq + 1] - base - 1;
-    if (k >= sv.max_segments) return;
-    if (k >= K) {
-        if (omega && sub == 0) omega[(int64_t)p * sv.max_segments + k] = 0.f;
-        return;
-    }
-    const int a = sv.seg_off[base + k], b = sv.seg_off[base + k + 1];
+    const int k0 = blockIdx.x * RSEG;
+    const int k1 = min(k0 + RSEG, K);
+    // rows of omega are max_segments wide: zero behind the sequence's last segment
+    if (omega)
+        for (int k = max(k0, K) + (int)threadIdx.x; k < min(k0 + RSEG, sv.max_segments); k += NT)
+            omega[(int64_t)p * sv.max_segments + k] = 0.f;
+    if (k0 >= K) return;
     const float *sp = s + (int64_t)p * d.L;
     const float *ep = ent + (int64_t)p * d.L;
+    float *op = s_tilde + (int64_t)p * d.T;
+    // this lane group's segment (its bounds are fetched together with the range's)
+    const int k = k0 + grp;
+    const bool mine = k < k1;
+    const int a = sv.seg_off[base + (mine ? k : k0)], b = sv.seg_off[base + (mine ? k : k0) + 1];
+    const int lo = sv.seg_off[base + k0], hi = sv.seg_off[base + k1];
+    const bool staged = hi - lo <= RCAP;
+    if (staged) {
+        float rs[RPT], re[RPT];
+#pragma unroll
+        for (int j = 0; j < RPT; ++j) {
+            const int t = min(lo + j * NT + (int)threadIdx.x, hi - 1);
+            rs[j] = sp[t];
+            re[j] = ep[t];
+        }
+#pragma unroll
+        for (int j = 0; j < RPT; ++j) {
+            const int i = j * NT + (int)threadIdx.x;
+            if (lo + i < hi) { sh_s[i] = rs[j]; sh_e[i] = re[j]; }
+        }
+        __syncthreads();
+    }
+    if (!mine) return;
     double sum_s = 0.0, sum_e = 0.0;
-    for (int t = a + sub; t < b; t += GROUP) { sum_s += (double)sp[t]; sum_e += (double)ep[t]; }
+    if (staged) for (int t = a + sub; t < b; t += GROUP) { sum_s += (double)sh_s[t - lo]; sum_e += (double)sh_e[t - lo]; }
+    else for (int t = a + sub; t < b; t += GROUP) { sum_s += (double)sp[t]; sum_e += (double)ep[t]; }
     sum_s = group_sum(sum_s);
     sum_e = group_sum(sum_e);
     const double n = (double)(b - a);
@@ -46,8 +76,8 @@ refine_kernel(Dims d, const float *s, const float *ent, SegView sv, sablock_hpar
     const double Dk = sum_e / n;                                   // Eq. Dk
     const double wk = Ik * (1.0 + (double)hp.eta * Dk);            // Eq. omegak
     const double f = 1.0 + (double)hp.alpha * wk;
-    float *op = s_tilde + (int64_t)p * d.T;
-    for (int t = a + sub; t < b; t += GROUP) op[t] = (float)((double)sp[t] * f);   // Eq. st_tilde
+    if (staged) for (int t = a + sub; t < b; t += GROUP) op[t] = (float)((double)sh_s[t - lo] * f);   // Eq. st_tilde
+    else for (int t = a + sub; t < b; t += GROUP) op[t] = (float)((double)sp[t] * f);
     if (omega && sub == 0) omega[(int64_t)p * sv.max_segments + k] = (float)wk;
 }
 
@@ -57,7 +87,7 @@ hipError_t launch_refine(const Dims &d, const float *s, const float *ent, const 
                          sablock_hparams hp, float *s_tilde, float *omega, hipStream_t st)
 {
     if (sv.max_segments <= 0 || d.P <= 0) return hipSuccess;
-    dim3 grid((sv.max_segments + NT / GROUP - 1) / (NT / GROUP), d.P);
+    dim3 grid((sv.max_segments + RSEG - 1) / RSEG, d.P);
     hipLaunchKernelGGL(refine_kernel, grid, dim3(NT), 0, st, d, s, ent, sv, hp, s_tilde, omega);
     return hipGetLastError();
 }

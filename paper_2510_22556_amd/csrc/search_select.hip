@@ -398,11 +398,13 @@ __device__ inline void segment_fill(V val, int a, int b, int g, int bk, WaveScra
 // ------------------------------------------------------------------ search
 // One workgroup per problem: g_k* = 1 where b_k == 1 (the rows are zero elsewhere), and the segments with
 // b_k >= 2 are appended to the call's search list.
-__global__ void __launch_bounds__(256)
+constexpr int LIST_THREADS = 1024;         // threads of the per-problem list-building kernels: segments handled per step
+
+__global__ void __launch_bounds__(LIST_THREADS)
 heavy_list_kernel(Dims d, SegView sv, const int32_t *thr, const int32_t *seg_budget, int32_t *block_size,
                   SegRec *list, int32_t *counter, int capacity)
 {
-    __shared__ int sh_w[4];
+    __shared__ int sh_w[LIST_THREADS / 64];
     __shared__ int sh_base;
     const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = seq_of_problem(d, p);
@@ -410,7 +412,7 @@ heavy_list_kernel(Dims d, SegView sv, const int32_t *thr, const int32_t *seg_bud
     const int K = sv.seq_ptr[seq + 1] - sv.seq_ptr[seq] - 1;
     const int64_t row = (int64_t)p * sv.max_segments;
     const int32_t thr_key = thr[2 * p], thr_cut = thr[2 * p + 1];
-    for (int c0 = 0; c0 < K; c0 += 256) {
+    for (int c0 = 0; c0 < K; c0 += LIST_THREADS) {
         const int k = c0 + tid;
         const int bk = k < K ? seg_budget[row + k] : 0;
         if (k < K && bk == 1) block_size[row + k] = 1;
@@ -419,7 +421,7 @@ heavy_list_kernel(Dims d, SegView sv, const int32_t *thr, const int32_t *seg_bud
         if (lane == 0) sh_w[wave] = __popcll(bal);
         __syncthreads();
         int before = 0, total = 0;
-        for (int w = 0; w < 4; ++w) { if (w < wave) before += sh_w[w]; total += sh_w[w]; }
+        for (int w = 0; w < LIST_THREADS / 64; ++w) { if (w < wave) before += sh_w[w]; total += sh_w[w]; }
         if (tid == 0 && total > 0) sh_base = atomicAdd(counter, total);
         __syncthreads();
         const int pos = sh_base + before + __popcll(bal & ((1ull << lane) - 1ull));
@@ -501,11 +503,11 @@ __global__ void reset_counters_kernel(int32_t *counters)
 // problem's idx_out row), n_sel, the -1 padding of idx_out.  The segments that retain anything are appended to
 // one of the call's two select lists: token-level ones (g_k* = 1) to `light`, the others to `full`.
 // counters[0] / counters[1] are the lengths of light / full.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(LIST_THREADS)
 seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *block_size, int budget,
                   SegRec *light, SegRec *full, int32_t *counters, int capacity, int32_t *idx_out, int32_t *n_sel_out)
 {
-    __shared__ int sh_w[4], sh_l[4], sh_f[4];
+    __shared__ int sh_w[LIST_THREADS / 64], sh_l[LIST_THREADS / 64], sh_f[LIST_THREADS / 64];
     __shared__ int sh_base[2];
     const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = seq_of_problem(d, p);
@@ -514,7 +516,7 @@ seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *
     const int64_t row = (int64_t)p * sv.max_segments;
     const unsigned long long lt = (1ull << lane) - 1ull;
     int carry = 0;
-    for (int c0 = 0; c0 < K; c0 += 256) {
+    for (int c0 = 0; c0 < K; c0 += LIST_THREADS) {
         const int k = c0 + tid;
         const int v = (k < K) ? seg_budget[row + k] : 0;
         const int g = (k < K) ? block_size[row + k] : 0;
@@ -526,7 +528,7 @@ seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *
         if (lane == 0) { sh_l[wave] = __popcll(bl); sh_f[wave] = __popcll(bf); }
         __syncthreads();
         int before = 0, total = 0, before_l = 0, total_l = 0, before_f = 0, total_f = 0;
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < LIST_THREADS / 64; ++w) {
             if (w < wave) { before += sh_w[w]; before_l += sh_l[w]; before_f += sh_f[w]; }
             total += sh_w[w]; total_l += sh_l[w]; total_f += sh_f[w];
         }
@@ -545,7 +547,7 @@ seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *
     }
     const int n = min(carry, budget);
     if (tid == 0) n_sel_out[p] = n;
-    for (int j = n + tid; j < budget; j += 256) idx_out[(int64_t)p * budget + j] = -1;
+    for (int j = n + tid; j < budget; j += LIST_THREADS) idx_out[(int64_t)p * budget + j] = -1;
 }
 
 // Token-level segments, sixteen lanes each (most retaining segments hold one or two Top-B tokens, so a wavefront
@@ -700,7 +702,7 @@ hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv,
     hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, sv, seg_budget,
                        block_size, counter);
     if (budget > 0 && d.T > 0) {
-        hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(256), 0, st, d, sv, thr, seg_budget, block_size, list,
+        hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, thr, seg_budget, block_size, list,
                            counter, (int)cap);
         if (cap > 0)
             hipLaunchKernelGGL(search_kernel, dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64), 0, st, d,
@@ -743,7 +745,7 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
         thr = thr_ws;
     }
     hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, counters);
-    hipLaunchKernelGGL(seg_prefix_kernel, dim3(d.P), dim3(256), 0, st, d, sv, seg_budget, block_size, budget, light,
+    hipLaunchKernelGGL(seg_prefix_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, seg_budget, block_size, budget, light,
                        full, counters, (int)cap, idx_out, n_sel_out);
     if (cap > 0) {
         const unsigned per_wg = 256 / LIGHT_GROUP;
