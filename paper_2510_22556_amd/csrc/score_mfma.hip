@@ -294,25 +294,21 @@ constexpr int STATS_PREV = 3;              // the guard failed for head 3 of the
 // Returns STATS_OK, or which head failed its guard: STATS_PREV, or 0..2 = that head of this subtile (the heads
 // before it were added, it and the ones after it were not).  Head 3 of this subtile is left waiting in acc[1].
 __device__ __forceinline__ int stats_fast(const bf16x8 (&qa)[4][8], const bf16x8 (&kb)[8], floatx16 (&acc)[2],
-                                          const float *cref, float (&z)[4][16], float c1, float lim, int hf)
+                                          const floatx16 (&cr)[4], float (&z)[4][16], float c1, float lim)
 {
-    floatx16 c_cur = load_cref(cref, 0, hf);
-    floatx16 c_nxt = load_cref(cref, 1, hf);
-    acc[0] = chain<0, 2>(qa[0], kb, c_cur);
+    acc[0] = chain<0, 2>(qa[0], kb, cr[0]);
     if (stats_guard(acc[1], lim)) return STATS_PREV;
     acc[0] = chain<2, 8>(qa[0], kb, acc[0]);
     stats_add(acc[1], z[3], c1);
-    c_cur = load_cref(cref, 2, hf);
-    acc[1] = chain<0, 2>(qa[1], kb, c_nxt);
+    acc[1] = chain<0, 2>(qa[1], kb, cr[1]);
     if (stats_guard(acc[0], lim)) return 0;
     acc[1] = chain<2, 8>(qa[1], kb, acc[1]);
     stats_add(acc[0], z[0], c1);
-    c_nxt = load_cref(cref, 3, hf);
-    acc[0] = chain<0, 2>(qa[2], kb, c_cur);
+    acc[0] = chain<0, 2>(qa[2], kb, cr[2]);
     if (stats_guard(acc[1], lim)) return 1;
     acc[0] = chain<2, 8>(qa[2], kb, acc[0]);
     stats_add(acc[1], z[1], c1);
-    acc[1] = chain<0, 2>(qa[3], kb, c_nxt);
+    acc[1] = chain<0, 2>(qa[3], kb, cr[3]);
     if (stats_guard(acc[0], lim)) return 2;
     acc[1] = chain<2, 8>(qa[3], kb, acc[1]);
     stats_add(acc[0], z[2], c1);
@@ -365,6 +361,11 @@ score_mfma_stats(ScoreArgs a)
     // `waiting`: head 3 of subtile u-1 sits in acc[1], multiplied but not yet reduced (never of subtile 0, which
     // the careful body handles whole).  When nothing waits, acc[1] = -inf makes the fast body's first step add zeros.
     const float lim = RESCALE_AT / a.c1;
+    floatx16 cr[4];                                            // the rows' references as MFMA C operands (copy of cref)
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) cr[h][i] = 0.f;
     bool waiting = false;
     for (int u = 0; u < w.n_sub; ++u) {
         bf16x8 kb[8];
@@ -372,7 +373,7 @@ score_mfma_stats(ScoreArgs a)
         const int t0 = w.first + u * STRIDE;
         int code = 0;
         const bool plain = u > 0 && t0 + SUB <= d.T;           // neither the anchoring subtile nor a masked one
-        if (plain) code = stats_fast(qa, kb, acc, cref, z, a.c1, lim, hf);
+        if (plain) code = stats_fast(qa, kb, acc, cr, z, a.c1, lim);
         if (code == STATS_OK) { waiting = true; continue; }
         if (waiting && (!plain || code == STATS_PREV))         // the waiting head was not reduced by the fast body
             stats_head_careful(acc[1], z[3], cref + 96, a.c1, false, t0 - STRIDE + n, hf, n, d.T, d.L);
@@ -380,6 +381,8 @@ score_mfma_stats(ScoreArgs a)
         waiting = false;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[1][i] = -INFINITY;
+#pragma unroll
+        for (int h = 0; h < 4; ++h) cr[h] = load_cref(cref, h, hf);     // the careful body may have moved references
     }
     if (waiting)
         stats_head_careful(acc[1], z[3], cref + 96, a.c1, false, w.first + (w.n_sub - 1) * STRIDE + n, hf, n, d.T, d.L);
