@@ -1,8 +1,9 @@
 // Budget-driven block-size search and selection (Alg. 2; Eqs. topk,
 // implicit_budget, rk, gk_star, final_selection).
 //
-// topb_kernel     one workgroup per problem: LDS radix select (11+11+10 bits) of
-//                 the min(B,T)-th best score, ties resolved by ascending index.
+// topb_kernel     one workgroup per problem: radix select of the min(B,T)-th best
+//                 score (12 bits over the row, then 10 + 10 on an LDS candidate
+//                 list), ties resolved by ascending index.
 //                 Result: (ordered key v, index cut c); token t is in T_topB iff
 //                 key(t) > v or (key(t) == v and t <= c).  Its last phase counts
 //                 the Top-B tokens of every segment: the implicit budgets b_k.
@@ -40,8 +41,8 @@ struct __attribute__((aligned(32))) SegRec {
     int32_t pad;
 };
 
-constexpr int CAPB = 512;           // blocks per segment whose Phi/class fit the wave's LDS slice
-constexpr int CAPT = 1024;          // tokens per segment whose scores are staged in the wave's LDS slice
+constexpr int CAPB = 256;           // blocks per segment whose Phi/class fit the wave's LDS slice
+constexpr int CAPT = 512;          // tokens per segment whose scores are staged in the wave's LDS slice
 constexpr int MAX_G = 64;           // largest candidate block size
 
 __device__ inline int wave_sum_i(int v)
@@ -70,6 +71,7 @@ __device__ inline double add_in_order(double acc, unsigned long long mask, float
 constexpr int TB_THREADS = 1024;
 constexpr int TB_OFFS = 4096;              // segment offsets and per-segment counts kept in LDS while the implicit budgets are counted
 constexpr int TB_HITS = 4096;              // Top-B tokens collected in LDS before they are assigned to segments
+constexpr int TB_CAND = 4096;              // tokens of the threshold's 12-bit bin that the LDS candidate list holds
 
 __device__ inline bool in_topb(float v, int t, uint32_t thr_key, int thr_cut)
 {
@@ -114,20 +116,63 @@ __device__ inline void scan_row(const float *sp, int T, int tid, F &&f)
     if (t_tail < T) f(t_tail, sp[t_tail]);
 }
 
+// Bin of the k-th entry counted from the top bin of hist[0 .. nbins): wavefront 0 scans, everyone gets
+// (bin, entries in the bins above it).  nbins is a multiple of 64.  Ends with a barrier.
+__device__ inline void find_bin_from_top(const uint32_t *hist, int nbins, uint32_t krem, uint32_t *sh_pair,
+                                         uint32_t &bin, uint32_t &above)
+{
+    const int lane = threadIdx.x & 63;
+    if ((threadIdx.x >> 6) == 0) {
+        // position r counts bins from the top: r = nbins-1-bin; lane owns `per` consecutive positions
+        const int per = nbins / 64;
+        uint32_t mine = 0;
+        for (int j = 0; j < per; ++j) mine += hist[nbins - 1 - (lane * per + j)];
+        uint32_t incl = mine;
+        for (int off = 1; off < 64; off <<= 1) {
+            uint32_t o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        const uint32_t excl = incl - mine;
+        if (excl < krem && krem <= incl) {
+            uint32_t run = excl;
+            for (int j = 0; j < per; ++j) {
+                const int bn = nbins - 1 - (lane * per + j);
+                const uint32_t c = hist[bn];
+                if (run + c >= krem) { sh_pair[0] = (uint32_t)bn; sh_pair[1] = run; break; }
+                run += c;
+            }
+        }
+    }
+    __syncthreads();
+    bin = sh_pair[0];
+    above = sh_pair[1];
+}
+
 // grid (P).  With seg_budget != NULL the kernel also clears the problem's seg_budget / block_size rows, counts
 // the implicit budgets (Eq. implicit_budget) into seg_budget, and workgroup 0 clears `counter`.
+//
+// Selection of the k-th best score, k = min(B, T).  Usual path, two passes over the row: a histogram of the
+// keys' top 12 bits locates the bin of the k-th key; the second pass puts the tokens of higher bins straight
+// into the list of Top-B tokens and the tokens of that bin (key, index) into a candidate list in LDS, on which
+// the remaining 20 bits are resolved without touching global memory again.  If the bin holds more candidates
+// than the list (or k exceeds the token list), three histogram passes over the row (11 + 11 + 10 bits) do it.
+// Ties at the threshold are cut by ascending index with one ordered pass over the row.
 __global__ void __launch_bounds__(TB_THREADS)
 topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, int32_t *seg_budget,
             int32_t *block_size, int32_t *counter)
 {
-    __shared__ uint32_t hist[2048];
-    __shared__ int32_t sh_off[TB_OFFS];
-    __shared__ int32_t sh_cnt[TB_OFFS];
-    __shared__ int32_t sh_hit[TB_HITS];
-    __shared__ int sh_nhit;
-    __shared__ uint32_t sh_bin, sh_above;
+    __shared__ uint32_t hist[TB_HITS];           // pass-A histogram (4096 bins), later the list of Top-B tokens
+    __shared__ uint32_t hist2[2048];             // histograms of the later passes
+    __shared__ int32_t sh_u[2 * TB_OFFS];        // candidates (key, index) during selection, then offsets and counters
+    __shared__ int sh_nhit, sh_ncand;
+    __shared__ uint32_t sh_pair[2];
     __shared__ int sh_wcnt[TB_THREADS / 64];
     __shared__ int sh_cut;
+    static_assert(TB_HITS == 4096 && TB_CAND <= TB_OFFS, "LDS regions are shared between phases");
+    int32_t *sh_hit = reinterpret_cast<int32_t *>(hist);
+    uint32_t *cand_key = reinterpret_cast<uint32_t *>(sh_u);
+    int32_t *cand_idx = sh_u + TB_OFFS;
+    int32_t *sh_off = sh_u, *sh_cnt = sh_u + TB_OFFS;
     const int p = blockIdx.x, T = d.T;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *sp = s_tilde + (int64_t)p * T;
@@ -140,74 +185,107 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
 
     uint32_t prefix = 0, mask = 0, krem = (uint32_t)max(k, 0), n_eq = 0;
     int cut = T - 1;
+    bool have_hits = false;                    // sh_hit[0 .. k) holds T_topB
     if (k <= 0) {
-        prefix = 0xFFFFFFFFu;                 // nothing is inside
+        prefix = 0xFFFFFFFFu;                  // nothing is inside
         cut = -1;
     } else if (k < T) {
-    const int shifts[3] = {21, 10, 0};
-    const int bits[3] = {11, 11, 10};
-    for (int pass = 0; pass < 3; ++pass) {
-        const int nbins = 1 << bits[pass], shift = shifts[pass];
-        for (int i = tid; i < nbins; i += TB_THREADS) hist[i] = 0;
+        // ---- pass A: top 12 bits
+        for (int i = tid; i < 4096; i += TB_THREADS) hist[i] = 0;
         __syncthreads();
-        scan_row(sp, T, tid, [&](int, float v) {
-            const uint32_t key = ordered_key(v);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (nbins - 1)], 1u);
-        });
+        scan_row(sp, T, tid, [&](int, float v) { atomicAdd(&hist[ordered_key(v) >> 20], 1u); });
         __syncthreads();
-        if (wave == 0) {
-            // position r counts bins from the top: r = nbins-1-bin; lane owns `per` consecutive positions
-            const int per = nbins / 64;
-            uint32_t mine = 0;
-            for (int j = 0; j < per; ++j) mine += hist[nbins - 1 - (lane * per + j)];
-            uint32_t incl = mine;
-            for (int off = 1; off < 64; off <<= 1) {
-                uint32_t o = __shfl_up(incl, off);
-                if (lane >= off) incl += o;
+        uint32_t bin, above;
+        find_bin_from_top(hist, 4096, krem, sh_pair, bin, above);
+        const uint32_t n_bin = hist[bin];
+        __syncthreads();                       // hist is reused below
+        if (n_bin <= (uint32_t)TB_CAND && k <= TB_HITS) {
+            // ---- pass B: split the row into sure Top-B tokens and candidates
+            if (tid == 0) { sh_nhit = 0; sh_ncand = 0; }
+            __syncthreads();
+            scan_row(sp, T, tid, [&](int t, float v) {
+                const uint32_t key = ordered_key(v);
+                const uint32_t kb = key >> 20;
+                if (kb > bin) sh_hit[atomicAdd(&sh_nhit, 1)] = t;
+                else if (kb == bin) { const int c = atomicAdd(&sh_ncand, 1); cand_key[c] = key; cand_idx[c] = t; }
+            });
+            __syncthreads();
+            const int ncand = sh_ncand;
+            krem -= above;
+            prefix = bin << 20;
+            mask = 0xFFF00000u;
+            // ---- the remaining 20 bits on the candidate list
+            for (int shift = 10; shift >= 0; shift -= 10) {
+                for (int i = tid; i < 1024; i += TB_THREADS) hist2[i] = 0;
+                __syncthreads();
+                for (int c = tid; c < ncand; c += TB_THREADS)
+                    if ((cand_key[c] & mask) == prefix) atomicAdd(&hist2[(cand_key[c] >> shift) & 1023u], 1u);
+                __syncthreads();
+                uint32_t b2, a2;
+                find_bin_from_top(hist2, 1024, krem, sh_pair, b2, a2);
+                krem -= a2;
+                n_eq = hist2[b2];
+                prefix |= b2 << shift;
+                mask |= 1023u << shift;
+                __syncthreads();
             }
-            uint32_t excl = incl - mine;
-            if (excl < krem && krem <= incl) {
-                uint32_t run = excl;
-                for (int j = 0; j < per; ++j) {
-                    int bin = nbins - 1 - (lane * per + j);
-                    uint32_t c = hist[bin];
-                    if (run + c >= krem) { sh_bin = (uint32_t)bin; sh_above = run; break; }
-                    run += c;
-                }
+            have_hits = true;
+        } else {
+            // ---- three histogram passes over the row
+            const int shifts[3] = {21, 10, 0};
+            const int bits[3] = {11, 11, 10};
+            for (int pass = 0; pass < 3; ++pass) {
+                const int nbins = 1 << bits[pass], shift = shifts[pass];
+                for (int i = tid; i < nbins; i += TB_THREADS) hist2[i] = 0;
+                __syncthreads();
+                scan_row(sp, T, tid, [&](int, float v) {
+                    const uint32_t key = ordered_key(v);
+                    if ((key & mask) == prefix) atomicAdd(&hist2[(key >> shift) & (nbins - 1)], 1u);
+                });
+                __syncthreads();
+                uint32_t b2, a2;
+                find_bin_from_top(hist2, nbins, krem, sh_pair, b2, a2);
+                krem -= a2;
+                n_eq = hist2[b2];
+                prefix |= b2 << shift;
+                mask |= (uint32_t)(nbins - 1) << shift;
+                __syncthreads();
             }
         }
-        __syncthreads();
-        const uint32_t bin = sh_bin;
-        krem -= sh_above;
-        n_eq = hist[bin];
-        prefix |= bin << shift;
-        mask |= (uint32_t)(nbins - 1) << shift;
-        __syncthreads();
-    }
-    // prefix is the key v of the k-th best score; krem of its n_eq ties are inside, lowest indices first
-    if (krem < n_eq) {
-        int seen = 0;
-        for (int c0 = 0; c0 < T; c0 += TB_THREADS) {
-            const int t = c0 + tid;
-            const bool tie = t < T && ordered_key(sp[t]) == prefix;
-            const unsigned long long bal = __ballot(tie);
-            if (lane == 0) sh_wcnt[wave] = __popcll(bal);
-            __syncthreads();
-            int before = 0, total = 0;
-            for (int w = 0; w < TB_THREADS / 64; ++w) { int c = sh_wcnt[w]; if (w < wave) before += c; total += c; }
-            const bool found = seen + total >= (int)krem;
-            if (found && tie && seen + before + __popcll(bal & ((1ull << lane) - 1ull)) + 1 == (int)krem) sh_cut = t;
-            __syncthreads();
-            if (found) { cut = sh_cut; break; }
-            seen += total;
+        // prefix is the key v of the k-th best score; krem of its n_eq ties are inside, lowest indices first
+        if (krem < n_eq) {
+            int seen = 0;
+            for (int c0 = 0; c0 < T; c0 += TB_THREADS) {
+                const int t = c0 + tid;
+                const bool tie = t < T && ordered_key(sp[t]) == prefix;
+                const unsigned long long bal = __ballot(tie);
+                if (lane == 0) sh_wcnt[wave] = __popcll(bal);
+                __syncthreads();
+                int before = 0, total = 0;
+                for (int w = 0; w < TB_THREADS / 64; ++w) { int c = sh_wcnt[w]; if (w < wave) before += c; total += c; }
+                const bool found = seen + total >= (int)krem;
+                if (found && tie && seen + before + __popcll(bal & ((1ull << lane) - 1ull)) + 1 == (int)krem) sh_cut = t;
+                __syncthreads();
+                if (found) { cut = sh_cut; break; }
+                seen += total;
+            }
         }
-    }
+        if (have_hits) {
+            // candidates at or above the threshold complete the list of Top-B tokens
+            const int ncand = sh_ncand;
+            for (int c = tid; c < ncand; c += TB_THREADS) {
+                const uint32_t key = cand_key[c];
+                const int t = cand_idx[c];
+                if (key > prefix || (key == prefix && t <= cut)) sh_hit[atomicAdd(&sh_nhit, 1)] = t;
+            }
+            __syncthreads();                   // sh_nhit == k; the candidate region is free again
+        }
     }   // k < T; for k >= T everything is inside: key 0 is below every score's key, cut = T - 1
     if (tid == 0) { thr[2 * p] = (int32_t)prefix; thr[2 * p + 1] = cut; }
     if (!seg_budget || k <= 0) return;
 
-    // implicit budgets: every Top-B token adds one to its segment (rows cleared above; the barrier below orders
-    // the clearing stores of all wavefronts before the first atomic)
+    // ---- implicit budgets: every Top-B token adds one to its segment (rows cleared above; the barrier below
+    // orders the clearing stores of all wavefronts before the first atomic)
     __syncthreads();
     const int seq = seq_of_problem(d, p);
     const int32_t *off = sv.seg_off + sv.seq_ptr[seq];
@@ -216,20 +294,25 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         for (int j = tid; j < K; j += TB_THREADS) seg_budget[row + j] = off[j + 1] - off[j];
         return;
     }
-    // Fast path (offsets fit in LDS, at most TB_HITS Top-B tokens): the row pass only collects the Top-B tokens;
-    // they are then assigned to segments in parallel (binary search on the LDS copy of the offsets, LDS counters)
-    // and the counts are written out.  Otherwise every Top-B token adds to the cleared row in global memory.
-    if (K + 1 <= TB_OFFS && k <= TB_HITS) {
-        for (int j = tid; j <= K; j += TB_THREADS) { sh_off[j] = off[j]; sh_cnt[j] = 0; }
+    if (!have_hits && k <= TB_HITS) {
+        // collect T_topB with one more pass over the row
         if (tid == 0) sh_nhit = 0;
         __syncthreads();
         scan_row(sp, T, tid, [&](int t, float v) {
             if (in_topb(v, t, prefix, cut)) sh_hit[atomicAdd(&sh_nhit, 1)] = t;      // exactly k of them
         });
         __syncthreads();
+        have_hits = true;
+    }
+    if (have_hits && K + 1 <= TB_OFFS) {
+        // assign the listed tokens to segments in parallel: binary search on an LDS copy of the offsets, LDS counters
+        for (int j = tid; j <= K; j += TB_THREADS) { sh_off[j] = off[j]; sh_cnt[j] = 0; }
+        __syncthreads();
         for (int i = tid; i < sh_nhit; i += TB_THREADS) atomicAdd(&sh_cnt[segment_of(sh_off, K, sh_hit[i])], 1);
         __syncthreads();
         for (int j = tid; j < K; j += TB_THREADS) seg_budget[row + j] = sh_cnt[j];
+    } else if (have_hits) {
+        for (int i = tid; i < sh_nhit; i += TB_THREADS) atomicAdd(&seg_budget[row + segment_of(off, K, sh_hit[i])], 1);
     } else {
         scan_row(sp, T, tid, [&](int t, float v) {
             if (in_topb(v, t, prefix, cut)) atomicAdd(&seg_budget[row + segment_of(off, K, t)], 1);

@@ -181,6 +181,14 @@ def test_search_select_degenerate_cases(oracle, torch_cuda):
         _assert_search_select(oracle, torch, st3, off3, cand, budget, 0.85)
     off4 = np.unique(np.concatenate([[0, T3], rng.integers(1, T3, size=900)])).astype(np.int32)
     _assert_search_select(oracle, torch, st3, off4, cand, 5000, 0.85)
+    # all scores inside one narrow range: the Top-B threshold's 12-bit bin holds every token (more than the
+    # candidate list of the selection kernel), with and without exact ties
+    T5 = 9001
+    st5 = (1.0 + 0.05 * rng.random((2, T5))).astype(np.float32).astype(np.float64)
+    st5[1] = np.round(st5[1] * 256) / 256.0
+    off5 = np.unique(np.concatenate([[0, T5], rng.integers(1, T5, size=150)])).astype(np.int32)
+    for budget in (300, 4500):
+        _assert_search_select(oracle, torch, st5, off5, cand, budget, 0.85)
 
 
 def test_compact_strided_inputs_bit_exact(oracle, torch_cuda):
