@@ -6,7 +6,9 @@ compact: five C-ABI calls) over every layer of one synthetic workload whose
 Q/K/V already sit in HBM.  Prints ONE JSON line:
   value     tokens/s per layer = n_seq * L * n_layers / step time
   roofline  the scoring step (the kernels that stream K): algorithmic bytes per
-            step / their HIP-event time per step, against the 8 TB/s HBM peak
+            step / their HIP-event time per step inside the timed region, against
+            the 8 TB/s HBM peak
+  stages_ms per-call breakdown from a second loop (events after every call)
   cpu_baseline  the fp64 oracle timed on the host on a bounded sample
 """
 
