@@ -46,6 +46,16 @@ def algorithmic_bytes(w, budget, append_window=True):
     }
 
 
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(w, q, k, v, off, ptr, budget, n_layers_sample, threads):
     """Time the fp64 oracle (all five steps) on `n_layers_sample` layers of sequence 0."""
     import numpy as np
@@ -75,6 +85,8 @@ def cpu_baseline(w, q, k, v, off, ptr, budget, n_layers_sample, threads):
         "value": w.seq_len * n_layers_sample / dt,
         "unit": "tokens/s per layer",
         "cores": min(threads, len(jobs)),
+        "host_cpus": os.cpu_count(),
+        "cpu_model": _cpu_model(),
         "kind": "oracle",
         "sample": f"{n_layers_sample} of {w.n_layers} layers of sequence 0 ({len(jobs)} KV-head problems, "
                   f"full L={w.seq_len}), all five steps, {dt:.2f} s",
@@ -84,7 +96,7 @@ def cpu_baseline(w, q, k, v, off, ptr, budget, n_layers_sample, threads):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b_128k")
     ap.add_argument("--budget-index", type=int, default=0)
@@ -194,6 +206,32 @@ def main():
                      "frac": score_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),
                      "algorithmic_bytes": alg["score"], "ms": score_ms},
     }
+    # a plain device copy on the same box as a second yardstick (reads and writes 1 GiB each)
+    src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+    result["device_copy_GBps"] = copy_gbs
+    result["roofline"]["frac_of_device_copy"] = score_gbs / copy_gbs
+    # the step in front of the path: punctuation-based segmentation of the prompt on the device (once per
+    # prompt, shared by all layers; both calls plus the read-back of the counts between them)
+    tok = torch.as_tensor(synth.token_ids(w.seed(0, 0), w.n_seq, w.T, w.seg_means[0])).to(dev)
+    B.segment(tok, synth.DELIMS)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(5):
+        sg = B.segment(tok, synth.DELIMS)
+    torch.cuda.synchronize()
+    seg_ms = (time.perf_counter() - t1) / 5 * 1e3
+    result["segmentation"] = {"ms_per_prompt": seg_ms, "tokens": w.n_seq * w.T, "segments": int(sg.max_segments),
+                              "tokens_per_s": w.n_seq * w.T / (seg_ms * 1e-3)}
     if not args.no_row_lse:
         # scoring handed the rows' log-sum-exp (single pass over K); lse taken from a first run's statistics
         # is not available through the ABI, so time the kernel on arbitrary finite lse values

@@ -8,6 +8,8 @@
  *   sablock_search_blocks  Top-B, implicit budgets, block-size search    (Alg. 2, Eqs. topk, implicit_budget, rk, gk_star)
  *   sablock_select         per-segment token sets and their union        (Alg. 2, Eq. final_selection)
  *   sablock_compact        gather of K/V rows into the retained cache    (end of Sec. 3.3)
+ * In front of them, sablock_segment_count / sablock_segment_offsets turn token ids and a delimiter set into the
+ * segment offsets the five calls take (Sec. 3.1).
  *
  * Conventions shared by all calls
  * -------------------------------
@@ -160,6 +162,28 @@ SABLOCK_API sablock_status sablock_select(const sablock_shape *shape, const floa
 SABLOCK_API sablock_status sablock_compact(const sablock_shape *shape, const void *k, const void *v,
                                const int32_t *idx, const int32_t *n_sel, int32_t budget,
                                int32_t append_window, void *k_out, void *v_out, void *stream);
+
+/*
+ * Punctuation-based segmentation of the compressible region (Sec. 3.1), the step in front of the five calls:
+ * delimiter tokens (commas, periods, ...) mark segment boundaries.  A delimiter closes the segment it belongs to:
+ * a new segment starts after every token t < n_tokens - 1 whose id is in `delims`; consecutive delimiters give
+ * one-token segments; a sequence without delimiters is one segment.  Two calls, because the offsets are CSR
+ * with HOST pointers (see "Segments" above):
+ *   1. sablock_segment_count writes the segment count K_s of every sequence to seg_count_out (device, n_seq
+ *      int32); the caller reads it back and forms seg_ptr[s+1] = seg_ptr[s] + K_s + 1;
+ *   2. sablock_segment_offsets writes, for every sequence, 0, the boundaries in ascending order, n_tokens to
+ *      seg_off_out[seg_ptr[s] .. seg_ptr[s+1]) (device); entries beyond what seg_ptr leaves room for are dropped.
+ * token_ids: device int32, sequence s at token_ids + s * token_stride (elements), n_tokens = T ids each (the
+ * compressible region only).  delims: HOST array of n_delim <= 64 token ids (n_delim = 0: one segment each).
+ * Errors: INVALID_ARG for NULL pointers, n_seq < 1, n_tokens < 1, token_stride < n_tokens, a seg_ptr that leaves
+ * a sequence fewer than 2 or more than n_tokens + 1 offsets; UNSUPPORTED for n_seq > 64 or n_delim > 64.
+ */
+SABLOCK_API sablock_status sablock_segment_count(const int32_t *token_ids, int64_t token_stride, int32_t n_seq,
+                                     int32_t n_tokens, const int32_t *delims, int32_t n_delim,
+                                     int32_t *seg_count_out, void *stream);
+SABLOCK_API sablock_status sablock_segment_offsets(const int32_t *token_ids, int64_t token_stride, int32_t n_seq,
+                                       int32_t n_tokens, const int32_t *delims, int32_t n_delim,
+                                       const int32_t *seg_ptr, int32_t *seg_off_out, void *stream);
 
 #ifdef __cplusplus
 }

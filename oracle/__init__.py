@@ -14,4 +14,5 @@ from .sablock_ref import (  # noqa: F401
     compact,
     segment_score,
     pipeline_head,
+    segment,
 )

@@ -2,7 +2,9 @@
 
 TEST INFRASTRUCTURE ONLY: argument marshalling for the plain C oracle.  Every
 function takes numpy arrays for ONE KV head of one (sequence, layer) and widens
-them to float64 before the call; nothing here does arithmetic of the method.
+them to float64 before the call; nothing here does arithmetic of the method,
+with one exception: ``segment`` (punctuation-based segmentation, Sec. 3.1) is
+integer-only and is written out here as a plain Python loop.
 """
 
 from __future__ import annotations
@@ -165,3 +167,21 @@ def pipeline_head(q, k, v, seg_off, cand, budget: int, eps=1e-6, alpha=0.9, eta=
     ko, vo = compact(k if k_raw is None else k_raw, v if v_raw is None else v_raw, W, idx, n_sel,
                      budget, append_window)
     return dict(s=s, e=e, s_tilde=st, omega=om, b=b, g=g, idx=idx, n_sel=n_sel, k_out=ko, v_out=vo)
+
+
+def segment(token_ids, delims: Sequence[int]) -> np.ndarray:
+    """Punctuation-based segmentation of one sequence's compressible region (Sec. 3.1).
+
+    Walks the tokens in order; a delimiter token closes the segment it is in, so the
+    next token (if there is one) starts a new segment.  Returns the offsets
+    ``[0, ..., T]`` (int32): segment k is tokens ``off[k] .. off[k+1]-1``.
+    """
+    ids = [int(x) for x in np.asarray(token_ids).reshape(-1)]
+    dset = set(int(d) for d in delims)
+    T = len(ids)
+    off = [0]
+    for t, tok in enumerate(ids):
+        if tok in dset and t + 1 < T:
+            off.append(t + 1)
+    off.append(T)
+    return np.asarray(off, dtype=np.int32)

@@ -22,7 +22,8 @@ STATUS_NAMES = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_S
 SABLOCK_F32, SABLOCK_BF16 = 0, 1
 
 EXPORTS = ("sablock_version", "sablock_last_error", "sablock_workspace_bytes", "sablock_score",
-           "sablock_refine", "sablock_search_blocks", "sablock_select", "sablock_compact")
+           "sablock_refine", "sablock_search_blocks", "sablock_select", "sablock_compact",
+           "sablock_segment_count", "sablock_segment_offsets")
 
 
 class SablockError(RuntimeError):
@@ -64,6 +65,9 @@ def load():
         lib.sablock_select.argtypes = [sp, vp, vp, ctypes.POINTER(i32), i32, vp, vp, vp, i32, vp, vp, vp,
                                        ctypes.c_size_t, vp]
         lib.sablock_compact.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        lib.sablock_segment_count.argtypes = [vp, ctypes.c_int64, i32, i32, ctypes.POINTER(i32), i32, vp, vp]
+        lib.sablock_segment_offsets.argtypes = [vp, ctypes.c_int64, i32, i32, ctypes.POINTER(i32), i32,
+                                                ctypes.POINTER(i32), vp, vp]
         for n in EXPORTS[2:]:
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
@@ -170,6 +174,36 @@ def sablock_compact(shape: CShape, k, v, idx, n_sel, budget: int, append_window:
                     stream=None):
     _check(load().sablock_compact(ctypes.byref(shape), _ptr(k), _ptr(v), _ptr(idx), _ptr(n_sel), budget,
                                   1 if append_window else 0, _ptr(k_out), _ptr(v_out), _stream(stream)))
+
+
+def sablock_segment_count(token_ids, delims: Sequence[int], seg_count_out, stream=None):
+    """``token_ids [n_seq, T]`` int32 (row stride in elements taken from the tensor) -> ``seg_count_out [n_seq]``."""
+    d = (ctypes.c_int32 * max(len(delims), 1))(*[int(x) for x in delims])
+    _check(load().sablock_segment_count(_ptr(token_ids), token_ids.stride(0), token_ids.shape[0], token_ids.shape[1],
+                                        d, len(delims), _ptr(seg_count_out), _stream(stream)))
+
+
+def sablock_segment_offsets(token_ids, delims: Sequence[int], seg_ptr: Sequence[int], seg_off_out, stream=None):
+    d = (ctypes.c_int32 * max(len(delims), 1))(*[int(x) for x in delims])
+    sp = (ctypes.c_int32 * len(seg_ptr))(*[int(x) for x in seg_ptr])
+    _check(load().sablock_segment_offsets(_ptr(token_ids), token_ids.stride(0), token_ids.shape[0],
+                                          token_ids.shape[1], d, len(delims), sp, _ptr(seg_off_out), _stream(stream)))
+
+
+def segment(token_ids, delims: Sequence[int]) -> "Segments":
+    """Both segmentation calls and the host step between them (one read-back of n_seq counts)."""
+    import torch
+
+    assert token_ids.dim() == 2 and token_ids.dtype == torch.int32 and token_ids.stride(1) == 1
+    counts = torch.empty((token_ids.shape[0],), dtype=torch.int32, device=token_ids.device)
+    sablock_segment_count(token_ids, delims, counts)
+    c = counts.cpu().tolist()
+    ptr = [0]
+    for n in c:
+        ptr.append(ptr[-1] + n + 1)
+    seg_off = torch.empty((ptr[-1],), dtype=torch.int32, device=token_ids.device)
+    sablock_segment_offsets(token_ids, delims, ptr, seg_off)
+    return Segments(seg_off, ptr, max(c))
 
 
 class Buffers:

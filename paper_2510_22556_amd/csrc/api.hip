@@ -223,4 +223,50 @@ sablock_status sablock_compact(const sablock_shape *shape, const void *k, const 
                               static_cast<hipStream_t>(stream)), "sablock_compact");
 }
 
+static sablock_status make_delims(const int32_t *delims, int32_t n_delim, DelimSet *ds)
+{
+    if (n_delim < 0 || (n_delim > 0 && !delims)) return fail(SABLOCK_ERR_INVALID_ARG, "delims is NULL or n_delim < 0");
+    if (n_delim > MAX_DELIM) return fail(SABLOCK_ERR_UNSUPPORTED, "n_delim %d: at most %d", n_delim, MAX_DELIM);
+    ds->n = n_delim;
+    for (int i = 0; i < MAX_DELIM; ++i) ds->id[i] = i < n_delim ? delims[i] : 0;
+    return SABLOCK_OK;
+}
+
+sablock_status sablock_segment_count(const int32_t *token_ids, int64_t token_stride, int32_t n_seq, int32_t n_tokens,
+                                     const int32_t *delims, int32_t n_delim, int32_t *seg_count_out, void *stream)
+{
+    if (!token_ids || !seg_count_out) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_segment_count: NULL argument");
+    if (n_seq < 1 || n_tokens < 1 || token_stride < n_tokens)
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_segment_count: need n_seq >= 1, n_tokens >= 1, token_stride >= n_tokens");
+    if (n_seq > MAX_SEQ) return fail(SABLOCK_ERR_UNSUPPORTED, "n_seq %d: at most %d per call", n_seq, MAX_SEQ);
+    DelimSet ds;
+    sablock_status st = make_delims(delims, n_delim, &ds);
+    if (st != SABLOCK_OK) return st;
+    return dev(launch_segment_count(token_ids, token_stride, n_seq, n_tokens, ds, seg_count_out,
+                                    static_cast<hipStream_t>(stream)), "sablock_segment_count");
+}
+
+sablock_status sablock_segment_offsets(const int32_t *token_ids, int64_t token_stride, int32_t n_seq, int32_t n_tokens,
+                                       const int32_t *delims, int32_t n_delim, const int32_t *seg_ptr,
+                                       int32_t *seg_off_out, void *stream)
+{
+    if (!token_ids || !seg_ptr || !seg_off_out) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_segment_offsets: NULL argument");
+    if (n_seq < 1 || n_tokens < 1 || token_stride < n_tokens)
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_segment_offsets: need n_seq >= 1, n_tokens >= 1, token_stride >= n_tokens");
+    if (n_seq > MAX_SEQ) return fail(SABLOCK_ERR_UNSUPPORTED, "n_seq %d: at most %d per call", n_seq, MAX_SEQ);
+    SeqPtr sp;
+    if (seg_ptr[0] < 0) return fail(SABLOCK_ERR_INVALID_ARG, "seg_ptr[0] < 0");
+    for (int s = 0; s <= MAX_SEQ; ++s) sp.ptr[s] = seg_ptr[s < n_seq ? s : n_seq];
+    for (int s = 0; s < n_seq; ++s) {
+        const int n = seg_ptr[s + 1] - seg_ptr[s];
+        if (n < 2 || n > n_tokens + 1)
+            return fail(SABLOCK_ERR_INVALID_ARG, "sequence %d: seg_ptr leaves %d offsets, need 2 .. n_tokens + 1", s, n);
+    }
+    DelimSet ds;
+    sablock_status st = make_delims(delims, n_delim, &ds);
+    if (st != SABLOCK_OK) return st;
+    return dev(launch_segment_offsets(token_ids, token_stride, n_seq, n_tokens, ds, sp, seg_off_out,
+                                      static_cast<hipStream_t>(stream)), "sablock_segment_offsets");
+}
+
 }  // extern "C"

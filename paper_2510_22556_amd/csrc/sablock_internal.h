@@ -26,6 +26,17 @@ struct SegView {
     int32_t max_segments;
 };
 
+constexpr int MAX_DELIM = 64;
+
+struct DelimSet {                  // delimiter token ids, by value in the kernel arguments
+    int32_t n;
+    int32_t id[MAX_DELIM];
+};
+
+struct SeqPtr {                    // host CSR pointers of the segment offsets, by value in the kernel arguments
+    int32_t ptr[MAX_SEQ + 1];
+};
+
 struct CandList {
     int32_t n;
     int32_t g[MAX_CAND];
@@ -96,5 +107,11 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
 hipError_t launch_compact(const Dims &d, const void *k, const void *v, const int32_t *idx,
                           const int32_t *n_sel, int32_t budget, int32_t append_window,
                           void *k_out, void *v_out, hipStream_t st);
+
+// punctuation-based segmentation (the step before the path)
+hipError_t launch_segment_count(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,
+                                int32_t *seg_count, hipStream_t st);
+hipError_t launch_segment_offsets(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,
+                                  const SeqPtr &sp, int32_t *seg_off, hipStream_t st);
 
 }  // namespace sablock

@@ -30,7 +30,7 @@ _MASK64 = (1 << 64) - 1
 BASE_SEED = 0x5AB10C00
 
 # stream ids: one per tensor kind so tensors of one configuration are independent
-STREAM_Q, STREAM_K, STREAM_V, STREAM_SEG, STREAM_HEAVY = 1, 2, 3, 4, 5
+STREAM_Q, STREAM_K, STREAM_V, STREAM_SEG, STREAM_HEAVY, STREAM_TOK = 1, 2, 3, 4, 5, 6
 
 
 # --------------------------------------------------------------------------
@@ -180,6 +180,31 @@ def segment_offsets(seed: int, T: int, mean: float, min_len: int = 2,
 # --------------------------------------------------------------------------
 # rotary position embedding (input preparation for configuration 2)
 # --------------------------------------------------------------------------
+# Delimiter ids of the synthetic prompts (stand-ins for a tokenizer's comma, period, semicolon, ... ids; the real
+# sets belong to tokenizers that are not available here).
+DELIMS = (11, 13, 26, 30, 198, 0)
+
+
+def token_ids(seed: int, n_seq: int, T: int, mean: float, vocab: int = 128256,
+              delims: Sequence[int] = DELIMS) -> np.ndarray:
+    """Synthetic prompts ``[n_seq, T]`` int32: each token is a delimiter with probability 1/mean (so segment
+    lengths are geometric with that mean), otherwise a non-delimiter id below ``vocab``."""
+    out = np.empty((n_seq, T), dtype=np.int32)
+    dl = np.asarray(delims, dtype=np.int64)
+    dset = set(int(d) for d in delims)
+    for s in range(n_seq):
+        h = hash_u64(seed + 7919 * s, STREAM_TOK, 0, 2 * T)
+        u = (h[:T] >> np.uint64(11)).astype(np.float64) / float(1 << 53)
+        r = h[T:]
+        ids = (r % np.uint64(vocab)).astype(np.int64)
+        for d in dset:                                   # keep ordinary tokens off the delimiter ids
+            ids[ids == d] = (d + 1) % vocab if ((d + 1) % vocab) not in dset else (d + 7) % vocab
+        is_d = u < 1.0 / mean
+        ids[is_d] = dl[(r[is_d] >> np.uint64(32)).astype(np.int64) % len(dl)]
+        out[s] = ids.astype(np.int32)
+    return out
+
+
 def apply_rope(x: np.ndarray, positions: np.ndarray, base: float = 500000.0) -> np.ndarray:
     """Rotate ``x[..., pos, D]`` by position; half-split pairing (d, d + D/2)."""
     D = x.shape[-1]

@@ -369,3 +369,40 @@ def test_llama8b_128k_full_size_sampled(oracle, torch_cuda):
     for p in (0, 100, 255):                                                        # per segment, exactly b_k tokens selected
         assert (np.bincount(seg_of[p], minlength=len(off) - 1) == run.b[p][:len(off) - 1]).all()
     _check_all(oracle, w, run, q, k, v, off, ptr, [3, 130, 255])
+
+
+def test_segmentation_matches_oracle_and_feeds_the_path(oracle, torch_cuda):
+    # punctuation-based segmentation on the device (the step in front of the path): offsets bit-exact against the
+    # oracle's token walk for ragged lengths, padded rows, no / only delimiters, and as input of the five calls
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    def check(ids_np, delims, stride=None):
+        n_seq, T = ids_np.shape
+        buf = torch.zeros((n_seq, stride or T), dtype=torch.int32, device="cuda")
+        buf[:, :T] = torch.as_tensor(ids_np).cuda()
+        seg = B.segment(buf[:, :T], delims)
+        torch.cuda.synchronize()
+        off = H.to_np(seg.seg_off)
+        for s in range(n_seq):
+            np.testing.assert_array_equal(off[seg.seg_ptr[s]:seg.seg_ptr[s + 1]], oracle.segment(ids_np[s], delims))
+        return seg
+
+    for T, mean in [(10007, 24.0), (4096, 3.0), (4097, 200.0), (131040, 64.0), (5, 2.0), (1, 2.0), (2, 1.0)]:
+        check(synth.token_ids(100 + T, 3, T, mean), synth.DELIMS, stride=T + 13)
+    ids = synth.token_ids(1, 2, 3000, 16.0)
+    check(ids, [])                                              # no delimiter set: one segment each
+    check(ids, [10 ** 9])                                       # a delimiter that never occurs
+    check(np.full((2, 777), 11, dtype=np.int32), [11])          # only delimiters: one-token segments
+    check(ids, list(range(200000, 200058)) + list(synth.DELIMS))          # 64 delimiter ids
+    last = ids.copy(); last[:, -1] = 13
+    check(last, synth.DELIMS)                                   # delimiter as the last token
+
+    # the device's segments as input of the path (tiny workload, its own seeded prompt)
+    w = synth.WORKLOADS["tiny"]
+    q, k, v, _, _ = _device_workload(torch, w)
+    tok = synth.token_ids(77, w.n_seq, w.T, 24.0)
+    seg = check(tok, synth.DELIMS)
+    off, ptr = H.to_np(seg.seg_off), list(seg.seg_ptr)
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau)
+    _check_all(oracle, w, run, q, k, v, off, ptr, range(w.n_kv_heads))

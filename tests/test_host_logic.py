@@ -88,6 +88,17 @@ def test_calls_reject_bad_host_arguments_before_launch(lib):
     assert lib.sablock_compact(sp, fake, None, fake, fake, 8, 1, fake, fake, None) == 1
     assert lib.sablock_compact(sp, fake, fake, fake, fake, -8, 1, fake, fake, None) == 1
     assert lib.sablock_score(None, fake, fake, None, 1e-6, fake, fake, fake, 0, None) == 1
+    # segmentation
+    dl = (ctypes.c_int32 * 2)(11, 13)
+    many = (ctypes.c_int32 * 65)(*range(65))
+    assert lib.sablock_segment_count(None, 100, 1, 100, dl, 2, fake, None) == 1
+    assert lib.sablock_segment_count(fake, 50, 1, 100, dl, 2, fake, None) == 1              # stride < n_tokens
+    assert lib.sablock_segment_count(fake, 100, 1, 0, dl, 2, fake, None) == 1
+    assert lib.sablock_segment_count(fake, 100, 1, 100, many, 65, fake, None) == 2
+    assert lib.sablock_segment_count(fake, 100, 65, 100, dl, 2, fake, None) == 2
+    assert lib.sablock_segment_offsets(fake, 100, 1, 100, dl, 2, None, fake, None) == 1
+    assert lib.sablock_segment_offsets(fake, 100, 1, 100, dl, 2, (ctypes.c_int32 * 2)(0, 1), fake, None) == 1     # < 2 offsets
+    assert lib.sablock_segment_offsets(fake, 100, 1, 100, dl, 2, (ctypes.c_int32 * 2)(0, 200), fake, None) == 1   # > T + 1
 
 
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):

@@ -324,3 +324,33 @@ def test_pipeline_tiny_invariants(oracle):
         np.testing.assert_array_equal(r["v_out"][B:], v[j][w.T:])
         ref = bf.run(r["s_tilde"], off.tolist(), list(w.cand), B, w.tau)
         assert r["g"].tolist() == ref["g"] and r["idx"].tolist() == ref["idx"]
+
+
+# ---------------------------------------------------------------- segmentation (Sec. 3.1)
+def test_segment_hand_examples(oracle):
+    # "a , b c . d" with delimiters {",", "."}: [a ,] [b c .] [d]
+    np.testing.assert_array_equal(oracle.segment([5, 11, 7, 8, 13, 9], [11, 13]), [0, 2, 5, 6])
+    # a delimiter as the last token closes the last segment without opening an empty one
+    np.testing.assert_array_equal(oracle.segment([5, 11, 7, 13], [11, 13]), [0, 2, 4])
+    # no delimiter at all / no delimiter set: one segment
+    np.testing.assert_array_equal(oracle.segment([1, 2, 3], [11]), [0, 3])
+    np.testing.assert_array_equal(oracle.segment([1, 2, 3], []), [0, 3])
+    # consecutive delimiters: one-token segments
+    np.testing.assert_array_equal(oracle.segment([11, 11, 11, 4], [11]), [0, 1, 2, 3, 4])
+    np.testing.assert_array_equal(oracle.segment([11], [11]), [0, 1])
+
+
+def test_segment_against_library_routines(oracle):
+    from paper_2510_22556_amd import synth
+
+    ids = synth.token_ids(11, 3, 5003, 24.0)
+    for row in ids:
+        off = oracle.segment(row, synth.DELIMS)
+        interior = np.flatnonzero(np.isin(row[:-1], synth.DELIMS)) + 1          # library formulation
+        np.testing.assert_array_equal(off, np.concatenate([[0], interior, [len(row)]]))
+        assert (np.diff(off) >= 1).all()
+        # every segment but the last ends with a delimiter and holds no other one
+        for a, b in zip(off[:-1], off[1:]):
+            assert not np.isin(row[a:b - 1], synth.DELIMS).any()
+            assert b == len(row) or row[b - 1] in synth.DELIMS
+        assert 16 < np.diff(off).mean() < 36                                       # the generator's mean length
