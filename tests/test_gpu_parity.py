@@ -99,6 +99,24 @@ def test_ragged_shapes_generic_kernels(oracle, torch_cuda, case):
     _check_all(oracle, w, run, q, k, v, off, ptr, range(ns * nl * Hkv), tau=0.8)
 
 
+@pytest.mark.parametrize("cand", [list(range(1, 14)), [1, 2, 3, 5, 7, 9, 11, 13]])
+def test_paper_hyperparameters_window8_integer_candidates(oracle, torch_cuda, cand):
+    # the paper's own settings (Sec. 4.1): observation window 8, block sizes searched over every integer up to
+    # 13 or over the restricted list, eps 1e-6, alpha 0.9, eta 1.0, tau 0.85; Llama-shaped heads (G 4, D 128, bf16)
+    torch = torch_cuda
+    L, W, D, G, Hkv = 6008, 8, 128, 4, 2
+    T = L - W
+    q = synth.normal_torch(808, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(808, 2, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(808, 3, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    off = synth.segment_offsets(808, T, mean=28.0, min_len=1, max_len=200)
+    w = synth.Workload("paper", 0, 1, 1, G * Hkv, Hkv, D, L, W, "bf16", tuple(cand), (1024,), (28.0,))
+    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget(), 1e-6, 0.9, 1.0, 0.85)
+    _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv), tau=0.85)
+    assert set(np.unique(run.g)) <= set([0] + cand)
+    assert (run.g > 1).any()
+
+
 def _stage_inputs(torch, st_rows, L_extra=4):
     """Dummy Q/K/V of the right geometry around hand-made s_tilde rows (search/select stage tests)."""
     P, T = st_rows.shape
