@@ -232,6 +232,33 @@ def main():
     seg_ms = (time.perf_counter() - t1) / 5 * 1e3
     result["segmentation"] = {"ms_per_prompt": seg_ms, "tokens": w.n_seq * w.T, "segments": int(sg.max_segments),
                               "tokens_per_s": w.n_seq * w.T / (seg_ms * 1e-3)}
+    # the step behind the path: one decode step (one new token per layer) over the full cache and over the cache
+    # the path just wrote (the comparison behind the paper's decoding-latency figures, attention only)
+    qn = synth.normal_torch(w.seed(0, 0), synth.STREAM_Q, (w.n_seq, w.n_layers, w.n_q_heads, w.head_dim), dev,
+                            q.dtype, start=1 << 40)
+    rows = budget + w.window
+    kc = buf.k_out.view(w.n_seq, w.n_layers, w.n_kv_heads, rows, w.head_dim)
+    vc = buf.v_out.view(w.n_seq, w.n_layers, w.n_kv_heads, rows, w.head_dim)
+    dec = {}
+    elt = 4 if w.dtype == "f32" else 2
+    for name, (kk, vv, ns_, bb) in {"full_cache": (k, v, None, 0), "compacted_cache": (kc, vc, buf.n_sel, budget)}.items():
+        cs = B.make_cache_shape(qn, kk, vv)
+        dws = torch.empty((B.sablock_decode_workspace_bytes(cs),), dtype=torch.uint8, device=dev)
+        dout = torch.empty(qn.shape, dtype=torch.float32, device=dev)
+        B.sablock_decode_attention(cs, qn, kk, vv, dout, dws, n_sel=ns_, budget=bb)
+        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        d0.record()
+        for _ in range(5):
+            B.sablock_decode_attention(cs, qn, kk, vv, dout, dws, n_sel=ns_, budget=bb)
+        d1.record()
+        torch.cuda.synchronize()
+        ms = d0.elapsed_time(d1) / 5
+        nbytes = 2 * w.n_seq * w.n_layers * w.n_kv_heads * kk.shape[3] * w.head_dim * elt
+        dec[name] = {"rows": int(kk.shape[3]), "ms_per_token": ms, "GBps": nbytes / (ms * 1e-3) / 1e9,
+                     "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    dec["speedup"] = dec["full_cache"]["ms_per_token"] / dec["compacted_cache"]["ms_per_token"]
+    dec["cache_bytes_ratio"] = rows / w.seq_len
+    result["decode_attention"] = dec
     if not args.no_row_lse:
         # scoring handed the rows' log-sum-exp (single pass over K); lse taken from a first run's statistics
         # is not available through the ABI, so time the kernel on arbitrary finite lse values

@@ -9,7 +9,8 @@
  *   sablock_select         per-segment token sets and their union        (Alg. 2, Eq. final_selection)
  *   sablock_compact        gather of K/V rows into the retained cache    (end of Sec. 3.3)
  * In front of them, sablock_segment_count / sablock_segment_offsets turn token ids and a delimiter set into the
- * segment offsets the five calls take (Sec. 3.1).
+ * segment offsets the five calls take (Sec. 3.1); behind them, sablock_decode_attention is one decode step
+ * over the cache they leave (or over the full cache, for comparison).
  *
  * Conventions shared by all calls
  * -------------------------------
@@ -184,6 +185,27 @@ SABLOCK_API sablock_status sablock_segment_count(const int32_t *token_ids, int64
 SABLOCK_API sablock_status sablock_segment_offsets(const int32_t *token_ids, int64_t token_stride, int32_t n_seq,
                                        int32_t n_tokens, const int32_t *delims, int32_t n_delim,
                                        const int32_t *seg_ptr, int32_t *seg_off_out, void *stream);
+
+/*
+ * Decode-time attention of ONE new token over a KV cache (Sec. 2.1, Eq. 1 with a single query position): the
+ * step after the path, over the compacted cache that sablock_compact wrote or over the full cache.  For every
+ * problem p and each of its G query heads h:  out[h] = softmax_r(<q[h], K[p][r]> / sqrt(D)) . V[p][r].
+ *   shape      n_seq, n_layers, heads, head_dim, dtype as in the other calls; seq_len = number of ROWS of the
+ *              cache buffers; k_stride / v_stride describe them (elements; [3] = row stride); window and
+ *              q_stride are ignored.  A compacted cache is dense: row stride D, head stride rows * D, ...
+ *   q          [n_seq][n_layers][n_q_heads][D], dense, dtype of the cache.
+ *   n_sel      NULL (every row holds an entry), or device [P]: rows n_sel[p] .. budget-1 of problem p hold no
+ *              entry (the zero-filled gap sablock_compact leaves when fewer than `budget` tokens were retained)
+ *              and are skipped; rows from `budget` on (the window rows) always count.
+ *   out        [n_seq][n_layers][n_q_heads][D] fp32, dense.  A problem without any row gives zeros.
+ *   ws         at least sablock_decode_workspace_bytes(shape) bytes (partial results of the row splits).
+ * Supported: G in {1,2,4,8}; head_dim * element size / 16 a power of two in [4, 64]; G * head_dim <= 1024;
+ * at least 2 rows.  Errors as for the other calls.
+ */
+SABLOCK_API sablock_status sablock_decode_workspace_bytes(const sablock_shape *shape, size_t *bytes_out);
+SABLOCK_API sablock_status sablock_decode_attention(const sablock_shape *shape, const void *q, const void *k_cache,
+                                        const void *v_cache, const int32_t *n_sel, int32_t budget, float *out,
+                                        void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

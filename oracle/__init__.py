@@ -15,4 +15,5 @@ from .sablock_ref import (  # noqa: F401
     segment_score,
     pipeline_head,
     segment,
+    decode_attention,
 )

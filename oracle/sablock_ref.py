@@ -3,8 +3,9 @@
 TEST INFRASTRUCTURE ONLY: argument marshalling for the plain C oracle.  Every
 function takes numpy arrays for ONE KV head of one (sequence, layer) and widens
 them to float64 before the call; nothing here does arithmetic of the method,
-with one exception: ``segment`` (punctuation-based segmentation, Sec. 3.1) is
-integer-only and is written out here as a plain Python loop.
+with two exceptions written out here in plain numpy / Python: ``segment``
+(punctuation-based segmentation, Sec. 3.1; integer-only, a token walk) and
+``decode_attention`` (Sec. 2.1 Eq. 1 for one query position; float64).
 """
 
 from __future__ import annotations
@@ -185,3 +186,23 @@ def segment(token_ids, delims: Sequence[int]) -> np.ndarray:
             off.append(t + 1)
     off.append(T)
     return np.asarray(off, dtype=np.int32)
+
+
+def decode_attention(q, k_rows, v_rows) -> np.ndarray:
+    """Attention of one new token over a cache, one KV head (Sec. 2.1, Eq. 1 with a single query position).
+
+    ``q [G, D]`` (the query heads that share the KV head), ``k_rows, v_rows [R, D]`` (the rows that hold an
+    entry).  Returns ``[G, D]`` float64: ``softmax_r(q . k_r / sqrt(D)) @ v``; zeros if there is no row.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k_rows, dtype=np.float64)
+    v = np.asarray(v_rows, dtype=np.float64)
+    G, D = q.shape                               # D: the contraction length that the scale 1/sqrt(D) refers to
+    out = np.zeros((G, v.shape[1]), dtype=np.float64)
+    if k.shape[0] == 0:
+        return out
+    for g in range(G):
+        x = k @ q[g] / np.sqrt(float(D))
+        w = np.exp(x - x.max())
+        out[g] = (w / w.sum()) @ v
+    return out

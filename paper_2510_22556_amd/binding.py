@@ -23,7 +23,8 @@ SABLOCK_F32, SABLOCK_BF16 = 0, 1
 
 EXPORTS = ("sablock_version", "sablock_last_error", "sablock_workspace_bytes", "sablock_score",
            "sablock_refine", "sablock_search_blocks", "sablock_select", "sablock_compact",
-           "sablock_segment_count", "sablock_segment_offsets")
+           "sablock_segment_count", "sablock_segment_offsets", "sablock_decode_workspace_bytes",
+           "sablock_decode_attention")
 
 
 class SablockError(RuntimeError):
@@ -68,6 +69,8 @@ def load():
         lib.sablock_segment_count.argtypes = [vp, ctypes.c_int64, i32, i32, ctypes.POINTER(i32), i32, vp, vp]
         lib.sablock_segment_offsets.argtypes = [vp, ctypes.c_int64, i32, i32, ctypes.POINTER(i32), i32,
                                                 ctypes.POINTER(i32), vp, vp]
+        lib.sablock_decode_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
+        lib.sablock_decode_attention.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, ctypes.c_size_t, vp]
         for n in EXPORTS[2:]:
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
@@ -204,6 +207,38 @@ def segment(token_ids, delims: Sequence[int]) -> "Segments":
     seg_off = torch.empty((ptr[-1],), dtype=torch.int32, device=token_ids.device)
     sablock_segment_offsets(token_ids, delims, ptr, seg_off)
     return Segments(seg_off, ptr, max(c))
+
+
+def make_cache_shape(q, k_cache, v_cache=None) -> CShape:
+    """Shape of a decode call: ``q [n_seq, n_layers, Hq, D]`` and a cache ``[n_seq, n_layers, Hkv, rows, D]``
+    (any strides on the four outer axes; a compacted cache ``[P, rows, D]`` is viewed that way by the caller)."""
+    import torch
+
+    assert q.dim() == 4 and k_cache.dim() == 5 and q.is_contiguous() and k_cache.stride(-1) == 1
+    assert q.dtype == k_cache.dtype and q.dtype in (torch.float32, torch.bfloat16)
+    s = CShape()
+    s.n_seq, s.n_layers, s.n_q_heads, s.head_dim = q.shape
+    s.n_kv_heads, s.seq_len = k_cache.shape[2], k_cache.shape[3]
+    s.window = 1
+    s.dtype = SABLOCK_F32 if q.dtype == torch.float32 else SABLOCK_BF16
+    vv = k_cache if v_cache is None else v_cache
+    for a in range(4):
+        s.q_stride[a] = 0
+        s.k_stride[a] = k_cache.stride(a)
+        s.v_stride[a] = vv.stride(a)
+    return s
+
+
+def sablock_decode_workspace_bytes(shape: CShape) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().sablock_decode_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)))
+    return int(out.value)
+
+
+def sablock_decode_attention(shape: CShape, q, k_cache, v_cache, out, ws, n_sel=None, budget: int = 0, stream=None):
+    _check(load().sablock_decode_attention(ctypes.byref(shape), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(n_sel),
+                                           budget, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(),
+                                           _stream(stream)))
 
 
 class Buffers:

@@ -269,4 +269,49 @@ sablock_status sablock_segment_offsets(const int32_t *token_ids, int64_t token_s
                                       static_cast<hipStream_t>(stream)), "sablock_segment_offsets");
 }
 
+static sablock_status make_cache_dims(const sablock_shape *shape, Dims *d)
+{
+    if (!shape) return fail(SABLOCK_ERR_INVALID_ARG, "shape is NULL");
+    if (shape->seq_len < 2) return fail(SABLOCK_ERR_INVALID_ARG, "decode: the cache needs at least 2 rows");
+    sablock_shape s = *shape;
+    s.window = 1;                                  // not used by the decode kernels
+    s.q_stride[0] = (int64_t)s.n_layers * s.n_q_heads * s.head_dim;   // q is dense
+    s.q_stride[1] = (int64_t)s.n_q_heads * s.head_dim;
+    s.q_stride[2] = s.q_stride[3] = s.head_dim;
+    sablock_status st = make_dims(&s, d);
+    if (st != SABLOCK_OK) return st;
+    if (!decode_supported(*d))
+        return fail(SABLOCK_ERR_UNSUPPORTED, "decode: need G in {1,2,4,8}, head_dim * element size / 16 a power of two in [4, 64], G * head_dim <= 1024");
+    return SABLOCK_OK;
+}
+
+sablock_status sablock_decode_workspace_bytes(const sablock_shape *shape, size_t *bytes_out)
+{
+    if (!bytes_out) return fail(SABLOCK_ERR_INVALID_ARG, "bytes_out is NULL");
+    Dims d;
+    sablock_status st = make_cache_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    *bytes_out = decode_ws_bytes(d);
+    return SABLOCK_OK;
+}
+
+sablock_status sablock_decode_attention(const sablock_shape *shape, const void *q, const void *k_cache,
+                                        const void *v_cache, const int32_t *n_sel, int32_t budget, float *out,
+                                        void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    sablock_status st = make_cache_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!q || !k_cache || !v_cache || !out) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_decode_attention: NULL argument");
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache))
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_decode_attention: q/K/V must be 16-byte aligned");
+    if (n_sel && (budget < 0 || budget > d.L)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_decode_attention: need 0 <= budget <= rows");
+    if (shape->v_stride[3] < d.D) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_decode_attention: V row stride smaller than head_dim");
+    const size_t need = decode_ws_bytes(d);
+    if (!ws || ws_bytes < need)
+        return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_decode_attention: workspace %zu < %zu bytes", ws_bytes, need);
+    return dev(launch_decode(d, q, k_cache, v_cache, n_sel, budget, out, ws, static_cast<hipStream_t>(stream)),
+               "sablock_decode_attention");
+}
+
 }  // extern "C"

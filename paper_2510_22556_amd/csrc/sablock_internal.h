@@ -114,4 +114,10 @@ hipError_t launch_segment_count(const int32_t *tok, int64_t stride, int32_t n_se
 hipError_t launch_segment_offsets(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,
                                   const SeqPtr &sp, int32_t *seg_off, hipStream_t st);
 
+// decode-time attention over a cache (the step after the path); d.L = rows of the cache buffers
+bool decode_supported(const Dims &d);
+size_t decode_ws_bytes(const Dims &d);
+hipError_t launch_decode(const Dims &d, const void *q, const void *k, const void *v, const int32_t *n_sel,
+                         int32_t budget, float *out, void *ws, hipStream_t st);
+
 }  // namespace sablock

@@ -424,3 +424,104 @@ def test_segmentation_matches_oracle_and_feeds_the_path(oracle, torch_cuda):
     off, ptr = H.to_np(seg.seg_off), list(seg.seg_ptr)
     run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau)
     _check_all(oracle, w, run, q, k, v, off, ptr, range(w.n_kv_heads))
+
+
+def _decode_gpu(torch, q, kc, vc, n_sel=None, budget=0):
+    from paper_2510_22556_amd import binding as B
+
+    shape = B.make_cache_shape(q, kc, vc)
+    ws = torch.empty((B.sablock_decode_workspace_bytes(shape),), dtype=torch.uint8, device="cuda")
+    out = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda")
+    B.sablock_decode_attention(shape, q, kc, vc, out, ws, n_sel=n_sel, budget=budget)
+    torch.cuda.synchronize()
+    return H.to_np(out)
+
+
+@pytest.mark.parametrize("case", [
+    dict(G=4, Hkv=2, D=128, R=5013, dtype="bf16", nl=2, ns=1),
+    dict(G=1, Hkv=3, D=64, R=777, dtype="bf16", nl=1, ns=2),
+    dict(G=8, Hkv=1, D=128, R=2, dtype="bf16", nl=1, ns=1),
+    dict(G=2, Hkv=2, D=256, R=1500, dtype="bf16", nl=1, ns=1),
+    dict(G=4, Hkv=2, D=64, R=3001, dtype="f32", nl=1, ns=1),
+    dict(G=2, Hkv=1, D=16, R=130, dtype="f32", nl=3, ns=1),
+])
+def test_decode_attention_full_cache(oracle, torch_cuda, case):
+    # one decode step over an uncompressed cache given as a strided view (row stride 2 D), ragged row counts
+    torch = torch_cuda
+    G, Hkv, D, R, nl, ns = case["G"], case["Hkv"], case["D"], case["R"], case["nl"], case["ns"]
+    dt = torch.float32 if case["dtype"] == "f32" else torch.bfloat16
+    q = synth.normal_torch(900 + R, 1, (ns, nl, G * Hkv, D), "cuda", dt)
+    kc = synth.normal_torch(900 + R, 2, (ns, nl, Hkv, R, 2 * D), "cuda", dt)[..., :D]
+    vc = synth.normal_torch(900 + R, 3, (ns, nl, Hkv, R, 2 * D), "cuda", dt)[..., D:]
+    kc[0, 0, 0, R // 2] = (q[0, 0, 1 % (G * Hkv)].float() * 3.0).to(dt)        # a peaked row for one head
+    out = _decode_gpu(torch, q, kc, vc)
+    for s in range(ns):
+        for l in range(nl):
+            for h in range(Hkv):
+                ref = oracle.decode_attention(H.widen(H.to_np(q[s, l, h * G:(h + 1) * G])),
+                                              H.widen(H.to_np(kc[s, l, h].contiguous())),
+                                              H.widen(H.to_np(vc[s, l, h].contiguous())))
+                np.testing.assert_allclose(out[s, l, h * G:(h + 1) * G], ref, rtol=2e-4, atol=2e-5)
+
+
+def test_decode_attention_over_the_compacted_cache(oracle, torch_cuda):
+    # configuration 2 through the five calls, then one decode step over the cache they leave: the retained rows
+    # and the window rows count, the zero-filled gap behind n_sel does not (n_sel lowered by hand for two problems)
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    w = synth.WORKLOADS["llama8b_8k"]
+    q, k, v, off, ptr = _device_workload(torch, w)
+    shape = B.make_shape(q, k, v)
+    seg = B.make_segments(off, ptr, "cuda")
+    budget = w.budget()
+    buf = B.Buffers(shape, seg, budget, "cuda")
+    B.compress(shape, q, k, v, seg, w.cand, budget, buf, w.eps, w.alpha, w.eta, w.tau)
+    n_sel = buf.n_sel.clone()
+    n_sel[1] -= 7
+    n_sel[5] = 0
+    rows = budget + w.window
+    kc = buf.k_out.view(w.n_seq, w.n_layers, w.n_kv_heads, rows, w.head_dim)
+    vc = buf.v_out.view(w.n_seq, w.n_layers, w.n_kv_heads, rows, w.head_dim)
+    qn = synth.normal_torch(4321, 1, (w.n_seq, w.n_layers, w.n_q_heads, w.head_dim), "cuda", torch.bfloat16)
+    out = _decode_gpu(torch, qn, kc, vc, n_sel=n_sel, budget=budget)
+    ns = H.to_np(n_sel)
+    for p in range(w.n_kv_heads):
+        keep = np.r_[0:ns[p], budget:rows]
+        ref = oracle.decode_attention(H.widen(H.to_np(qn[0, 0, p * w.G:(p + 1) * w.G])),
+                                      H.widen(H.to_np(kc[0, 0, p]))[keep], H.widen(H.to_np(vc[0, 0, p]))[keep])
+        np.testing.assert_allclose(out[0, 0, p * w.G:(p + 1) * w.G], ref, rtol=2e-4, atol=2e-5)
+    # the same cache without the gap information differs where rows were dropped by hand
+    out_all = _decode_gpu(torch, qn, kc, vc)
+    assert not np.allclose(out_all[0, 0, 5 * w.G], out[0, 0, 5 * w.G], rtol=1e-3, atol=1e-4)
+
+
+def test_decode_attention_128k_full_and_compacted(oracle, torch_cuda):
+    # the benchmark's shapes (4 of the 32 layers): full 131 072-row cache and the 1 024-entry cache, sampled problems
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+    import dataclasses
+
+    w = dataclasses.replace(synth.WORKLOADS["llama8b_128k"], n_layers=4)
+    q, k, v, off, ptr = _device_workload(torch, w)
+    qn = synth.normal_torch(99, 1, (w.n_seq, w.n_layers, w.n_q_heads, w.head_dim), "cuda", torch.bfloat16)
+    out = _decode_gpu(torch, qn, k, v)
+    for p in (0, 13, 31):
+        l, h = divmod(p, w.n_kv_heads)
+        ref = oracle.decode_attention(H.widen(H.to_np(qn[0, l, h * w.G:(h + 1) * w.G])), H.widen(H.to_np(k[0, l, h])),
+                                      H.widen(H.to_np(v[0, l, h])))
+        np.testing.assert_allclose(out[0, l, h * w.G:(h + 1) * w.G], ref, rtol=2e-4, atol=2e-5)
+    shape = B.make_shape(q, k, v)
+    seg = B.make_segments(off, ptr, "cuda")
+    budget = w.budget()
+    buf = B.Buffers(shape, seg, budget, "cuda")
+    B.compress(shape, q, k, v, seg, w.cand, budget, buf, w.eps, w.alpha, w.eta, w.tau)
+    rows = budget + w.window
+    kc = buf.k_out.view(w.n_seq, w.n_layers, w.n_kv_heads, rows, w.head_dim)
+    vc = buf.v_out.view(w.n_seq, w.n_layers, w.n_kv_heads, rows, w.head_dim)
+    out_c = _decode_gpu(torch, qn, kc, vc, n_sel=buf.n_sel, budget=budget)
+    for p in (2, 17, 30):
+        l, h = divmod(p, w.n_kv_heads)
+        ref = oracle.decode_attention(H.widen(H.to_np(qn[0, l, h * w.G:(h + 1) * w.G])), H.widen(H.to_np(kc[0, l, h])),
+                                      H.widen(H.to_np(vc[0, l, h])))
+        np.testing.assert_allclose(out_c[0, l, h * w.G:(h + 1) * w.G], ref, rtol=2e-4, atol=2e-5)

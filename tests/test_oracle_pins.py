@@ -354,3 +354,33 @@ def test_segment_against_library_routines(oracle):
             assert not np.isin(row[a:b - 1], synth.DELIMS).any()
             assert b == len(row) or row[b - 1] in synth.DELIMS
         assert 16 < np.diff(off).mean() < 36                                       # the generator's mean length
+
+
+# ---------------------------------------------------------------- decode attention (Sec. 2.1, Eq. 1)
+def test_decode_attention_pins(oracle):
+    from scipy.special import softmax
+
+    rng = np.random.default_rng(3)
+    G, D, R = 4, 16, 37
+    q, k, v = rng.standard_normal((G, D)), rng.standard_normal((R, D)), rng.standard_normal((R, D))
+    out = oracle.decode_attention(q, k, v)
+    # library routines: softmax of the scaled logits, then a matrix product
+    np.testing.assert_allclose(out, softmax(q @ k.T / 4.0, axis=1) @ v, rtol=1e-12, atol=1e-14)
+    # q = 0: uniform weights, the mean of V; a single row: that row of V
+    np.testing.assert_allclose(oracle.decode_attention(np.zeros((G, D)), k, v), np.tile(v.mean(axis=0), (G, 1)), rtol=1e-12)
+    np.testing.assert_allclose(oracle.decode_attention(q, k[:1], v[:1]), np.tile(v[0], (G, 1)), rtol=1e-12)
+    # one-hot limit: a key aligned with the query and scaled up takes all the weight (transposed operands or a
+    # missing scale would pick another row or blur the weights)
+    k2 = k.copy(); k2[5] = 200.0 * q[2] / np.linalg.norm(q[2])
+    np.testing.assert_allclose(oracle.decode_attention(q, k2, v)[2], v[5], rtol=1e-9, atol=1e-12)
+    # the 1/sqrt(D) scale: zero-padding D -> 4D divides the logits by 2 = logits of (q/2, k) at the old D
+    pad = lambda a: np.concatenate([a, np.zeros((a.shape[0], 3 * D))], axis=1)
+    np.testing.assert_allclose(oracle.decode_attention(pad(q), pad(k), v), oracle.decode_attention(q / 2, k, v), rtol=1e-12)
+    # invariances: order of the rows, a common shift of the logits (k + c*q/|q|^2 direction per head is head-specific,
+    # so shift through an extra constant column instead)
+    perm = rng.permutation(R)
+    np.testing.assert_allclose(oracle.decode_attention(q, k[perm], v[perm]), out, rtol=1e-12, atol=1e-14)
+    q1 = np.concatenate([q, np.ones((G, 1))], axis=1); k1 = np.concatenate([k, np.full((R, 1), 7.0)], axis=1)
+    ref = softmax(q @ k.T / np.sqrt(D + 1.0), axis=1) @ v
+    np.testing.assert_allclose(oracle.decode_attention(q1, k1, v), ref, rtol=1e-12, atol=1e-14)
+    assert (oracle.decode_attention(q, k[:0], v[:0]) == 0).all()
