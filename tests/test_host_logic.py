@@ -101,6 +101,29 @@ def test_calls_reject_bad_host_arguments_before_launch(lib):
     assert lib.sablock_segment_offsets(fake, 100, 1, 100, dl, 2, (ctypes.c_int32 * 2)(0, 200), fake, None) == 1   # > T + 1
 
 
+def test_decode_calls_validate_host_arguments(lib):
+    def cache_shape(**kw):
+        s = _shape(dtype=B.SABLOCK_BF16, head_dim=128, n_q_heads=8, n_kv_heads=2, seq_len=1056, window=1)
+        for a, st in enumerate([2 * 1056 * 128, 2 * 1056 * 128, 1056 * 128, 128]):
+            s.k_stride[a] = s.v_stride[a] = st
+        for k, v in kw.items():
+            setattr(s, k, v)
+        return s
+
+    n = B.sablock_decode_workspace_bytes(cache_shape())
+    assert n > 0 and n % 256 == 0
+    fake = ctypes.c_void_p(0x1000)
+    sp = ctypes.byref(cache_shape())
+    assert lib.sablock_decode_attention(sp, None, fake, fake, None, 0, fake, fake, n, None) == 1
+    assert lib.sablock_decode_attention(sp, fake, fake, fake, None, 0, fake, fake, 16, None) == 3
+    assert lib.sablock_decode_attention(sp, fake, fake, fake, fake, 2000, fake, fake, n, None) == 1      # budget > rows
+    assert lib.sablock_decode_attention(sp, ctypes.c_void_p(0x1008), fake, fake, None, 0, fake, fake, n, None) == 1
+    for bad, status in [(dict(n_q_heads=6), 2), (dict(head_dim=24), 2), (dict(seq_len=1), 1), (dict(n_q_heads=7), 1)]:
+        with pytest.raises(B.SablockError) as ei:
+            B.sablock_decode_workspace_bytes(cache_shape(**bad))
+        assert ei.value.status == status, bad
+
+
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
