@@ -41,8 +41,11 @@ struct __attribute__((aligned(32))) SegRec {
     int32_t pad;
 };
 
-constexpr int CAPB = 256;           // blocks per segment whose Phi/class fit the wave's LDS slice
-constexpr int CAPT = 512;          // tokens per segment whose scores are staged in the wave's LDS slice
+// LDS slices of a search/select wavefront: tokens whose scores are staged, blocks whose Phi / class are kept.
+// Two sizes: the small one keeps many wavefronts resident for the bulk of the segments; segments longer than
+// CAPT go to a second list that is served by the same kernels with the large slices.
+constexpr int CAPT = 512, CAPB = 256;
+constexpr int CAPT_LONG = 4096, CAPB_LONG = 2048;
 constexpr int MAX_G = 64;           // largest candidate block size
 
 __device__ inline int wave_sum_i(int v)
@@ -149,7 +152,7 @@ __device__ inline void find_bin_from_top(const uint32_t *hist, int nbins, uint32
 }
 
 // grid (P).  With seg_budget != NULL the kernel also clears the problem's seg_budget / block_size rows, counts
-// the implicit budgets (Eq. implicit_budget) into seg_budget, and workgroup 0 clears `counter`.
+// the implicit budgets (Eq. implicit_budget) into seg_budget, and workgroup 0 clears counter[0..1].
 //
 // Selection of the k-th best score, k = min(B, T).  Usual path, two passes over the row: a histogram of the
 // keys' top 12 bits locates the bin of the k-th key; the second pass puts the tokens of higher bins straight
@@ -180,7 +183,7 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
     const int64_t row = (int64_t)p * sv.max_segments;
     if (seg_budget) {
         for (int i = tid; i < sv.max_segments; i += TB_THREADS) { seg_budget[row + i] = 0; block_size[row + i] = 0; }
-        if (counter && p == 0 && tid == 0) *counter = 0;
+        if (counter && p == 0 && tid < 2) counter[tid] = 0;
     }
 
     uint32_t prefix = 0, mask = 0, krem = (uint32_t)max(k, 0), n_eq = 0;
@@ -322,8 +325,9 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
 
 // ------------------------------------------------------------------ one segment, one block size
 struct WaveScratch {
-    double *phi;        // CAPB block sums
-    uint8_t *cls;       // CAPB block classes: 0 not taken, 1 taken whole, 2 cut to its best tokens
+    double *phi;        // block sums
+    uint8_t *cls;       // block classes: 0 not taken, 1 taken whole, 2 cut to its best tokens
+    int capb;           // blocks that fit
 };
 
 // Phi of block m of segment [a,b) with block size g: ascending fp64 sum.  `val(t)` yields s_tilde of token t
@@ -362,7 +366,7 @@ __device__ inline void segment_fill(V val, int a, int b, int g, int bk, WaveScra
     const int len = b - a;
     const int nb = (len + g - 1) / g;
     const int ts = len - (nb - 1) * g;                 // size of the last block, 1..g
-    const bool fast = nb <= CAPB;
+    const bool fast = nb <= ws.capb;
     const int mt = nb - 1;
 
     if (fast) {
@@ -485,10 +489,10 @@ constexpr int LIST_THREADS = 1024;         // threads of the per-problem list-bu
 
 __global__ void __launch_bounds__(LIST_THREADS)
 heavy_list_kernel(Dims d, SegView sv, const int32_t *thr, const int32_t *seg_budget, int32_t *block_size,
-                  SegRec *list, int32_t *counter, int capacity)
+                  SegRec *list, SegRec *list_long, int32_t *counters, int capacity)
 {
-    __shared__ int sh_w[LIST_THREADS / 64];
-    __shared__ int sh_base;
+    __shared__ int sh_w[LIST_THREADS / 64], sh_x[LIST_THREADS / 64];
+    __shared__ int sh_base[2];
     const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = seq_of_problem(d, p);
     const int32_t *off = sv.seg_off + sv.seq_ptr[seq];
@@ -499,19 +503,27 @@ heavy_list_kernel(Dims d, SegView sv, const int32_t *thr, const int32_t *seg_bud
         const int k = c0 + tid;
         const int bk = k < K ? seg_budget[row + k] : 0;
         if (k < K && bk == 1) block_size[row + k] = 1;
-        const bool hv = bk >= 2;
-        const unsigned long long bal = __ballot(hv);
-        if (lane == 0) sh_w[wave] = __popcll(bal);
+        const int a = k < K ? off[k] : 0, b = k < K ? off[k + 1] : 0;
+        const bool hv = bk >= 2 && b - a <= CAPT, hx = bk >= 2 && b - a > CAPT;
+        const unsigned long long bal = __ballot(hv), bax = __ballot(hx);
+        if (lane == 0) { sh_w[wave] = __popcll(bal); sh_x[wave] = __popcll(bax); }
         __syncthreads();
-        int before = 0, total = 0;
-        for (int w = 0; w < LIST_THREADS / 64; ++w) { if (w < wave) before += sh_w[w]; total += sh_w[w]; }
-        if (tid == 0 && total > 0) sh_base = atomicAdd(counter, total);
+        int before = 0, total = 0, before_x = 0, total_x = 0;
+        for (int w = 0; w < LIST_THREADS / 64; ++w) {
+            if (w < wave) { before += sh_w[w]; before_x += sh_x[w]; }
+            total += sh_w[w]; total_x += sh_x[w];
+        }
+        if (tid == 0 && total > 0) sh_base[0] = atomicAdd(&counters[0], total);
+        if (tid == 1 && total_x > 0) sh_base[1] = atomicAdd(&counters[1], total_x);
         __syncthreads();
-        const int pos = sh_base + before + __popcll(bal & ((1ull << lane) - 1ull));
-        if (hv && pos < capacity) {
-            SegRec r;
-            r.p = p; r.k = k; r.a = off[k]; r.b = off[k + 1]; r.bk = bk; r.g = thr_key; r.pos = thr_cut; r.pad = 0;
-            list[pos] = r;
+        if (hv || hx) {
+            const unsigned long long lt = (1ull << lane) - 1ull;
+            const int pos = hv ? sh_base[0] + before + __popcll(bal & lt) : sh_base[1] + before_x + __popcll(bax & lt);
+            if (pos < capacity) {
+                SegRec r;
+                r.p = p; r.k = k; r.a = a; r.b = b; r.bk = bk; r.g = thr_key; r.pos = thr_cut; r.pad = 0;
+                (hv ? list : list_long)[pos] = r;
+            }
         }
     }
 }
@@ -519,13 +531,14 @@ heavy_list_kernel(Dims d, SegView sv, const int32_t *thr, const int32_t *seg_bud
 // one wavefront per workgroup, striding over the call's search list
 constexpr int SEARCH_WGS = 65536;
 
+template <int CT, int CB>
 __global__ void __launch_bounds__(64)
 search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau,
               const SegRec *list, const int32_t *counter, int capacity, int32_t *block_size)
 {
-    __shared__ double sh_phi[CAPB];
-    __shared__ float sh_val[CAPT];
-    __shared__ uint8_t sh_cls[CAPB];
+    __shared__ double sh_phi[CB];
+    __shared__ float sh_val[CT];
+    __shared__ uint8_t sh_cls[CB];
     const int lane = threadIdx.x;
     int j = blockIdx.x;                                     // < capacity: the grid is no larger than the list can get
     SegRec r = list[j];                                     // fetched together with the list length
@@ -539,7 +552,7 @@ search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau
 
     // token-level baseline Score_base = sum over T_topB & S_k, ascending; segments that fit are copied to LDS
     // on the way so that the candidate loop never goes back to global memory
-    const bool staged = b - a <= CAPT;
+    const bool staged = b - a <= CT;
     double base = 0.0;
     for (int c0 = a; c0 < b; c0 += 64) {
         const int t = c0 + lane;
@@ -556,7 +569,7 @@ search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau
     int gstar = 0;
     const int gcap = min(b - a, bk);                        // G_k: g <= min(|S_k|, b_k, g_max)
     const double need = (double)tau * base;                // R_k(g) >= tau  <=>  Score_k(g) >= tau * Score_base
-    WaveScratch ws{sh_phi, sh_cls};
+    WaveScratch ws{sh_phi, sh_cls, CB};
     auto run = [&](auto val) {
         for (int c = cand.n - 1; c >= 0; --c) {
             const int g = cand.g[c];
@@ -579,19 +592,20 @@ search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau
 // ------------------------------------------------------------------ select
 __global__ void reset_counters_kernel(int32_t *counters)
 {
-    if (threadIdx.x < 2) counters[threadIdx.x] = 0;
+    if (threadIdx.x < 3) counters[threadIdx.x] = 0;
 }
 
 // One workgroup per problem: exclusive prefix of b_k over its segments (where each segment's tokens go in the
 // problem's idx_out row), n_sel, the -1 padding of idx_out.  The segments that retain anything are appended to
-// one of the call's two select lists: token-level ones (g_k* = 1) to `light`, the others to `full`.
-// counters[0] / counters[1] are the lengths of light / full.
+// one of the call's three select lists: token-level ones (g_k* = 1) to `light`, the others to `full` or, when
+// longer than CAPT tokens, to `full_long`.  counters[0..2] are the lengths of light / full / full_long.
 __global__ void __launch_bounds__(LIST_THREADS)
 seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *block_size, int budget,
-                  SegRec *light, SegRec *full, int32_t *counters, int capacity, int32_t *idx_out, int32_t *n_sel_out)
+                  SegRec *light, SegRec *full, SegRec *full_long, int32_t *counters, int capacity, int32_t *idx_out,
+                  int32_t *n_sel_out)
 {
-    __shared__ int sh_w[LIST_THREADS / 64], sh_l[LIST_THREADS / 64], sh_f[LIST_THREADS / 64];
-    __shared__ int sh_base[2];
+    __shared__ int sh_w[LIST_THREADS / 64], sh_l[LIST_THREADS / 64], sh_f[LIST_THREADS / 64], sh_x[LIST_THREADS / 64];
+    __shared__ int sh_base[3];
     const int p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = seq_of_problem(d, p);
     const int32_t *off = sv.seg_off + sv.seq_ptr[seq];
@@ -603,27 +617,32 @@ seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *
         const int k = c0 + tid;
         const int v = (k < K) ? seg_budget[row + k] : 0;
         const int g = (k < K) ? block_size[row + k] : 0;
-        const bool is_light = v > 0 && g == 1, is_full = v > 0 && g > 1;
-        const unsigned long long bl = __ballot(is_light), bf = __ballot(is_full);
+        const int sa = k < K ? off[k] : 0, sb = k < K ? off[k + 1] : 0;
+        const bool is_light = v > 0 && g == 1;
+        const bool is_full = v > 0 && g > 1 && sb - sa <= CAPT, is_long = v > 0 && g > 1 && sb - sa > CAPT;
+        const unsigned long long bl = __ballot(is_light), bf = __ballot(is_full), bx = __ballot(is_long);
         int incl = v;
         for (int o = 1; o < 64; o <<= 1) { int x = __shfl_up(incl, o); if (lane >= o) incl += x; }
         if (lane == 63) sh_w[wave] = incl;
-        if (lane == 0) { sh_l[wave] = __popcll(bl); sh_f[wave] = __popcll(bf); }
+        if (lane == 0) { sh_l[wave] = __popcll(bl); sh_f[wave] = __popcll(bf); sh_x[wave] = __popcll(bx); }
         __syncthreads();
-        int before = 0, total = 0, before_l = 0, total_l = 0, before_f = 0, total_f = 0;
+        int before = 0, total = 0, before_l = 0, total_l = 0, before_f = 0, total_f = 0, before_x = 0, total_x = 0;
         for (int w = 0; w < LIST_THREADS / 64; ++w) {
-            if (w < wave) { before += sh_w[w]; before_l += sh_l[w]; before_f += sh_f[w]; }
-            total += sh_w[w]; total_l += sh_l[w]; total_f += sh_f[w];
+            if (w < wave) { before += sh_w[w]; before_l += sh_l[w]; before_f += sh_f[w]; before_x += sh_x[w]; }
+            total += sh_w[w]; total_l += sh_l[w]; total_f += sh_f[w]; total_x += sh_x[w];
         }
         if (tid == 0 && total_l > 0) sh_base[0] = atomicAdd(&counters[0], total_l);
         if (tid == 1 && total_f > 0) sh_base[1] = atomicAdd(&counters[1], total_f);
+        if (tid == 2 && total_x > 0) sh_base[2] = atomicAdd(&counters[2], total_x);
         __syncthreads();
-        if (is_light || is_full) {
-            const int slot = is_light ? sh_base[0] + before_l + __popcll(bl & lt) : sh_base[1] + before_f + __popcll(bf & lt);
+        if (is_light || is_full || is_long) {
+            const int slot = is_light ? sh_base[0] + before_l + __popcll(bl & lt)
+                           : is_full ? sh_base[1] + before_f + __popcll(bf & lt)
+                                     : sh_base[2] + before_x + __popcll(bx & lt);
             if (slot < capacity) {
                 SegRec r;
-                r.p = p; r.k = k; r.a = off[k]; r.b = off[k + 1]; r.bk = v; r.g = g; r.pos = carry + before + incl - v; r.pad = 0;
-                (is_light ? light : full)[slot] = r;
+                r.p = p; r.k = k; r.a = sa; r.b = sb; r.bk = v; r.g = g; r.pos = carry + before + incl - v; r.pad = 0;
+                (is_light ? light : is_full ? full : full_long)[slot] = r;
             }
         }
         carry += total;
@@ -635,12 +654,12 @@ seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *
 
 // Token-level segments, sixteen lanes each (most retaining segments hold one or two Top-B tokens, so a wavefront
 // per segment would mostly idle): T_k(1) = T_topB & S_k when b_k is the implicit budget, written in ascending
-// order.  A segment whose b_k is something else (a caller's own budgets) is passed on to the full list.
+// order.  A segment whose b_k is something else (a caller's own budgets) is passed on to one of the full lists.
 constexpr int LIGHT_GROUP = 16;
 
 __global__ void __launch_bounds__(256)
 select_light_kernel(Dims d, const float *s_tilde, const int32_t *thr, const SegRec *light, SegRec *full,
-                    int32_t *counters, int capacity, int budget, int32_t *idx_out)
+                    SegRec *full_long, int32_t *counters, int capacity, int budget, int32_t *idx_out)
 {
     const int sub = threadIdx.x & (LIGHT_GROUP - 1);
     const int j = blockIdx.x * (256 / LIGHT_GROUP) + threadIdx.x / LIGHT_GROUP;       // < capacity rounded up
@@ -665,15 +684,17 @@ select_light_kernel(Dims d, const float *s_tilde, const int32_t *thr, const SegR
         cnt += __popc(gm);
     }
     if (cnt != bk && sub == 0) {
-        const int slot = atomicAdd(&counters[1], 1);
-        if (slot < capacity) full[slot] = r;
+        const bool lng = b - a > CAPT;
+        const int slot = atomicAdd(&counters[lng ? 2 : 1], 1);
+        if (slot < capacity) (lng ? full_long : full)[slot] = r;
     }
 }
 
 // T_k(g_k*) of one listed segment, written in ascending order from its offset in idx_out
+template <int CT, int CB>
 __device__ inline void select_segment(const Dims &d, const float *s_tilde, const int32_t *thr, const SegRec &r,
-                                      int budget, int32_t *idx_out, double (&sh_phi)[CAPB], float (&sh_val)[CAPT],
-                                      uint8_t (&sh_cls)[CAPB])
+                                      int budget, int32_t *idx_out, double (&sh_phi)[CB], float (&sh_val)[CT],
+                                      uint8_t (&sh_cls)[CB])
 {
     const int lane = threadIdx.x & 63;
     const int p = r.p, a = r.a, b = r.b;
@@ -713,8 +734,8 @@ __device__ inline void select_segment(const Dims &d, const float *s_tilde, const
             }
         }
     }
-    WaveScratch ws{sh_phi, sh_cls};
-    if (b - a <= CAPT) {
+    WaveScratch ws{sh_phi, sh_cls, CB};
+    if (b - a <= CT) {
         float *lv = sh_val;
         for (int t = a + lane; t < b; t += 64) lv[t - a] = sp[t];
         __builtin_amdgcn_wave_barrier();
@@ -729,18 +750,19 @@ __device__ inline void select_segment(const Dims &d, const float *s_tilde, const
 // one wavefront per workgroup, striding over the call's select list
 constexpr int SELECT_WGS = 32768;
 
+template <int CT, int CB>
 __global__ void __launch_bounds__(64)
 select_kernel(Dims d, const float *s_tilde, const int32_t *thr, const SegRec *list, const int32_t *counter,
               int capacity, int budget, int32_t *idx_out)
 {
-    __shared__ double sh_phi[CAPB];
-    __shared__ float sh_val[CAPT];
-    __shared__ uint8_t sh_cls[CAPB];
+    __shared__ double sh_phi[CB];
+    __shared__ float sh_val[CT];
+    __shared__ uint8_t sh_cls[CB];
     int j = blockIdx.x;                                     // < capacity: the grid is no larger than the list can get
     SegRec r = list[j];                                     // fetched together with the list length
     const int n_list = min(*counter, capacity);
     for (; j < n_list; j += gridDim.x, r = list[min(j, capacity - 1)]) {
-        select_segment(d, s_tilde, thr, r, budget, idx_out, sh_phi, sh_val, sh_cls);
+        select_segment<CT, CB>(d, s_tilde, thr, r, budget, idx_out, sh_phi, sh_val, sh_cls);
         __builtin_amdgcn_wave_barrier();                    // the LDS slices are reused by the next segment
     }
 }
@@ -764,10 +786,12 @@ static size_t max_heavy_segments(const Dims &d, int32_t max_segments, int32_t bu
     return (size_t)d.P * (size_t)(h > 0 ? h : 0);
 }
 
+constexpr int LONG_WGS = 8192;             // workgroups of the kernels that serve the lists of long segments
+
 size_t search_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget)
 {
     const size_t cap = max_heavy_segments(d, max_segments, budget);
-    return align256((size_t)d.P * 2 * 4) + align256(4) + align256((cap > 0 ? cap : 1) * sizeof(SegRec));
+    return align256((size_t)d.P * 2 * 4) + align256(8) + 2 * align256((cap > 0 ? cap : 1) * sizeof(SegRec));
 }
 
 hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
@@ -779,22 +803,27 @@ hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv,
     char *w = static_cast<char *>(ws);
     int32_t *thr = topb_out ? topb_out : reinterpret_cast<int32_t *>(w);
     w += align256((size_t)d.P * 2 * 4);
-    int32_t *counter = reinterpret_cast<int32_t *>(w);
-    w += align256(4);
+    int32_t *counters = reinterpret_cast<int32_t *>(w);
+    w += align256(8);
     SegRec *list = reinterpret_cast<SegRec *>(w);
+    w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
+    SegRec *list_long = reinterpret_cast<SegRec *>(w);
     hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, sv, seg_budget,
-                       block_size, counter);
+                       block_size, counters);
     if (budget > 0 && d.T > 0) {
-        hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, thr, seg_budget, block_size, list,
-                           counter, (int)cap);
-        if (cap > 0)
-            hipLaunchKernelGGL(search_kernel, dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64), 0, st, d,
-                               s_tilde, sv, cand, tau, list, counter, (int)cap, block_size);
+        hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, thr, seg_budget, block_size,
+                           list, list_long, counters, (int)cap);
+        if (cap > 0) {
+            hipLaunchKernelGGL((search_kernel<CAPT, CAPB>), dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64),
+                               0, st, d, s_tilde, sv, cand, tau, list, counters, (int)cap, block_size);
+            hipLaunchKernelGGL((search_kernel<CAPT_LONG, CAPB_LONG>), dim3((unsigned)(cap < LONG_WGS ? cap : LONG_WGS)),
+                               dim3(64), 0, st, d, s_tilde, sv, cand, tau, list_long, counters + 1, (int)cap, block_size);
+        }
     }
     return hipGetLastError();
 }
 
-// upper bound of the select list: a listed segment retains at least one token of its problem's budget
+// upper bound of the select lists: a listed segment retains at least one token of its problem's budget
 static size_t max_active_segments(const Dims &d, int32_t max_segments, int32_t budget)
 {
     const int a = budget < max_segments ? budget : max_segments;
@@ -804,7 +833,7 @@ static size_t max_active_segments(const Dims &d, int32_t max_segments, int32_t b
 size_t select_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget)
 {
     const size_t cap = max_active_segments(d, max_segments, budget);
-    return align256((size_t)d.P * 2 * 4) + align256(8) + 2 * align256((cap > 0 ? cap : 1) * sizeof(SegRec));
+    return align256((size_t)d.P * 2 * 4) + align256(12) + 3 * align256((cap > 0 ? cap : 1) * sizeof(SegRec));
 }
 
 hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv, const int32_t *seg_budget,
@@ -813,14 +842,15 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
 {
     if (d.P <= 0) return hipSuccess;
     const size_t cap = max_active_segments(d, sv.max_segments, budget);
+    const size_t list_bytes = align256((cap > 0 ? cap : 1) * sizeof(SegRec));
     char *w = static_cast<char *>(ws);
     int32_t *thr_ws = reinterpret_cast<int32_t *>(w);
     w += align256((size_t)d.P * 2 * 4);
     int32_t *counters = reinterpret_cast<int32_t *>(w);
-    w += align256(8);
+    w += align256(12);
     SegRec *light = reinterpret_cast<SegRec *>(w);
-    w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
-    SegRec *full = reinterpret_cast<SegRec *>(w);
+    SegRec *full = reinterpret_cast<SegRec *>(w + list_bytes);
+    SegRec *full_long = reinterpret_cast<SegRec *>(w + 2 * list_bytes);
     const int32_t *thr = topb;
     if (!thr) {
         hipError_t e = launch_topb(d, s_tilde, budget, thr_ws, st);
@@ -828,14 +858,16 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
         thr = thr_ws;
     }
     hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, counters);
-    hipLaunchKernelGGL(seg_prefix_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, seg_budget, block_size, budget, light,
-                       full, counters, (int)cap, idx_out, n_sel_out);
+    hipLaunchKernelGGL(seg_prefix_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, seg_budget, block_size, budget,
+                       light, full, full_long, counters, (int)cap, idx_out, n_sel_out);
     if (cap > 0) {
         const unsigned per_wg = 256 / LIGHT_GROUP;
         hipLaunchKernelGGL(select_light_kernel, dim3((unsigned)((cap + per_wg - 1) / per_wg)), dim3(256), 0, st, d,
-                           s_tilde, thr, light, full, counters, (int)cap, budget, idx_out);
-        hipLaunchKernelGGL(select_kernel, dim3((unsigned)(cap < SELECT_WGS ? cap : SELECT_WGS)), dim3(64), 0, st, d,
-                           s_tilde, thr, full, counters + 1, (int)cap, budget, idx_out);
+                           s_tilde, thr, light, full, full_long, counters, (int)cap, budget, idx_out);
+        hipLaunchKernelGGL((select_kernel<CAPT, CAPB>), dim3((unsigned)(cap < SELECT_WGS ? cap : SELECT_WGS)), dim3(64), 0,
+                           st, d, s_tilde, thr, full, counters + 1, (int)cap, budget, idx_out);
+        hipLaunchKernelGGL((select_kernel<CAPT_LONG, CAPB_LONG>), dim3((unsigned)(cap < LONG_WGS ? cap : LONG_WGS)), dim3(64),
+                           0, st, d, s_tilde, thr, full_long, counters + 2, (int)cap, budget, idx_out);
     }
     return hipGetLastError();
 }
