@@ -1,4 +1,4 @@
-// MFMA window scoring (Sec. 3.2, Eqs. barA, st, Dk) for bf16, D = 128, G = 4, W = 32.
+// MFMA window scoring (Sec. 3.2, Eqs. barA, st, Dk) for bf16, D = 128, G = 4, W = 32 or 64.
 //
 // The window-query rows of a KV head (4 query heads x 32 window queries) stay in
 // accumulation registers as MFMA A operands; keys are the B operand, 32 per
@@ -26,6 +26,12 @@
 // multiplied while head h-1 is exponentiated, which overlaps the matrix pipe
 // with the exp/log work inside one wavefront (one wavefront per SIMD).
 // One launch per pass covers every problem of the call.
+//
+// W = 64 (256 window-query rows per KV head).  The row statistics are independent per row, so pass 1 runs the
+// same kernel on the two halves of the window as if they were two problems (K is streamed once per half).
+// Pass 2 needs all 64 queries of a key together (head mean, column sum, entropy), so a variant of the column
+// kernel keeps all eight 32-row tiles as A operands (256 accumulation registers), the keys in ordinary
+// registers and the C operands in LDS.
 #include "sablock_internal.h"
 
 #include <cstdlib>
@@ -58,10 +64,11 @@ struct ScoreArgs {
     int p0;                // first problem of the group
     int chunk_len;         // keys per workgroup, multiple of STRIDE
     int n_chunks;          // workgroups per problem
+    int nv;                // 32-query blocks per problem in pass 1 (W / 32)
     float c1;              // log2(e) / sqrt(D)
     float eps;
-    float *partial;        // pass 1 out / pass 2 in: [group problem][chunk][128][2] (reference, sum), log2 domain
-    const float *lse;      // pass 2 in, optional: [P][128] natural-log sum-exp per row (NULL: use partial)
+    float *partial;        // pass 1 out / pass 2 in: [problem][query block][chunk][128][2] (reference, sum), log2 domain
+    const float *lse;      // pass 2 in, optional: [P][G * W] natural-log sum-exp per row (NULL: use partial)
     float *s_out, *e_out;  // pass 2 out: [P][L]
 };
 
@@ -112,6 +119,7 @@ __device__ __forceinline__ void wait_loads(int subtiles_after)
 struct WaveWork {
     const uint16_t *kp;    // keys of the problem
     int p, pl, chunk;
+    int pv, qoff;          // pass 1: (problem, query block) index and the block's first window query
     int first, n_sub;      // this stream's subtiles: keys [first + u * STRIDE, +SUB), u < n_sub
 };
 
@@ -122,12 +130,25 @@ __device__ __forceinline__ WaveWork wave_work(const ScoreArgs &a, int stream)
     w.pl = blockIdx.x / a.n_chunks;
     w.chunk = blockIdx.x - w.pl * a.n_chunks;
     w.p = a.p0 + w.pl;
+    w.pv = w.p;
+    w.qoff = 0;
     w.kp = a.k + k_problem_offset(a.d, w.p);
     const int lo = w.chunk * a.chunk_len;
     const int hi = min(lo + a.chunk_len, a.d.L);
     w.first = lo + stream * SUB;
     const int span = hi - w.first;
     w.n_sub = span > 0 ? (span + STRIDE - 1) / STRIDE : 0;
+    return w;
+}
+
+// pass 1: workgroups are indexed by ((problem, query block), chunk)
+__device__ __forceinline__ WaveWork wave_work_blocks(const ScoreArgs &a, int stream)
+{
+    WaveWork w = wave_work(a, stream);
+    w.pv = a.p0 * a.nv + w.pl;
+    w.p = w.pv / a.nv;
+    w.qoff = (w.pv - w.p * a.nv) * 32;
+    w.kp = a.k + k_problem_offset(a.d, w.p);
     return w;
 }
 
@@ -141,6 +162,18 @@ __device__ __forceinline__ void read_subtile_acc(uint32_t lane_addr, bf16x8 (&kb
         asm volatile("ds_read_b128 %0, %1" : "=a"(kb[s]) : "v"(lane_addr ^ (uint32_t)(s << 5)) : "memory");
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+a"(kb[0]), "+a"(kb[1]), "+a"(kb[2]), "+a"(kb[3]), "+a"(kb[4]), "+a"(kb[5]), "+a"(kb[6]), "+a"(kb[7])
+                 :
+                 : "memory");
+}
+
+// the same into ordinary registers (for the kernel whose accumulation registers are all taken by A operands)
+__device__ __forceinline__ void read_subtile_vgpr(uint32_t lane_addr, bf16x8 (&kb)[8])
+{
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+        asm volatile("ds_read_b128 %0, %1" : "=v"(kb[s]) : "v"(lane_addr ^ (uint32_t)(s << 5)) : "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(kb[0]), "+v"(kb[1]), "+v"(kb[2]), "+v"(kb[3]), "+v"(kb[4]), "+v"(kb[5]), "+v"(kb[6]), "+v"(kb[7])
                  :
                  : "memory");
 }
@@ -193,6 +226,12 @@ struct KeyStream {
         read_subtile_acc(lane_addr0 + (u % NBUF) * BUF_BYTES, kb);
         if (u + NBUF < n_sub) issue(u + NBUF);
     }
+    __device__ __forceinline__ void fetch_vgpr(int u, bf16x8 (&kb)[8]) const
+    {
+        wait_loads(min(NBUF - 1, n_sub - 1 - u));
+        read_subtile_vgpr(lane_addr0 + (u % NBUF) * BUF_BYTES, kb);
+        if (u + NBUF < n_sub) issue(u + NBUF);
+    }
 };
 
 // A operands: the window queries of the four heads, query row `n`, k-slices (2s + hf) * 8 .. +8, into
@@ -201,7 +240,7 @@ __device__ __forceinline__ void load_queries(bf16x8 (&qa)[4][8], const uint16_t 
 {
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-        const uint16_t *row = q + q_row_offset(d, p, h, n);
+        const uint16_t *row = q + q_row_offset(d, p, h, n);   // n: window query of this lane
 #pragma unroll
         for (int s = 0; s < 8; ++s) qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
     }
@@ -340,14 +379,15 @@ score_mfma_stats(ScoreArgs a)
     char *ring = lds + wave_u * RING_BYTES;
     float *wg_red = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [WAVES][128][2]
     float *cref = wg_red + WAVES * M_ROWS * 2 + wave_u * M_ROWS;               // [4 heads][2 halves][16], this wave's
-    const WaveWork w = wave_work(a, wave);
+    const WaveWork w = wave_work_blocks(a, wave);
+    const int Tq = d.T + w.qoff;                               // causal limit of this block's query 0: key t is visible to query i iff t <= Tq + i
 
     KeyStream<NBUF> ks;
     ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
     ks.prime();
 
     bf16x8 qa[4][8];
-    load_queries(qa, a.q, d, w.p, n, hf);
+    load_queries(qa, a.q, d, w.p, w.qoff + n, hf);
     cref[lane] = 0.f;
     cref[lane + 64] = 0.f;
 
@@ -376,8 +416,8 @@ score_mfma_stats(ScoreArgs a)
         if (plain) code = stats_fast(qa, kb, acc, cr, z, a.c1, lim);
         if (code == STATS_OK) { waiting = true; continue; }
         if (waiting && (!plain || code == STATS_PREV))         // the waiting head was not reduced by the fast body
-            stats_head_careful(acc[1], z[3], cref + 96, a.c1, false, t0 - STRIDE + n, hf, n, d.T, d.L);
-        stats_careful(qa, kb, cref, z, a.c1, (plain && code != STATS_PREV) ? code : 0, u == 0, t0 + n, hf, n, d.T, d.L);
+            stats_head_careful(acc[1], z[3], cref + 96, a.c1, false, t0 - STRIDE + n, hf, n, Tq, d.L);
+        stats_careful(qa, kb, cref, z, a.c1, (plain && code != STATS_PREV) ? code : 0, u == 0, t0 + n, hf, n, Tq, d.L);
         waiting = false;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[1][i] = -INFINITY;
@@ -385,7 +425,7 @@ score_mfma_stats(ScoreArgs a)
         for (int h = 0; h < 4; ++h) cr[h] = load_cref(cref, h, hf);     // the careful body may have moved references
     }
     if (waiting)
-        stats_head_careful(acc[1], z[3], cref + 96, a.c1, false, w.first + (w.n_sub - 1) * STRIDE + n, hf, n, d.T, d.L);
+        stats_head_careful(acc[1], z[3], cref + 96, a.c1, false, w.first + (w.n_sub - 1) * STRIDE + n, hf, n, Tq, d.L);
 
     // ---- per row: add the 32 lane sums (same reference) through the wavefront's ring (every load has landed),
     // then combine the four wavefronts' (reference, sum) pairs
@@ -418,7 +458,7 @@ score_mfma_stats(ScoreArgs a)
             const float *e = wg_red + (wv * M_ROWS + row) * 2;
             if (e[1] > 0.f) zz += e[1] * __builtin_amdgcn_exp2f(e[0] - m);
         }
-        float *o = a.partial + (((int64_t)w.p * a.n_chunks + w.chunk) * M_ROWS + row) * 2;
+        float *o = a.partial + (((int64_t)w.pv * a.n_chunks + w.chunk) * M_ROWS + row) * 2;
         o[0] = m;
         o[1] = zz;
     }
@@ -583,6 +623,157 @@ score_mfma_columns(ScoreArgs a)
     }
 }
 
+// ------------------------------------------------------------------ pass 2, W = 64
+// Eight 32-row tiles: tile j holds head j / 2, window queries 32 (j % 2) .. +32.  Same pipeline as above with the
+// tiles rotating through two accumulators; ab[v] collects the head mean of query block v.
+constexpr int M_ROWS64 = 256;
+constexpr int P2W_LDS = 4 * 4 * BUF_BYTES + M_ROWS64 * 4 + 8 * 32 * 4;   // rings + the rows' log-sum-exp + C operands
+
+__device__ __forceinline__ float columns_finish64(const float (&ab)[2][16], float eps, int hf)
+{
+    float s_part = 0.f;
+#pragma unroll
+    for (int v = 0; v < 2; ++v)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s_part += ab[v][i];
+    const float s = add_other_half(s_part);
+    const float inv_s = s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f;
+    float e_part = 0.f;
+#pragma unroll
+    for (int v = 0; v < 2; ++v)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float ah = ab[v][i] * inv_s;
+            e_part = fmaf(ah, __builtin_amdgcn_logf(ah + eps), e_part);
+        }
+    const float ent = -LN2 * add_other_half(e_part);
+    return hf == 0 ? s : ent;
+}
+
+__device__ __forceinline__ floatx16 load_c64(const float *cmat, int j, int hf)
+{
+    return *reinterpret_cast<const floatx16 *>(cmat + j * 32 + hf * 16);
+}
+
+// One subtile; returns the output value of the PREVIOUS subtile (its last tile waits in acc[1])
+template <bool EDGE>
+__device__ __forceinline__ float columns_body64(const bf16x8 (&qa)[8][8], const bf16x8 (&kb)[8], const float *cmat,
+                                                floatx16 (&acc)[2], float (&ab)[2][16], float c1, float eps, int t_prev,
+                                                int t_cur, int hf, int T, int L)
+{
+    acc[0] = chain<0, 8>(qa[0], kb, load_c64(cmat, 0, hf));
+    columns_head<EDGE, false>(acc[1], ab[1], c1, t_prev, hf, T + 32, L);      // tile 7 of the previous subtile
+    const float prev = columns_finish64(ab, eps, hf);
+    acc[1] = chain<0, 8>(qa[1], kb, load_c64(cmat, 1, hf));
+    columns_head<EDGE, true>(acc[0], ab[0], c1, t_cur, hf, T, L);             // head 0, queries 0..31
+    acc[0] = chain<0, 8>(qa[2], kb, load_c64(cmat, 2, hf));
+    columns_head<EDGE, true>(acc[1], ab[1], c1, t_cur, hf, T + 32, L);        // head 0, queries 32..63
+    acc[1] = chain<0, 8>(qa[3], kb, load_c64(cmat, 3, hf));
+    columns_head<EDGE, false>(acc[0], ab[0], c1, t_cur, hf, T, L);
+    acc[0] = chain<0, 8>(qa[4], kb, load_c64(cmat, 4, hf));
+    columns_head<EDGE, false>(acc[1], ab[1], c1, t_cur, hf, T + 32, L);
+    acc[1] = chain<0, 8>(qa[5], kb, load_c64(cmat, 5, hf));
+    columns_head<EDGE, false>(acc[0], ab[0], c1, t_cur, hf, T, L);
+    acc[0] = chain<0, 8>(qa[6], kb, load_c64(cmat, 6, hf));
+    columns_head<EDGE, false>(acc[1], ab[1], c1, t_cur, hf, T + 32, L);
+    acc[1] = chain<0, 8>(qa[7], kb, load_c64(cmat, 7, hf));
+    columns_head<EDGE, false>(acc[0], ab[0], c1, t_cur, hf, T, L);
+    return prev;
+}
+
+__global__ void __launch_bounds__(WAVES * 64)
+score_mfma_columns64(ScoreArgs a)
+{
+    extern __shared__ __attribute__((aligned(8192))) char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, hf = lane >> 5;
+    const Dims &d = a.d;
+    char *ring = lds + __builtin_amdgcn_readfirstlane(wave) * RING_BYTES;
+    float *lse2 = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [256] log2-domain lse + log2 G, row h * 64 + i
+    float *cmat = lse2 + M_ROWS64;                                           // [8 tiles][2 halves][16] C operands
+    const WaveWork w = wave_work(a, wave);
+
+    KeyStream<NBUF> ks;
+    ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
+    ks.prime();
+
+    // one thread per row: its log-sum-exp, given by the caller or folded from the chunk partials of pass 1
+    // (stored per 32-query block: block v of head h, query i % 32 is row h * 32 + i % 32 of block v)
+    {
+        const int r = threadIdx.x, h = r >> 6, i = r & 63, v = i >> 5;
+        float m = -INFINITY, zz = 0.f;
+        if (a.lse) {
+            m = a.lse[(int64_t)w.p * M_ROWS64 + r] * LOG2E;
+            zz = 1.f;
+        } else {
+            const float *pp = a.partial + (((int64_t)(w.p * 2 + v) * a.n_chunks) * M_ROWS + h * 32 + (i & 31)) * 2;
+            for (int c = 0; c < a.n_chunks; ++c) {
+                const float2 e = *reinterpret_cast<const float2 *>(pp + (int64_t)c * M_ROWS * 2);
+                if (e.y > 0.f) {
+                    const float mn = fmaxf(m, e.x);
+                    zz = zz * __builtin_amdgcn_exp2f(m - mn) + e.y * __builtin_amdgcn_exp2f(e.x - mn);
+                    m = mn;
+                }
+            }
+        }
+        lse2[r] = m + __builtin_amdgcn_logf(zz) + 2.0f;                      // + log2(G): exp2 then yields A / G
+    }
+    __syncthreads();
+    {
+        const float inv_c1 = 1.0f / a.c1;
+        const int j = threadIdx.x >> 5, slot = threadIdx.x & 31;
+        const int i = 32 * (j & 1) + query_of(slot & 15, slot >> 4);
+        cmat[threadIdx.x] = -lse2[(j >> 1) * 64 + i] * inv_c1;
+    }
+    __syncthreads();
+
+    bf16x8 qa[8][8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint16_t *row = a.q + q_row_offset(d, w.p, j >> 1, 32 * (j & 1) + n);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) qa[j][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qa[j][s]));       // all 256 accumulation registers
+
+    floatx16 acc[2];
+    float ab[2][16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc[0][i] = acc[1][i] = -INFINITY; ab[0][i] = ab[1][i] = 0.f; }
+    float *out = (hf == 0 ? a.s_out : a.e_out) + (int64_t)w.p * d.L;
+
+    float pending = 0.f;
+    int pending_t = -1;
+    const int n_plain = w.first + SUB <= d.T ? min(w.n_sub, (d.T - SUB - w.first) / STRIDE + 1) : 0;
+    int u = 0;
+    for (; u < n_plain; ++u) {
+        if (pending_t >= 0) out[pending_t] = pending;
+        bf16x8 kb[8];
+        ks.fetch_vgpr(u, kb);
+        const int t_cur = w.first + u * STRIDE + n;
+        pending = columns_body64<false>(qa, kb, cmat, acc, ab, a.c1, a.eps, t_cur - STRIDE, t_cur, hf, d.T, d.L);
+        pending_t = u > 0 ? t_cur - STRIDE : -1;
+    }
+    for (; u < w.n_sub; ++u) {
+        if (pending_t >= 0 && pending_t < d.L) out[pending_t] = pending;
+        bf16x8 kb[8];
+        ks.fetch_vgpr(u, kb);
+        const int t_cur = w.first + u * STRIDE + n;
+        pending = columns_body64<true>(qa, kb, cmat, acc, ab, a.c1, a.eps, t_cur - STRIDE, t_cur, hf, d.T, d.L);
+        pending_t = u > 0 ? t_cur - STRIDE : -1;
+    }
+    if (pending_t >= 0 && pending_t < d.L) out[pending_t] = pending;
+    if (w.n_sub > 0) {
+        const int t_last = w.first + (w.n_sub - 1) * STRIDE + n;
+        columns_head<true, false>(acc[1], ab[1], a.c1, t_last, hf, d.T + 32, d.L);
+        const float v = columns_finish64(ab, a.eps, hf);
+        if (t_last < d.L) out[t_last] = v;
+    }
+}
+
 struct Plan {
     int chunk_len;    // keys per workgroup
     int n_chunks;     // workgroups per problem
@@ -606,13 +797,13 @@ Plan make_plan(const Dims &d)
 
 bool score_mfma_supported(const Dims &d)
 {
-    return d.dtype == SABLOCK_BF16 && d.D == 128 && d.G == 4 && d.W == 32;
+    return d.dtype == SABLOCK_BF16 && d.D == 128 && d.G == 4 && (d.W == 32 || d.W == 64);
 }
 
 size_t score_mfma_ws_bytes(const Dims &d)
 {
     Plan pl = make_plan(d);
-    return align256((size_t)d.P * pl.n_chunks * M_ROWS * 2 * 4);
+    return align256((size_t)d.P * (d.W / 32) * pl.n_chunks * M_ROWS * 2 * 4);
 }
 
 hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
@@ -625,6 +816,9 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, P2_LDS);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns64),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, P2W_LDS);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
@@ -642,9 +836,12 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.partial = static_cast<float *>(ws);
     a.lse = row_lse;
     a.p0 = 0;
+    a.nv = d.W / 32;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
-    if (!row_lse) hipLaunchKernelGGL(score_mfma_stats, grid, dim3(WAVES * 64), P1_LDS, st, a);
-    hipLaunchKernelGGL(score_mfma_columns, grid, dim3(WAVES * 64), P2_LDS, st, a);
+    dim3 grid1((unsigned)((int64_t)d.P * a.nv * pl.n_chunks));
+    if (!row_lse) hipLaunchKernelGGL(score_mfma_stats, grid1, dim3(WAVES * 64), P1_LDS, st, a);
+    if (d.W == 64) hipLaunchKernelGGL(score_mfma_columns64, grid, dim3(WAVES * 64), P2W_LDS, st, a);
+    else hipLaunchKernelGGL(score_mfma_columns, grid, dim3(WAVES * 64), P2_LDS, st, a);
     return hipGetLastError();
 }
 

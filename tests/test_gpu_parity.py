@@ -267,6 +267,35 @@ def test_row_lse_input_equals_internal_pass(oracle, torch_cuda):
     np.testing.assert_allclose(H.to_np(buf.ent), e0, rtol=2e-5, atol=1e-6)
 
 
+@pytest.mark.parametrize("W", [32, 64])
+def test_mfma_row_lse_input_equals_internal_pass(oracle, torch_cuda, W):
+    # the MFMA shapes: scores from the caller's fp64 row log-sum-exp equal those of the two-pass run
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+    from scipy.special import logsumexp
+
+    L, D, G, Hkv = 5000 + W, 128, 4, 2
+    T = L - W
+    q = synth.normal_torch(61, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(61, 2, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    shape = B.make_shape(q, k)
+    seg = B.make_segments(np.array([0, T], dtype=np.int32), [0, 2], "cuda")
+    buf = B.Buffers(shape, seg, 16, "cuda")
+    B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, 1e-6)
+    s0, e0 = H.to_np(buf.s).copy(), H.to_np(buf.ent).copy()
+    qn, kn = H.widen(H.to_np(q[0, 0])), H.widen(H.to_np(k[0, 0]))
+    lse = np.zeros((1, 1, G * Hkv, W), dtype=np.float32)
+    for h in range(G * Hkv):
+        x = qn[h] @ kn[h // G].T / np.sqrt(D)
+        for i in range(W):
+            lse[0, 0, h, i] = logsumexp(x[i, :T + i + 1])
+    B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, 1e-6, row_lse=torch.as_tensor(lse).cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(H.to_np(buf.s), s0, rtol=2e-5, atol=1e-9)
+    np.testing.assert_allclose(H.to_np(buf.ent), e0, rtol=2e-5, atol=1e-6)
+    assert np.allclose(s0.sum(axis=1), W, rtol=1e-4)
+
+
 def test_mfma_score_long_ragged_with_heavy_rows(oracle, torch_cuda):
     # the MFMA shape (bf16, D 128, G 4, W 32) at a length that is no multiple of the tile, long enough
     # for many subtiles per wavefront, with key rows scaled up so that row references move (rescale path)
@@ -288,7 +317,8 @@ def test_mfma_score_long_ragged_with_heavy_rows(oracle, torch_cuda):
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
 
-def test_mfma_score_reference_moves_for_every_head(oracle, torch_cuda, monkeypatch):
+@pytest.mark.parametrize("W", [32, 64])
+def test_mfma_score_reference_moves_for_every_head(oracle, torch_cuda, monkeypatch, W):
     # Keys planted along chosen query rows give those rows logits far above (> 50 nats) everything seen before,
     # so the row's running reference has to move in the middle of a wavefront's stream: for each of the four
     # heads of a group, for two heads in one subtile, twice for one row, in the last subtile of a workgroup's
@@ -296,7 +326,7 @@ def test_mfma_score_reference_moves_for_every_head(oracle, torch_cuda, monkeypat
     # wavefront loop over 32 subtiles although there are only two problems.
     torch = torch_cuda
     monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "4096")
-    L, W, D, G, Hkv = 3 * 4096 + 77 + 32, 32, 128, 4, 2
+    L, D, G, Hkv = 3 * 4096 + 77 + W, 128, 4, 2
     T = L - W
     q = synth.normal_torch(515, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
     k = synth.normal_torch(515, 2, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
@@ -309,6 +339,9 @@ def test_mfma_score_reference_moves_for_every_head(oracle, torch_cuda, monkeypat
         (1, 1, 11, 4096 + 40, 5.0),                 # first subtile of a wavefront in chunk 1
         (0, 2, 20, T + 10, 5.0), (1, 3, 31, 9000, 6.0), (1, 3, 30, 9130, 6.0),
     ]
+    if W == 64:     # rows of the second query block (window queries 32..63), whose statistics run as their own pass
+        plants += [(0, 1, 40, 5200, 5.0), (1, 3, 63, 5300, 5.0), (0, 0, 33, 6000, 5.0), (0, 0, 33, 8000, 9.0),
+                   (1, 2, 50, T + 45, 5.0)]
     for g, h, i, t, scale in plants:
         k[0, 0, g, t, :] = (q[0, 0, g * G + h, i, :].float() * scale).to(torch.bfloat16)
     off = synth.segment_offsets(7, T, mean=48.0, min_len=1, max_len=300)
@@ -316,7 +349,7 @@ def test_mfma_score_reference_moves_for_every_head(oracle, torch_cuda, monkeypat
     run = H.GpuRun(q, k, v, off, [0, len(off)], w.cand, w.budget())
     assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
     for g, h, i, t, scale in plants:                 # a planted key takes (almost) all of its row: Abar = 1/G
-        if t < T and t != 700:                       # (the plant at 700 loses its row to the one at 2000)
+        if t < T and t not in (700, 6000):           # (the plants at 700 / 6000 lose their rows to those at 2000 / 8000)
             assert run.s[g, t] > 0.99 / G
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
