@@ -1,4 +1,4 @@
-// MFMA window scoring (Sec. 3.2, Eqs. barA, st, Dk) for bf16, D = 128, G = 4, W = 32 or 64.
+// MFMA window scoring (Sec. 3.2, Eqs. barA, st, Dk) for bf16, D = 128 and (G, W) = (4, 32), (4, 64) or (8, 32).
 //
 // The window-query rows of a KV head (4 query heads x 32 window queries) stay in
 // accumulation registers as MFMA A operands; keys are the B operand, 32 per
@@ -27,11 +27,11 @@
 // with the exp/log work inside one wavefront (one wavefront per SIMD).
 // One launch per pass covers every problem of the call.
 //
-// W = 64 (256 window-query rows per KV head).  The row statistics are independent per row, so pass 1 runs the
-// same kernel on the two halves of the window as if they were two problems (K is streamed once per half).
-// Pass 2 needs all 64 queries of a key together (head mean, column sum, entropy), so a variant of the column
-// kernel keeps all eight 32-row tiles as A operands (256 accumulation registers), the keys in ordinary
-// registers and the C operands in LDS.
+// 256 window-query rows per KV head (G = 4 with W = 64, or G = 8 with W = 32).  The row statistics are
+// independent per row, so pass 1 runs the same kernel on two blocks of 128 rows (the two halves of the window, or
+// heads 0-3 and 4-7) as if they were two problems (K is streamed once per block).  Pass 2 needs all rows of a
+// key together (head mean, column sum, entropy), so a variant of the column kernel keeps all eight 32-row tiles
+// as A operands (256 accumulation registers), the keys in ordinary registers and the C operands in LDS.
 #include "sablock_internal.h"
 
 #include <cstdlib>
@@ -64,7 +64,7 @@ struct ScoreArgs {
     int p0;                // first problem of the group
     int chunk_len;         // keys per workgroup, multiple of STRIDE
     int n_chunks;          // workgroups per problem
-    int nv;                // 32-query blocks per problem in pass 1 (W / 32)
+    int nv;                // 128-row blocks per problem in pass 1 (G * W / 128)
     float c1;              // log2(e) / sqrt(D)
     float eps;
     float *partial;        // pass 1 out / pass 2 in: [problem][query block][chunk][128][2] (reference, sum), log2 domain
@@ -119,7 +119,7 @@ __device__ __forceinline__ void wait_loads(int subtiles_after)
 struct WaveWork {
     const uint16_t *kp;    // keys of the problem
     int p, pl, chunk;
-    int pv, qoff;          // pass 1: (problem, query block) index and the block's first window query
+    int pv, qoff, hoff;    // pass 1: (problem, row block) index, the block's first window query and first head
     int first, n_sub;      // this stream's subtiles: keys [first + u * STRIDE, +SUB), u < n_sub
 };
 
@@ -132,6 +132,7 @@ __device__ __forceinline__ WaveWork wave_work(const ScoreArgs &a, int stream)
     w.p = a.p0 + w.pl;
     w.pv = w.p;
     w.qoff = 0;
+    w.hoff = 0;
     w.kp = a.k + k_problem_offset(a.d, w.p);
     const int lo = w.chunk * a.chunk_len;
     const int hi = min(lo + a.chunk_len, a.d.L);
@@ -147,7 +148,9 @@ __device__ __forceinline__ WaveWork wave_work_blocks(const ScoreArgs &a, int str
     WaveWork w = wave_work(a, stream);
     w.pv = a.p0 * a.nv + w.pl;
     w.p = w.pv / a.nv;
-    w.qoff = (w.pv - w.p * a.nv) * 32;
+    const int v = w.pv - w.p * a.nv;
+    w.qoff = a.d.W > 32 ? 32 * v : 0;                        // blocks are window halves ...
+    w.hoff = a.d.W > 32 ? 0 : 4 * v;                         // ... or groups of four heads
     w.kp = a.k + k_problem_offset(a.d, w.p);
     return w;
 }
@@ -236,11 +239,11 @@ struct KeyStream {
 
 // A operands: the window queries of the four heads, query row `n`, k-slices (2s + hf) * 8 .. +8, into
 // accumulation registers.  All 32 loads are issued before the first is consumed.
-__device__ __forceinline__ void load_queries(bf16x8 (&qa)[4][8], const uint16_t *q, const Dims &d, int p, int n, int hf)
+__device__ __forceinline__ void load_queries(bf16x8 (&qa)[4][8], const uint16_t *q, const Dims &d, int p, int h0, int n, int hf)
 {
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-        const uint16_t *row = q + q_row_offset(d, p, h, n);   // n: window query of this lane
+        const uint16_t *row = q + q_row_offset(d, p, h0 + h, n);   // n: window query of this lane
 #pragma unroll
         for (int s = 0; s < 8; ++s) qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
     }
@@ -387,7 +390,7 @@ score_mfma_stats(ScoreArgs a)
     ks.prime();
 
     bf16x8 qa[4][8];
-    load_queries(qa, a.q, d, w.p, w.qoff + n, hf);
+    load_queries(qa, a.q, d, w.p, w.hoff, w.qoff + n, hf);
     cref[lane] = 0.f;
     cref[lane + 64] = 0.f;
 
@@ -576,7 +579,7 @@ score_mfma_columns(ScoreArgs a)
     bf16x8 qa[4][8];
     floatx16 cinit[4], acc[2];
     const float inv_c1 = 1.0f / a.c1;
-    load_queries(qa, a.q, d, w.p, n, hf);
+    load_queries(qa, a.q, d, w.p, 0, n, hf);
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
 #pragma unroll
@@ -623,24 +626,36 @@ score_mfma_columns(ScoreArgs a)
     }
 }
 
-// ------------------------------------------------------------------ pass 2, W = 64
-// Eight 32-row tiles: tile j holds head j / 2, window queries 32 (j % 2) .. +32.  Same pipeline as above with the
-// tiles rotating through two accumulators; ab[v] collects the head mean of query block v.
+// ------------------------------------------------------------------ pass 2, 256 rows
+// Eight 32-row tiles.  W = 64: tile j holds head j / 2, window queries 32 (j % 2) .. +32; W = 32 (G = 8): tile j
+// holds head j.  Same pipeline as above with the tiles rotating through two accumulators; ab[b] collects the
+// head mean of the window queries 32 b .. 32 b + 31.
+template <int W> struct Tiles8 {
+    static constexpr int NB = W / 32;                                        // 32-query blocks of the window
+    __host__ __device__ static constexpr int head(int j) { return W == 64 ? j / 2 : j; }
+    __host__ __device__ static constexpr int qoff(int j) { return W == 64 ? 32 * (j % 2) : 0; }
+    __host__ __device__ static constexpr int blk(int j) { return W == 64 ? j % 2 : 0; }
+    __host__ __device__ static constexpr bool first(int j) { return W == 64 ? j < 2 : j == 0; }   // first tile of its block
+    // where pass 1 stored the statistics of tile j: (row block, 32-row group inside it)
+    __host__ __device__ static constexpr int p1_block(int j) { return W == 64 ? j % 2 : j / 4; }
+    __host__ __device__ static constexpr int p1_group(int j) { return W == 64 ? j / 2 : j % 4; }
+};
 constexpr int M_ROWS64 = 256;
 constexpr int P2W_LDS = 4 * 4 * BUF_BYTES + M_ROWS64 * 4 + 8 * 32 * 4;   // rings + the rows' log-sum-exp + C operands
 
-__device__ __forceinline__ float columns_finish64(const float (&ab)[2][16], float eps, int hf)
+template <int NB>
+__device__ __forceinline__ float columns_finish8t(const float (&ab)[NB][16], float eps, int hf)
 {
     float s_part = 0.f;
 #pragma unroll
-    for (int v = 0; v < 2; ++v)
+    for (int v = 0; v < NB; ++v)
 #pragma unroll
         for (int i = 0; i < 16; ++i) s_part += ab[v][i];
     const float s = add_other_half(s_part);
     const float inv_s = s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f;
     float e_part = 0.f;
 #pragma unroll
-    for (int v = 0; v < 2; ++v)
+    for (int v = 0; v < NB; ++v)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const float ah = ab[v][i] * inv_s;
@@ -656,40 +671,52 @@ __device__ __forceinline__ floatx16 load_c64(const float *cmat, int j, int hf)
 }
 
 // One subtile; returns the output value of the PREVIOUS subtile (its last tile waits in acc[1])
-template <bool EDGE>
-__device__ __forceinline__ float columns_body64(const bf16x8 (&qa)[8][8], const bf16x8 (&kb)[8], const float *cmat,
-                                                floatx16 (&acc)[2], float (&ab)[2][16], float c1, float eps, int t_prev,
-                                                int t_cur, int hf, int T, int L)
+template <int W, bool EDGE, int J>
+__device__ __forceinline__ void columns_tile8t(const floatx16 &acc, float (&ab)[Tiles8<W>::NB][16], float c1, int t, int hf,
+                                               int T, int L)
 {
+    using TL = Tiles8<W>;
+    columns_head<EDGE, TL::first(J)>(acc, ab[TL::blk(J)], c1, t, hf, T + TL::qoff(J), L);
+}
+
+template <int W, bool EDGE>
+__device__ __forceinline__ float columns_body8t(const bf16x8 (&qa)[8][8], const bf16x8 (&kb)[8], const float *cmat,
+                                                floatx16 (&acc)[2], float (&ab)[Tiles8<W>::NB][16], float c1, float eps,
+                                                int t_prev, int t_cur, int hf, int T, int L)
+{
+    using TL = Tiles8<W>;
     acc[0] = chain<0, 8>(qa[0], kb, load_c64(cmat, 0, hf));
-    columns_head<EDGE, false>(acc[1], ab[1], c1, t_prev, hf, T + 32, L);      // tile 7 of the previous subtile
-    const float prev = columns_finish64(ab, eps, hf);
+    columns_head<EDGE, false>(acc[1], ab[TL::blk(7)], c1, t_prev, hf, T + TL::qoff(7), L);     // tile 7 of the previous subtile
+    const float prev = columns_finish8t<TL::NB>(ab, eps, hf);
     acc[1] = chain<0, 8>(qa[1], kb, load_c64(cmat, 1, hf));
-    columns_head<EDGE, true>(acc[0], ab[0], c1, t_cur, hf, T, L);             // head 0, queries 0..31
+    columns_tile8t<W, EDGE, 0>(acc[0], ab, c1, t_cur, hf, T, L);
     acc[0] = chain<0, 8>(qa[2], kb, load_c64(cmat, 2, hf));
-    columns_head<EDGE, true>(acc[1], ab[1], c1, t_cur, hf, T + 32, L);        // head 0, queries 32..63
+    columns_tile8t<W, EDGE, 1>(acc[1], ab, c1, t_cur, hf, T, L);
     acc[1] = chain<0, 8>(qa[3], kb, load_c64(cmat, 3, hf));
-    columns_head<EDGE, false>(acc[0], ab[0], c1, t_cur, hf, T, L);
+    columns_tile8t<W, EDGE, 2>(acc[0], ab, c1, t_cur, hf, T, L);
     acc[0] = chain<0, 8>(qa[4], kb, load_c64(cmat, 4, hf));
-    columns_head<EDGE, false>(acc[1], ab[1], c1, t_cur, hf, T + 32, L);
+    columns_tile8t<W, EDGE, 3>(acc[1], ab, c1, t_cur, hf, T, L);
     acc[1] = chain<0, 8>(qa[5], kb, load_c64(cmat, 5, hf));
-    columns_head<EDGE, false>(acc[0], ab[0], c1, t_cur, hf, T, L);
+    columns_tile8t<W, EDGE, 4>(acc[0], ab, c1, t_cur, hf, T, L);
     acc[0] = chain<0, 8>(qa[6], kb, load_c64(cmat, 6, hf));
-    columns_head<EDGE, false>(acc[1], ab[1], c1, t_cur, hf, T + 32, L);
+    columns_tile8t<W, EDGE, 5>(acc[1], ab, c1, t_cur, hf, T, L);
     acc[1] = chain<0, 8>(qa[7], kb, load_c64(cmat, 7, hf));
-    columns_head<EDGE, false>(acc[0], ab[0], c1, t_cur, hf, T, L);
+    columns_tile8t<W, EDGE, 6>(acc[0], ab, c1, t_cur, hf, T, L);
     return prev;
 }
 
+template <int W>
 __global__ void __launch_bounds__(WAVES * 64)
-score_mfma_columns64(ScoreArgs a)
+score_mfma_columns8t(ScoreArgs a)
 {
+    using TL = Tiles8<W>;
+    constexpr int G = M_ROWS64 / W;
     extern __shared__ __attribute__((aligned(8192))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hf = lane >> 5;
     const Dims &d = a.d;
     char *ring = lds + __builtin_amdgcn_readfirstlane(wave) * RING_BYTES;
-    float *lse2 = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [256] log2-domain lse + log2 G, row h * 64 + i
+    float *lse2 = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [256] log2-domain lse + log2 G, row h * W + i
     float *cmat = lse2 + M_ROWS64;                                           // [8 tiles][2 halves][16] C operands
     const WaveWork w = wave_work(a, wave);
 
@@ -697,16 +724,17 @@ score_mfma_columns64(ScoreArgs a)
     ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
     ks.prime();
 
-    // one thread per row: its log-sum-exp, given by the caller or folded from the chunk partials of pass 1
-    // (stored per 32-query block: block v of head h, query i % 32 is row h * 32 + i % 32 of block v)
+    // one thread per row (h, i): its log-sum-exp, given by the caller or folded from the chunk partials of pass 1,
+    // which are stored per 128-row block (see Tiles8::p1_block / p1_group)
     {
-        const int r = threadIdx.x, h = r >> 6, i = r & 63, v = i >> 5;
+        const int r = threadIdx.x, h = r / W, i = r % W;
+        const int j = W == 64 ? 2 * h + i / 32 : h;                           // the row's tile
         float m = -INFINITY, zz = 0.f;
         if (a.lse) {
             m = a.lse[(int64_t)w.p * M_ROWS64 + r] * LOG2E;
             zz = 1.f;
         } else {
-            const float *pp = a.partial + (((int64_t)(w.p * 2 + v) * a.n_chunks) * M_ROWS + h * 32 + (i & 31)) * 2;
+            const float *pp = a.partial + (((int64_t)(w.p * 2 + TL::p1_block(j)) * a.n_chunks) * M_ROWS + TL::p1_group(j) * 32 + (i & 31)) * 2;
             for (int c = 0; c < a.n_chunks; ++c) {
                 const float2 e = *reinterpret_cast<const float2 *>(pp + (int64_t)c * M_ROWS * 2);
                 if (e.y > 0.f) {
@@ -716,21 +744,21 @@ score_mfma_columns64(ScoreArgs a)
                 }
             }
         }
-        lse2[r] = m + __builtin_amdgcn_logf(zz) + 2.0f;                      // + log2(G): exp2 then yields A / G
+        lse2[r] = m + __builtin_amdgcn_logf(zz) + (G == 4 ? 2.0f : 3.0f);    // + log2(G): exp2 then yields A / G
     }
     __syncthreads();
     {
         const float inv_c1 = 1.0f / a.c1;
         const int j = threadIdx.x >> 5, slot = threadIdx.x & 31;
-        const int i = 32 * (j & 1) + query_of(slot & 15, slot >> 4);
-        cmat[threadIdx.x] = -lse2[(j >> 1) * 64 + i] * inv_c1;
+        const int i = TL::qoff(j) + query_of(slot & 15, slot >> 4);
+        cmat[threadIdx.x] = -lse2[TL::head(j) * W + i] * inv_c1;
     }
     __syncthreads();
 
     bf16x8 qa[8][8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const uint16_t *row = a.q + q_row_offset(d, w.p, j >> 1, 32 * (j & 1) + n);
+        const uint16_t *row = a.q + q_row_offset(d, w.p, TL::head(j), TL::qoff(j) + n);
 #pragma unroll
         for (int s = 0; s < 8; ++s) qa[j][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
     }
@@ -740,9 +768,13 @@ score_mfma_columns64(ScoreArgs a)
         for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qa[j][s]));       // all 256 accumulation registers
 
     floatx16 acc[2];
-    float ab[2][16];
+    float ab[TL::NB][16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { acc[0][i] = acc[1][i] = -INFINITY; ab[0][i] = ab[1][i] = 0.f; }
+    for (int i = 0; i < 16; ++i) {
+        acc[0][i] = acc[1][i] = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < TL::NB; ++v) ab[v][i] = 0.f;
+    }
     float *out = (hf == 0 ? a.s_out : a.e_out) + (int64_t)w.p * d.L;
 
     float pending = 0.f;
@@ -754,7 +786,7 @@ score_mfma_columns64(ScoreArgs a)
         bf16x8 kb[8];
         ks.fetch_vgpr(u, kb);
         const int t_cur = w.first + u * STRIDE + n;
-        pending = columns_body64<false>(qa, kb, cmat, acc, ab, a.c1, a.eps, t_cur - STRIDE, t_cur, hf, d.T, d.L);
+        pending = columns_body8t<W, false>(qa, kb, cmat, acc, ab, a.c1, a.eps, t_cur - STRIDE, t_cur, hf, d.T, d.L);
         pending_t = u > 0 ? t_cur - STRIDE : -1;
     }
     for (; u < w.n_sub; ++u) {
@@ -762,14 +794,14 @@ score_mfma_columns64(ScoreArgs a)
         bf16x8 kb[8];
         ks.fetch_vgpr(u, kb);
         const int t_cur = w.first + u * STRIDE + n;
-        pending = columns_body64<true>(qa, kb, cmat, acc, ab, a.c1, a.eps, t_cur - STRIDE, t_cur, hf, d.T, d.L);
+        pending = columns_body8t<W, true>(qa, kb, cmat, acc, ab, a.c1, a.eps, t_cur - STRIDE, t_cur, hf, d.T, d.L);
         pending_t = u > 0 ? t_cur - STRIDE : -1;
     }
     if (pending_t >= 0 && pending_t < d.L) out[pending_t] = pending;
     if (w.n_sub > 0) {
         const int t_last = w.first + (w.n_sub - 1) * STRIDE + n;
-        columns_head<true, false>(acc[1], ab[1], a.c1, t_last, hf, d.T + 32, d.L);
-        const float v = columns_finish64(ab, a.eps, hf);
+        columns_head<true, false>(acc[1], ab[TL::blk(7)], a.c1, t_last, hf, d.T + TL::qoff(7), d.L);
+        const float v = columns_finish8t<TL::NB>(ab, a.eps, hf);
         if (t_last < d.L) out[t_last] = v;
     }
 }
@@ -797,13 +829,14 @@ Plan make_plan(const Dims &d)
 
 bool score_mfma_supported(const Dims &d)
 {
-    return d.dtype == SABLOCK_BF16 && d.D == 128 && d.G == 4 && (d.W == 32 || d.W == 64);
+    return d.dtype == SABLOCK_BF16 && d.D == 128 &&
+           ((d.G == 4 && (d.W == 32 || d.W == 64)) || (d.G == 8 && d.W == 32));
 }
 
 size_t score_mfma_ws_bytes(const Dims &d)
 {
     Plan pl = make_plan(d);
-    return align256((size_t)d.P * (d.W / 32) * pl.n_chunks * M_ROWS * 2 * 4);
+    return align256((size_t)d.P * (d.G * d.W / M_ROWS) * pl.n_chunks * M_ROWS * 2 * 4);
 }
 
 hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
@@ -817,7 +850,10 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, P2_LDS);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns64),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns8t<64>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, P2W_LDS);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns8t<32>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, P2W_LDS);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -836,11 +872,12 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.partial = static_cast<float *>(ws);
     a.lse = row_lse;
     a.p0 = 0;
-    a.nv = d.W / 32;
+    a.nv = d.G * d.W / M_ROWS;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
     dim3 grid1((unsigned)((int64_t)d.P * a.nv * pl.n_chunks));
     if (!row_lse) hipLaunchKernelGGL(score_mfma_stats, grid1, dim3(WAVES * 64), P1_LDS, st, a);
-    if (d.W == 64) hipLaunchKernelGGL(score_mfma_columns64, grid, dim3(WAVES * 64), P2W_LDS, st, a);
+    if (d.W == 64) hipLaunchKernelGGL(score_mfma_columns8t<64>, grid, dim3(WAVES * 64), P2W_LDS, st, a);
+    else if (d.G == 8) hipLaunchKernelGGL(score_mfma_columns8t<32>, grid, dim3(WAVES * 64), P2W_LDS, st, a);
     else hipLaunchKernelGGL(score_mfma_columns, grid, dim3(WAVES * 64), P2_LDS, st, a);
     return hipGetLastError();
 }

@@ -296,6 +296,26 @@ def test_mfma_row_lse_input_equals_internal_pass(oracle, torch_cuda, W):
     assert np.allclose(s0.sum(axis=1), W, rtol=1e-4)
 
 
+def test_mfma_score_eight_heads_per_group(oracle, torch_cuda, monkeypatch):
+    # G = 8 (64 query / 8 KV heads), W = 32: 256 window-query rows per KV head on the eight-tile column kernel;
+    # ragged length, 16 subtiles per wavefront, planted keys that move row references in both head blocks
+    torch = torch_cuda
+    monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "2048")
+    L, W, D, G, Hkv = 3 * 2048 + 333 + 32, 32, 128, 8, 2
+    T = L - W
+    q = synth.normal_torch(717, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(717, 2, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(717, 3, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    for g, h, i, t in [(0, 1, 3, 900), (0, 6, 17, 2500), (1, 7, 31, 4000), (1, 4, 0, T + 1)]:
+        k[0, 0, g, t, :] = (q[0, 0, g * G + h, i, :].float() * 5.0).to(torch.bfloat16)
+    off = synth.segment_offsets(717, T, mean=40.0, min_len=1, max_len=300)
+    w = synth.Workload("g8", 0, 1, 1, G * Hkv, Hkv, D, L, W, "bf16", (1, 2, 4, 8, 16, 32), (512,), (40.0,))
+    run = H.GpuRun(q, k, v, off, [0, len(off)], w.cand, w.budget())
+    assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
+    assert run.s[0, 900] > 0.99 / G and run.s[1, 4000] > 0.99 / G
+    _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
+
+
 def test_mfma_score_long_ragged_with_heavy_rows(oracle, torch_cuda):
     # the MFMA shape (bf16, D 128, G 4, W 32) at a length that is no multiple of the tile, long enough
     # for many subtiles per wavefront, with key rows scaled up so that row references move (rescale path)
