@@ -277,16 +277,17 @@ __device__ __forceinline__ floatx16 load_cref(const float *cref, int h, int hf)
     return *reinterpret_cast<const floatx16 *>(cref + h * 32 + hf * 16);
 }
 
-// careful reduction of one head tile of the subtile whose lane key is t
-__device__ __forceinline__ void stats_head_careful(const floatx16 &acc, float (&z)[16], float *cref_h, float c1, bool first,
-                                                   int t, int hf, int n, int T, int L)
+// careful reduction of one 32-row tile of the subtile whose lane key is t; qf(i) = window query of register i
+template <typename QF>
+__device__ __forceinline__ void stats_tile_careful(const floatx16 &acc, float (&z)[16], float *cref_h, float c1, bool first,
+                                                   int t, int hf, int n, QF qf, int T, int L)
 {
     float dd[16];
     float dmax = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         float v = acc[i] * c1;
-        if (!(t < L && t <= T + query_of(i, hf))) v = -INFINITY;         // causal inside the window
+        if (!(t < L && t <= T + qf(i))) v = -INFINITY;                   // causal inside the window
         dd[i] = v;
         dmax = fmaxf(dmax, v);
     }
@@ -307,6 +308,13 @@ __device__ __forceinline__ void stats_head_careful(const floatx16 &acc, float (&
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) z[i] += __builtin_amdgcn_exp2f(dd[i]);
+}
+
+// the same for a tile that is one head's 32 window queries
+__device__ __forceinline__ void stats_head_careful(const floatx16 &acc, float (&z)[16], float *cref_h, float c1, bool first,
+                                                   int t, int hf, int n, int T, int L)
+{
+    stats_tile_careful(acc, z, cref_h, c1, first, t, hf, n, [hf](int i) { return query_of(i, hf); }, T, L);
 }
 
 // guard of the fast body: true when some accumulator of the wavefront exceeds `lim` (= RESCALE_AT / c1)
@@ -806,6 +814,235 @@ score_mfma_columns8t(ScoreArgs a)
     }
 }
 
+// ------------------------------------------------------------------ other head / window shapes
+// G * W = 32, 64 or 128 rows in one to four 32-row tiles, row = head * W + window query.  For W < 32 a tile holds
+// several heads, so the head mean adds REGISTERS of one accumulator (register i of lane half hf is row
+// 8 (i / 4) + 4 hf + i % 4 of the tile); for W >= 32 it adds accumulators, as in the kernels above.  These
+// kernels run the tiles of a subtile one after the other (no rotation of accumulators): with at most a quarter
+// of the arithmetic of the 128-row case per key they wait for memory anyway.
+template <int G, int W> struct Rows {
+    static constexpr int M = G * W;
+    static constexpr int NT = M / 32;                       // tiles
+    static constexpr int QB = W >= 32 ? W / 32 : 1;         // 32-query blocks of the window
+    static constexpr int NS = W >= 32 ? 16 * QB : W / 2;    // head-mean values per lane
+    static_assert(M == 32 || M == 64 || M == 128, "unsupported shape");
+    __device__ static int tile_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
+    __device__ static int query(int J, int i, int hf) { return W >= 32 ? 32 * (J % QB) + tile_row(i, hf) : tile_row(i, hf) % W; }
+    __device__ static int head(int J, int i, int hf) { return W >= 32 ? J / QB : J * (32 / W) + tile_row(i, hf) / W; }
+    __host__ __device__ static constexpr int slot(int J, int i) { return W >= 32 ? 16 * (J % QB) + i : i % (W / 2); }
+};
+
+template <int G, int W>
+__global__ void __launch_bounds__(WAVES * 64)
+score_mfma_stats_g(ScoreArgs a)
+{
+    using R = Rows<G, W>;
+    constexpr int M = R::M, NT = R::NT;
+    extern __shared__ __attribute__((aligned(8192))) char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, hf = lane >> 5;
+    const Dims &d = a.d;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    char *ring = lds + wave_u * RING_BYTES;
+    float *wg_red = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [WAVES][M][2]
+    float *cref = wg_red + WAVES * M * 2 + wave_u * M;                         // [NT tiles][2 halves][16], this wave's
+    const WaveWork w = wave_work(a, wave);
+
+    KeyStream<NBUF> ks;
+    ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
+    ks.prime();
+
+    bf16x8 qa[NT][8];
+#pragma unroll
+    for (int J = 0; J < NT; ++J) {
+        const int r = 32 * J + n;                                              // row of the window-query matrix
+        const uint16_t *row = a.q + q_row_offset(d, w.p, r / W, r % W);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) qa[J][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+    }
+#pragma unroll
+    for (int J = 0; J < NT; ++J)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qa[J][s]));
+    for (int i = lane; i < M; i += 64) cref[i] = 0.f;
+
+    float z[NT][16];
+#pragma unroll
+    for (int J = 0; J < NT; ++J)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) z[J][i] = 0.f;
+    const float lim = RESCALE_AT / a.c1;
+    for (int u = 0; u < w.n_sub; ++u) {
+        bf16x8 kb[8];
+        ks.fetch(u, kb);
+        const int t0 = w.first + u * STRIDE;
+        const bool plain = u > 0 && t0 + SUB <= d.T;
+#pragma unroll
+        for (int J = 0; J < NT; ++J) {
+            const floatx16 acc = chain<0, 8>(qa[J], kb, load_cref(cref, J, hf));
+            if (plain && !stats_guard(acc, lim)) stats_add(acc, z[J], a.c1);
+            else stats_tile_careful(acc, z[J], cref + 32 * J, a.c1, u == 0, t0 + n, hf, n,
+                                    [J, hf](int i) { return R::query(J, i, hf); }, d.T, d.L);
+        }
+    }
+
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    float *scr_z = reinterpret_cast<float *>(ring);            // [M rows][32 lanes]
+#pragma unroll
+    for (int J = 0; J < NT; ++J)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) scr_z[(J * 32 + R::tile_row(i, hf)) * 32 + n] = z[J][i];
+    __builtin_amdgcn_wave_barrier();
+    for (int row = lane; row < M; row += 64) {                  // row = 32 * tile + row in tile
+        float zz = 0.f;
+        for (int j = 0; j < 32; ++j) zz += scr_z[row * 32 + ((j + lane) & 31)];
+        const int q = row & 31, hfq = (q >> 2) & 1, iq = ((q >> 3) << 2) | (q & 3);
+        wg_red[(wave * M + row) * 2] = -cref[(row >> 5) * 32 + hfq * 16 + iq] * a.c1;   // reference, log2 domain
+        wg_red[(wave * M + row) * 2 + 1] = zz;
+    }
+    __syncthreads();
+    if (threadIdx.x < M) {
+        const int row = threadIdx.x;
+        float m = -INFINITY;
+        for (int wv = 0; wv < WAVES; ++wv) {
+            const float *e = wg_red + (wv * M + row) * 2;
+            if (e[1] > 0.f) m = fmaxf(m, e[0]);
+        }
+        float zz = 0.f;
+        for (int wv = 0; wv < WAVES; ++wv) {
+            const float *e = wg_red + (wv * M + row) * 2;
+            if (e[1] > 0.f) zz += e[1] * __builtin_amdgcn_exp2f(e[0] - m);
+        }
+        float *o = a.partial + (((int64_t)w.p * a.n_chunks + w.chunk) * M + row) * 2;
+        o[0] = m;
+        o[1] = zz;
+    }
+}
+
+template <int G, int W>
+__global__ void __launch_bounds__(WAVES * 64)
+score_mfma_columns_g(ScoreArgs a)
+{
+    using R = Rows<G, W>;
+    constexpr int M = R::M, NT = R::NT, NS = R::NS;
+    extern __shared__ __attribute__((aligned(8192))) char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, hf = lane >> 5;
+    const Dims &d = a.d;
+    char *ring = lds + __builtin_amdgcn_readfirstlane(wave) * RING_BYTES;
+    float *lse2 = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [M] log2-domain lse + log2 G, row head * W + query
+    const WaveWork w = wave_work(a, wave);
+
+    KeyStream<NBUF> ks;
+    ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
+    ks.prime();
+
+    if (threadIdx.x < M) {
+        const int r = threadIdx.x;
+        float m = -INFINITY, zz = 0.f;
+        if (a.lse) {
+            m = a.lse[(int64_t)w.p * M + r] * LOG2E;
+            zz = 1.f;
+        } else {
+            const float *pp = a.partial + ((int64_t)w.p * a.n_chunks * M + r) * 2;
+            for (int c = 0; c < a.n_chunks; ++c) {
+                const float2 e = *reinterpret_cast<const float2 *>(pp + (int64_t)c * M * 2);
+                if (e.y > 0.f) {
+                    const float mn = fmaxf(m, e.x);
+                    zz = zz * __builtin_amdgcn_exp2f(m - mn) + e.y * __builtin_amdgcn_exp2f(e.x - mn);
+                    m = mn;
+                }
+            }
+        }
+        lse2[r] = m + __builtin_amdgcn_logf(zz) + (G == 1 ? 0.f : G == 2 ? 1.f : G == 4 ? 2.f : 3.f);   // + log2(G)
+    }
+    __syncthreads();
+
+    bf16x8 qa[NT][8];
+    floatx16 cinit[NT];
+    const float inv_c1 = 1.0f / a.c1;
+#pragma unroll
+    for (int J = 0; J < NT; ++J) {
+        const int r = 32 * J + n;
+        const uint16_t *row = a.q + q_row_offset(d, w.p, r / W, r % W);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) qa[J][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) cinit[J][i] = -lse2[32 * J + R::tile_row(i, hf)] * inv_c1;
+    }
+#pragma unroll
+    for (int J = 0; J < NT; ++J)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qa[J][s]));
+    float *out = (hf == 0 ? a.s_out : a.e_out) + (int64_t)w.p * d.L;
+
+    for (int u = 0; u < w.n_sub; ++u) {
+        bf16x8 kb[8];
+        ks.fetch(u, kb);
+        const int t0 = w.first + u * STRIDE, t = t0 + n;
+        const bool edge = t0 + SUB > d.T;
+        float ab[NS];
+#pragma unroll
+        for (int i = 0; i < NS; ++i) ab[i] = 0.f;
+#pragma unroll
+        for (int J = 0; J < NT; ++J) {
+            const floatx16 acc = chain<0, 8>(qa[J], kb, cinit[J]);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float v = __builtin_amdgcn_exp2f(acc[i] * a.c1);                        // A / G
+                if (edge && !(t < d.L && t <= d.T + R::query(J, i, hf))) v = 0.f;       // causal inside the window
+                ab[R::slot(J, i)] += v;                                                 // Eq. barA
+            }
+        }
+        float s_part = 0.f;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) s_part += ab[i];
+        const float sv = add_other_half(s_part);                                         // Eq. st
+        const float inv_s = sv > 0.f ? __builtin_amdgcn_rcpf(sv) : 0.f;
+        float e_part = 0.f;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const float ah = ab[i] * inv_s;
+            e_part = fmaf(ah, __builtin_amdgcn_logf(ah + a.eps), e_part);
+        }
+        const float ent = -LN2 * add_other_half(e_part);                                 // inner sum of Eq. Dk
+        if (t < d.L) out[t] = hf == 0 ? sv : ent;
+    }
+}
+
+template <int G, int W> constexpr int stats_g_lds() { return 4 * 4 * BUF_BYTES + 4 * G * W * 2 * 4 + 4 * G * W * 4; }
+template <int G, int W> constexpr int columns_g_lds() { return 4 * 4 * BUF_BYTES + G * W * 4; }
+
+template <int G, int W>
+hipError_t launch_score_g(const ScoreArgs &a, dim3 grid, bool with_stats, hipStream_t st)
+{
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats_g<G, W>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, stats_g_lds<G, W>());
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_g<G, W>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, columns_g_lds<G, W>());
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    constexpr int lds1 = stats_g_lds<G, W>(), lds2 = columns_g_lds<G, W>();
+    if (with_stats) hipLaunchKernelGGL((score_mfma_stats_g<G, W>), grid, dim3(WAVES * 64), lds1, st, a);
+    hipLaunchKernelGGL((score_mfma_columns_g<G, W>), grid, dim3(WAVES * 64), lds2, st, a);
+    return hipGetLastError();
+}
+
+// the (G, W) pairs served by the generic-row kernels
+#define SABLOCK_SMALL_SHAPES(X) X(4, 8) X(4, 16) X(8, 8) X(8, 16) X(2, 32) X(1, 32)
+
+bool small_shape(const Dims &d)
+{
+#define X(GV, WV) if (d.G == GV && d.W == WV) return true;
+    SABLOCK_SMALL_SHAPES(X)
+#undef X
+    return false;
+}
+
 struct Plan {
     int chunk_len;    // keys per workgroup
     int n_chunks;     // workgroups per problem
@@ -830,13 +1067,13 @@ Plan make_plan(const Dims &d)
 bool score_mfma_supported(const Dims &d)
 {
     return d.dtype == SABLOCK_BF16 && d.D == 128 &&
-           ((d.G == 4 && (d.W == 32 || d.W == 64)) || (d.G == 8 && d.W == 32));
+           ((d.G == 4 && (d.W == 32 || d.W == 64)) || (d.G == 8 && d.W == 32) || small_shape(d));
 }
 
 size_t score_mfma_ws_bytes(const Dims &d)
 {
     Plan pl = make_plan(d);
-    return align256((size_t)d.P * (d.G * d.W / M_ROWS) * pl.n_chunks * M_ROWS * 2 * 4);
+    return align256((size_t)d.P * pl.n_chunks * d.G * d.W * 2 * 4);
 }
 
 hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
@@ -872,8 +1109,11 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.partial = static_cast<float *>(ws);
     a.lse = row_lse;
     a.p0 = 0;
-    a.nv = d.G * d.W / M_ROWS;
+    a.nv = d.G * d.W > M_ROWS ? d.G * d.W / M_ROWS : 1;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
+#define X(GV, WV) if (d.G == GV && d.W == WV) return launch_score_g<GV, WV>(a, grid, !row_lse, st);
+    SABLOCK_SMALL_SHAPES(X)
+#undef X
     dim3 grid1((unsigned)((int64_t)d.P * a.nv * pl.n_chunks));
     if (!row_lse) hipLaunchKernelGGL(score_mfma_stats, grid1, dim3(WAVES * 64), P1_LDS, st, a);
     if (d.W == 64) hipLaunchKernelGGL(score_mfma_columns8t<64>, grid, dim3(WAVES * 64), P2W_LDS, st, a);

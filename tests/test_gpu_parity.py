@@ -267,7 +267,7 @@ def test_row_lse_input_equals_internal_pass(oracle, torch_cuda):
     np.testing.assert_allclose(H.to_np(buf.ent), e0, rtol=2e-5, atol=1e-6)
 
 
-@pytest.mark.parametrize("W", [32, 64])
+@pytest.mark.parametrize("W", [8, 16, 32, 64])
 def test_mfma_row_lse_input_equals_internal_pass(oracle, torch_cuda, W):
     # the MFMA shapes: scores from the caller's fp64 row log-sum-exp equal those of the two-pass run
     torch = torch_cuda
@@ -313,6 +313,30 @@ def test_mfma_score_eight_heads_per_group(oracle, torch_cuda, monkeypatch):
     run = H.GpuRun(q, k, v, off, [0, len(off)], w.cand, w.budget())
     assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
     assert run.s[0, 900] > 0.99 / G and run.s[1, 4000] > 0.99 / G
+    _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
+
+
+@pytest.mark.parametrize("G,W", [(4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)])
+def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, monkeypatch, G, W):
+    # 32, 64 or 128 window-query rows per KV head in one to four MFMA tiles (several heads per tile when W < 32):
+    # ragged length, 16 subtiles per wavefront, planted keys that move row references, all five steps
+    torch = torch_cuda
+    monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "2048")
+    L, D, Hkv = 2 * 2048 + 411 + W, 128, 2
+    T = L - W
+    q = synth.normal_torch(3000 + G * W, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(3000 + G * W, 2, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(3000 + G * W, 3, (1, 1, Hkv, L, D), "cuda", torch.bfloat16)
+    plants = [(0, 0, 0, 700), (0, G - 1, W - 1, 1900), (1, G // 2, W // 2, 3000), (1, G - 1, 1, T + 1)]
+    for g, h, i, t in plants:
+        k[0, 0, g, t, :] = (q[0, 0, g * G + h, i, :].float() * 5.0).to(torch.bfloat16)
+    off = synth.segment_offsets(55, T, mean=28.0, min_len=1, max_len=200)
+    cand = [1, 2, 3, 5, 7, 9, 11, 13]
+    w = synth.Workload("shape", 0, 1, 1, G * Hkv, Hkv, D, L, W, "bf16", tuple(cand), (512 + W,), (28.0,))
+    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget())
+    assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
+    for g, h, i, t in plants[:3]:
+        assert run.s[g, t] > 0.99 / G
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
 
