@@ -340,6 +340,36 @@ def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, monkeypatch
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
 
+@pytest.mark.parametrize("G,W,D,dtype", [(4, 32, 128, "bf16"), (4, 64, 128, "bf16"), (4, 8, 128, "bf16"), (3, 5, 40, "f32")])
+def test_score_closed_form_for_zero_queries(torch_cuda, G, W, D, dtype):
+    # Q = 0: every visible key gets the same probability, so window query i spreads 1 / (T + i + 1) over keys
+    # 0 .. T + i; s_t and the entropy term follow in closed form (checked here without the oracle)
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    L, Hkv, eps = 3000 + W, 2, 1e-6
+    T = L - W
+    dt = torch.float32 if dtype == "f32" else torch.bfloat16
+    q = torch.zeros((1, 1, G * Hkv, W, D), dtype=dt, device="cuda")
+    k = synth.normal_torch(9, 2, (1, 1, Hkv, L, D), "cuda", dt)
+    shape = B.make_shape(q, k)
+    seg = B.make_segments(np.array([0, T], dtype=np.int32), [0, 2], "cuda")
+    buf = B.Buffers(shape, seg, 16, "cuda")
+    B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, eps)
+    torch.cuda.synchronize()
+    inv = 1.0 / (T + np.arange(W) + 1.0)                       # probability mass per key of window query i
+    s_ref = np.empty(L)
+    e_ref = np.empty(L)
+    for t in range(L):
+        a = inv[max(0, t - T):]                                 # queries that see key t
+        s_ref[t] = a.sum()
+        ah = a / s_ref[t]
+        e_ref[t] = -(ah * np.log(ah + eps)).sum()
+    for p in range(Hkv):
+        np.testing.assert_allclose(H.to_np(buf.s)[p], s_ref, rtol=1e-5, atol=1e-9)
+        np.testing.assert_allclose(H.to_np(buf.ent)[p], e_ref, rtol=1e-5, atol=1e-6)
+
+
 def test_mfma_score_long_ragged_with_heavy_rows(oracle, torch_cuda):
     # the MFMA shape (bf16, D 128, G 4, W 32) at a length that is no multiple of the tile, long enough
     # for many subtiles per wavefront, with key rows scaled up so that row references move (rescale path)
