@@ -8,6 +8,7 @@ code with the HIP library and does not import the product package.
 from .sablock_ref import (  # noqa: F401
     build,
     score,
+    score_layer,
     refine,
     search_blocks,
     select,

@@ -106,6 +106,65 @@ int sablock_ref_score(const double *q, const double *k, int32_t G, int32_t W, in
 }
 
 /* ------------------------------------------------------------------------
+ * Window scoring with the head mean taken literally (Eq. barA averages over
+ * ALL H query heads of the layer): one score row per layer instead of one per
+ * KV head.
+ *
+ * q [Hq][W][D] : window queries of every query head of the layer
+ * k [Hkv][L][D]: keys of every KV head; query head h reads KV head h / (Hq/Hkv)
+ * s [L], e [L] : outputs, defined as in sablock_ref_score with Abar the mean
+ *                over the Hq heads.
+ * ---------------------------------------------------------------------- */
+int sablock_ref_score_layer(const double *q, const double *k, int32_t Hq, int32_t Hkv, int32_t W, int32_t D,
+                            int32_t L, double eps, double *s, double *e)
+{
+    if (!q || !k || !s || !e || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || W <= 0 || D <= 0 || L <= W) return 1;
+    const int32_t T = L - W, G = Hq / Hkv;
+    double *abar = (double *)calloc((size_t)W * (size_t)L, sizeof(double));
+    double *x = (double *)malloc((size_t)L * sizeof(double));
+    if (!abar || !x) { free(abar); free(x); return 2; }
+    const double scale = 1.0 / sqrt((double)D);
+
+    for (int32_t h = 0; h < Hq; ++h) {
+        const double *kh = k + (size_t)(h / G) * (size_t)L * D;
+        for (int32_t i = 0; i < W; ++i) {
+            const double *qr = q + ((size_t)h * W + i) * D;
+            const int32_t nvis = T + i + 1;
+            double m = -INFINITY;
+            for (int32_t t = 0; t < nvis; ++t) {
+                const double *kr = kh + (size_t)t * D;
+                double dot = 0.0;
+                for (int32_t d = 0; d < D; ++d) dot += qr[d] * kr[d];
+                x[t] = dot * scale;
+                if (x[t] > m) m = x[t];
+            }
+            double z = 0.0;
+            for (int32_t t = 0; t < nvis; ++t) z += exp(x[t] - m);
+            double *row = abar + (size_t)i * L;
+            for (int32_t t = 0; t < nvis; ++t) row[t] += exp(x[t] - m) / z;
+        }
+    }
+    for (size_t j = 0; j < (size_t)W * (size_t)L; ++j) abar[j] /= (double)Hq;
+
+    for (int32_t t = 0; t < L; ++t) {
+        double st = 0.0;
+        for (int32_t i = 0; i < W; ++i) st += abar[(size_t)i * L + t];
+        s[t] = st;
+        double ent = 0.0;
+        if (st > 0.0) {
+            for (int32_t i = 0; i < W; ++i) {
+                double ah = abar[(size_t)i * L + t] / st;
+                ent -= ah * log(ah + eps);
+            }
+        }
+        e[t] = ent;
+    }
+    free(abar);
+    free(x);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
  * Segment-guided refinement (Alg. 1; Eqs. Ik, Dk, omegak, st_tilde).
  * seg_off[0..K]: 0 = o_0 < ... < o_K = T, segment k = [o_k, o_{k+1}).
  * ---------------------------------------------------------------------- */

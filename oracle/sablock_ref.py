@@ -43,6 +43,8 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         i32, f64 = ctypes.c_int32, ctypes.c_double
         lib.sablock_ref_score.argtypes = [_dp, _dp, i32, i32, i32, i32, f64, _dp, _dp]
+        lib.sablock_ref_score_layer.argtypes = [_dp, _dp, i32, i32, i32, i32, i32, f64, _dp, _dp]
+        lib.sablock_ref_score_layer.restype = ctypes.c_int
         lib.sablock_ref_refine.argtypes = [_dp, _dp, i32, _ip, i32, f64, f64, _dp, _dp]
         lib.sablock_ref_search_blocks.argtypes = [_dp, i32, _ip, i32, _ip, i32, i32, f64, _ip, _ip]
         lib.sablock_ref_select.argtypes = [_dp, i32, _ip, i32, _ip, _ip, i32, _ip, _ip]
@@ -80,6 +82,20 @@ def score(q, k, eps: float = 1e-6) -> Tuple[np.ndarray, np.ndarray]:
     rc = _load().sablock_ref_score(q.ctypes.data_as(_dp), k.ctypes.data_as(_dp), G, W, D, L, float(eps),
                                    s.ctypes.data_as(_dp), e.ctypes.data_as(_dp))
     _check(rc, "score")
+    return s, e
+
+
+def score_layer(q, k, eps: float = 1e-6) -> Tuple[np.ndarray, np.ndarray]:
+    """Head mean over ALL query heads of a layer: q [Hq, W, D], k [Hkv, L, D] -> (s [L], e [L]) in float64."""
+    q, k = _f64(q), _f64(k)
+    Hq, W, D = q.shape
+    Hkv, L = k.shape[0], k.shape[1]
+    assert k.shape[2] == D and Hq % Hkv == 0
+    s = np.empty(L, dtype=np.float64)
+    e = np.empty(L, dtype=np.float64)
+    rc = _load().sablock_ref_score_layer(q.ctypes.data_as(_dp), k.ctypes.data_as(_dp), Hq, Hkv, W, D, L, float(eps),
+                                         s.ctypes.data_as(_dp), e.ctypes.data_as(_dp))
+    _check(rc, "score_layer")
     return s, e
 
 

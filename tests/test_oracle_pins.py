@@ -384,3 +384,38 @@ def test_decode_attention_pins(oracle):
     ref = softmax(q @ k.T / np.sqrt(D + 1.0), axis=1) @ v
     np.testing.assert_allclose(oracle.decode_attention(q1, k1, v), ref, rtol=1e-12, atol=1e-14)
     assert (oracle.decode_attention(q, k[:0], v[:0]) == 0).all()
+
+
+# ---------------------------------------------------------------- head mean over all heads of a layer (Eq. barA, literal)
+def test_score_layer_pins(oracle):
+    from scipy.special import softmax
+
+    rng = np.random.default_rng(17)
+    Hq, Hkv, W, D, L = 6, 3, 5, 8, 41
+    T = L - W
+    q, k = rng.standard_normal((Hq, W, D)), rng.standard_normal((Hkv, L, D))
+    s, e = oracle.score_layer(q, k, 1e-6)
+    # library routines: masked softmax per head, mean over all six heads, column sums, entropy of the
+    # column-normalised means
+    abar = np.zeros((W, L))
+    for h in range(Hq):
+        x = q[h] @ k[h // (Hq // Hkv)].T / np.sqrt(D)
+        for i in range(W):
+            abar[i, :T + i + 1] += softmax(x[i, :T + i + 1]) / Hq
+    np.testing.assert_allclose(s, abar.sum(axis=0), rtol=1e-12, atol=1e-15)
+    ah = abar / abar.sum(axis=0)
+    np.testing.assert_allclose(e, -(ah * np.log(ah + 1e-6)).sum(axis=0), rtol=1e-11, atol=1e-14)
+    assert abs(s.sum() - W) < 1e-12
+    # one KV head: the per-KV-head score is the same thing
+    s1, e1 = oracle.score_layer(q[:2], k[:1], 1e-6)
+    s0, e0 = oracle.score(q[:2], k[0], 1e-6)
+    np.testing.assert_allclose(s1, s0, rtol=1e-14, atol=0)
+    np.testing.assert_allclose(e1, e0, rtol=1e-13, atol=1e-16)
+    # the mean over heads of per-KV-head column sums (linear), though the entropy is not linear
+    per = [oracle.score(q[g * 2:(g + 1) * 2], k[g], 1e-6)[0] for g in range(Hkv)]
+    np.testing.assert_allclose(s, np.mean(per, axis=0), rtol=1e-12, atol=1e-15)
+    # a wrong head-to-KV-head map would show: make KV head 2 special
+    k2 = k.copy(); k2[2] *= 3.0
+    s2, _ = oracle.score_layer(q, k2, 1e-6)
+    per2 = [oracle.score(q[g * 2:(g + 1) * 2], k2[g], 1e-6)[0] for g in range(Hkv)]
+    np.testing.assert_allclose(s2, np.mean(per2, axis=0), rtol=1e-12, atol=1e-15)
