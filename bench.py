@@ -259,6 +259,22 @@ def main():
     dec["speedup"] = dec["full_cache"]["ms_per_token"] / dec["compacted_cache"]["ms_per_token"]
     dec["cache_bytes_ratio"] = rows / w.seq_len
     result["decode_attention"] = dec
+    # the head mean taken literally (one score row per layer): scoring alone, for comparison with the per-KV-head step
+    try:
+        aws = torch.empty((B.sablock_score_all_heads_workspace_bytes(shape),), dtype=torch.uint8, device=dev)
+        s_l = torch.empty((w.n_seq * w.n_layers, w.seq_len), dtype=torch.float32, device=dev)
+        e_l = torch.empty_like(s_l)
+        B.sablock_score_all_heads(shape, q, k, s_l, e_l, aws, w.eps)
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        for _ in range(5):
+            B.sablock_score_all_heads(shape, q, k, s_l, e_l, aws, w.eps)
+        a1.record()
+        torch.cuda.synchronize()
+        result["score_all_heads"] = {"ms": a0.elapsed_time(a1) / 5, "workspace_GB": aws.numel() / 1e9}
+        del aws, s_l, e_l
+    except B.SablockError as ex:
+        result["score_all_heads"] = {"unsupported": str(ex)}
     if not args.no_row_lse:
         # scoring handed the rows' log-sum-exp (single pass over K); lse taken from a first run's statistics
         # is not available through the ABI, so time the kernel on arbitrary finite lse values

@@ -165,6 +165,27 @@ SABLOCK_API sablock_status sablock_compact(const sablock_shape *shape, const voi
                                int32_t append_window, void *k_out, void *v_out, void *stream);
 
 /*
+ * The head mean taken literally (Eq. barA averages over ALL H query heads of a layer): ONE score row, hence one
+ * retained set, per (sequence, layer) instead of one per KV head.
+ *   sablock_score_all_heads   as sablock_score, but Abar[i, t] is the mean over all n_q_heads heads of the layer;
+ *       s_out / ent_out are [n_seq * n_layers][L].  row_lse as in sablock_score.  The workspace
+ *       (sablock_score_all_heads_workspace_bytes) holds the head-group means of every KV head, 4 * W bytes per key
+ *       and KV head, before they are averaged.  Supported: bf16, head_dim 128, (G, W) in {(4, 32), (4, 8), (4, 16),
+ *       (8, 8), (8, 16), (2, 32), (1, 32)}; otherwise UNSUPPORTED.
+ *   refine / search_blocks / select then run on the per-layer rows: pass them a shape whose n_q_heads and
+ *       n_kv_heads are 1 (a problem is then a (sequence, layer)).
+ *   sablock_compact_shared    as sablock_compact with the real head counts, but idx is [n_seq * n_layers][budget]
+ *       and n_sel [n_seq * n_layers]: every KV head of a layer gathers the layer's rows.
+ */
+SABLOCK_API sablock_status sablock_score_all_heads_workspace_bytes(const sablock_shape *shape, size_t *bytes_out);
+SABLOCK_API sablock_status sablock_score_all_heads(const sablock_shape *shape, const void *q_win, const void *k,
+                                       const float *row_lse, float eps, float *s_out, float *ent_out,
+                                       void *ws, size_t ws_bytes, void *stream);
+SABLOCK_API sablock_status sablock_compact_shared(const sablock_shape *shape, const void *k, const void *v,
+                                      const int32_t *idx, const int32_t *n_sel, int32_t budget,
+                                      int32_t append_window, void *k_out, void *v_out, void *stream);
+
+/*
  * Punctuation-based segmentation of the compressible region (Sec. 3.1), the step in front of the five calls:
  * delimiter tokens (commas, periods, ...) mark segment boundaries.  A delimiter closes the segment it belongs to:
  * a new segment starts after every token t < n_tokens - 1 whose id is in `delims`; consecutive delimiters give

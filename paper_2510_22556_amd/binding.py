@@ -24,7 +24,8 @@ SABLOCK_F32, SABLOCK_BF16 = 0, 1
 EXPORTS = ("sablock_version", "sablock_last_error", "sablock_workspace_bytes", "sablock_score",
            "sablock_refine", "sablock_search_blocks", "sablock_select", "sablock_compact",
            "sablock_segment_count", "sablock_segment_offsets", "sablock_decode_workspace_bytes",
-           "sablock_decode_attention")
+           "sablock_decode_attention", "sablock_score_all_heads_workspace_bytes", "sablock_score_all_heads",
+           "sablock_compact_shared")
 
 
 class SablockError(RuntimeError):
@@ -71,6 +72,9 @@ def load():
                                                 ctypes.POINTER(i32), vp, vp]
         lib.sablock_decode_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
         lib.sablock_decode_attention.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, ctypes.c_size_t, vp]
+        lib.sablock_score_all_heads_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
+        lib.sablock_score_all_heads.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.sablock_compact_shared.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
         for n in EXPORTS[2:]:
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
@@ -207,6 +211,30 @@ def segment(token_ids, delims: Sequence[int]) -> "Segments":
     seg_off = torch.empty((ptr[-1],), dtype=torch.int32, device=token_ids.device)
     sablock_segment_offsets(token_ids, delims, ptr, seg_off)
     return Segments(seg_off, ptr, max(c))
+
+
+def layer_shape(shape: CShape) -> CShape:
+    """The shape to pass to refine / search_blocks / select when scores are per (sequence, layer)."""
+    s = CShape.from_buffer_copy(shape)
+    s.n_q_heads = s.n_kv_heads = 1
+    return s
+
+
+def sablock_score_all_heads_workspace_bytes(shape: CShape) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().sablock_score_all_heads_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)))
+    return int(out.value)
+
+
+def sablock_score_all_heads(shape: CShape, q, k, s_out, ent_out, ws, eps: float = 1e-6, row_lse=None, stream=None):
+    _check(load().sablock_score_all_heads(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(row_lse), eps, _ptr(s_out),
+                                          _ptr(ent_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def sablock_compact_shared(shape: CShape, k, v, idx, n_sel, budget: int, append_window: bool, k_out, v_out,
+                           stream=None):
+    _check(load().sablock_compact_shared(ctypes.byref(shape), _ptr(k), _ptr(v), _ptr(idx), _ptr(n_sel), budget,
+                                         1 if append_window else 0, _ptr(k_out), _ptr(v_out), _stream(stream)))
 
 
 def make_cache_shape(q, k_cache, v_cache=None) -> CShape:

@@ -219,8 +219,57 @@ sablock_status sablock_compact(const sablock_shape *shape, const void *k, const 
     if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
         return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact: K/V buffers must be 16-byte aligned");
     if (shape->v_stride[3] < d.D) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact: V token stride smaller than head_dim");
-    return dev(launch_compact(d, k, v, idx, n_sel, budget, append_window, k_out, v_out,
+    return dev(launch_compact(d, k, v, idx, n_sel, budget, append_window, k_out, v_out, 0,
                               static_cast<hipStream_t>(stream)), "sablock_compact");
+}
+
+sablock_status sablock_compact_shared(const sablock_shape *shape, const void *k, const void *v,
+                                      const int32_t *idx, const int32_t *n_sel, int32_t budget,
+                                      int32_t append_window, void *k_out, void *v_out, void *stream)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (budget < 0) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact_shared: budget < 0");
+    if (!k || !v || !n_sel || (!idx && budget > 0)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact_shared: NULL argument");
+    const int rows = budget + (append_window ? d.W : 0);
+    if (rows > 0 && (!k_out || !v_out)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact_shared: NULL output");
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact_shared: K/V buffers must be 16-byte aligned");
+    if (shape->v_stride[3] < d.D) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_compact_shared: V token stride smaller than head_dim");
+    return dev(launch_compact(d, k, v, idx, n_sel, budget, append_window, k_out, v_out, 1,
+                              static_cast<hipStream_t>(stream)), "sablock_compact_shared");
+}
+
+sablock_status sablock_score_all_heads_workspace_bytes(const sablock_shape *shape, size_t *bytes_out)
+{
+    if (!bytes_out) return fail(SABLOCK_ERR_INVALID_ARG, "bytes_out is NULL");
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!score_all_heads_supported(d))
+        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_score_all_heads: needs bf16, head_dim 128 and at most 128 window-query rows per KV head in a shape the MFMA kernels cover");
+    *bytes_out = score_all_heads_ws_bytes(d);
+    return SABLOCK_OK;
+}
+
+sablock_status sablock_score_all_heads(const sablock_shape *shape, const void *q_win, const void *k,
+                                       const float *row_lse, float eps, float *s_out, float *ent_out,
+                                       void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!q_win || !k || !s_out || !ent_out) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score_all_heads: NULL argument");
+    if (!aligned16(q_win) || !aligned16(k)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score_all_heads: Q/K must be 16-byte aligned");
+    if (!(eps >= 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score_all_heads: eps must be >= 0");
+    if (!score_all_heads_supported(d))
+        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_score_all_heads: needs bf16, head_dim 128 and at most 128 window-query rows per KV head in a shape the MFMA kernels cover");
+    const size_t need = score_all_heads_ws_bytes(d);
+    if (!ws || ws_bytes < need)
+        return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_score_all_heads: workspace %zu < %zu bytes", ws_bytes, need);
+    return dev(launch_score_all_heads(d, q_win, k, row_lse, eps, s_out, ent_out, ws, static_cast<hipStream_t>(stream)),
+               "sablock_score_all_heads");
 }
 
 static sablock_status make_delims(const int32_t *delims, int32_t n_delim, DelimSet *ds)

@@ -9,12 +9,14 @@ namespace {
 
 constexpr int NT = 256;
 
-// grid (ceil(rows * chunks / NT), P, 2): z = 0 copies K, z = 1 copies V
+// grid (ceil(rows * chunks / NT), P, 2): z = 0 copies K, z = 1 copies V.  idx_div = 1: every problem has its own
+// index row; idx_div = Hkv: the KV heads of a (sequence, layer) share one (retained set chosen per layer)
 __global__ void __launch_bounds__(NT)
 compact_kernel(Dims d, const char *k, const char *v, const int32_t *idx, const int32_t *n_sel,
-               int budget, int rows, int chunks, int elt, char *k_out, char *v_out)
+               int budget, int rows, int chunks, int elt, char *k_out, char *v_out, int idx_div)
 {
     const int p = blockIdx.y;
+    const int ip = p / idx_div;                         // row of idx / n_sel: the problem, or its (sequence, layer)
     const int e = blockIdx.x * NT + threadIdx.x;
     if (e >= rows * chunks) return;
     const int row = e / chunks, ch = e - row * chunks;
@@ -25,7 +27,7 @@ compact_kernel(Dims d, const char *k, const char *v, const int32_t *idx, const i
     const int64_t tstride = is_v ? d.vs[3] : d.ks[3];
     int t;
     if (row < budget) {
-        t = (row < n_sel[p]) ? idx[(int64_t)p * budget + row] : -1;
+        t = (row < n_sel[ip]) ? idx[(int64_t)ip * budget + row] : -1;
     } else {
         t = d.T + (row - budget);                       // the W most recent rows, in order
     }
@@ -38,7 +40,7 @@ compact_kernel(Dims d, const char *k, const char *v, const int32_t *idx, const i
 
 hipError_t launch_compact(const Dims &d, const void *k, const void *v, const int32_t *idx,
                           const int32_t *n_sel, int32_t budget, int32_t append_window,
-                          void *k_out, void *v_out, hipStream_t st)
+                          void *k_out, void *v_out, int32_t shared_rows, hipStream_t st)
 {
     const int elt = d.dtype == SABLOCK_F32 ? 4 : 2;
     const int rows = budget + (append_window ? d.W : 0);
@@ -47,7 +49,7 @@ hipError_t launch_compact(const Dims &d, const void *k, const void *v, const int
     dim3 grid((unsigned)(((int64_t)rows * chunks + NT - 1) / NT), d.P, 2);
     hipLaunchKernelGGL(compact_kernel, grid, dim3(NT), 0, st, d, static_cast<const char *>(k),
                        static_cast<const char *>(v), idx, n_sel, budget, rows, chunks, elt,
-                       static_cast<char *>(k_out), static_cast<char *>(v_out));
+                       static_cast<char *>(k_out), static_cast<char *>(v_out), shared_rows ? d.Hkv : 1);
     return hipGetLastError();
 }
 

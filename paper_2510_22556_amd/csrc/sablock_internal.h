@@ -88,6 +88,12 @@ size_t score_mfma_ws_bytes(const Dims &d);
 hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
                              float *s_out, float *ent_out, void *ws, hipStream_t st);
 
+// head mean over all query heads of a layer (one score row per layer)
+bool score_all_heads_supported(const Dims &d);
+size_t score_all_heads_ws_bytes(const Dims &d);
+hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
+                                  float *s_out, float *ent_out, void *ws, hipStream_t st);
+
 hipError_t launch_refine(const Dims &d, const float *s, const float *ent, const SegView &sv,
                          sablock_hparams hp, float *s_tilde, float *omega, hipStream_t st);
 
@@ -106,7 +112,7 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
 
 hipError_t launch_compact(const Dims &d, const void *k, const void *v, const int32_t *idx,
                           const int32_t *n_sel, int32_t budget, int32_t append_window,
-                          void *k_out, void *v_out, hipStream_t st);
+                          void *k_out, void *v_out, int32_t shared_rows, hipStream_t st);
 
 // punctuation-based segmentation (the step before the path)
 hipError_t launch_segment_count(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,

@@ -70,6 +70,7 @@ struct ScoreArgs {
     float *partial;        // pass 1 out / pass 2 in: [problem][query block][chunk][128][2] (reference, sum), log2 domain
     const float *lse;      // pass 2 in, optional: [P][G * W] natural-log sum-exp per row (NULL: use partial)
     float *s_out, *e_out;  // pass 2 out: [P][L]
+    float *abar;           // pass 2 out of the all-head variant: head-group means [P][W / 4][L][4]
 };
 
 __device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)(lptr_t)p; }
@@ -830,6 +831,8 @@ template <int G, int W> struct Rows {
     __device__ static int query(int J, int i, int hf) { return W >= 32 ? 32 * (J % QB) + tile_row(i, hf) : tile_row(i, hf) % W; }
     __device__ static int head(int J, int i, int hf) { return W >= 32 ? J / QB : J * (32 / W) + tile_row(i, hf) / W; }
     __host__ __device__ static constexpr int slot(int J, int i) { return W >= 32 ? 16 * (J % QB) + i : i % (W / 2); }
+    // window query that head-mean value `s` of lane half hf belongs to
+    __device__ static int slot_query(int s, int hf) { return W >= 32 ? 32 * (s / 16) + tile_row(s % 16, hf) : tile_row(s, hf) % W; }
 };
 
 template <int G, int W>
@@ -919,7 +922,10 @@ score_mfma_stats_g(ScoreArgs a)
     }
 }
 
-template <int G, int W>
+// STORE: instead of the column sum and entropy of the KV head, write the head-group mean Abar[query][key] itself
+// (for the mean over ALL heads of a layer, which is formed across KV heads afterwards), four consecutive window
+// queries of a key per 16-byte store, layout [problem][W / 4][L][4].
+template <int G, int W, bool STORE>
 __global__ void __launch_bounds__(WAVES * 64)
 score_mfma_columns_g(ScoreArgs a)
 {
@@ -994,6 +1000,17 @@ score_mfma_columns_g(ScoreArgs a)
                 ab[R::slot(J, i)] += v;                                                 // Eq. barA
             }
         }
+        if (STORE) {
+            if (t < d.L) {
+#pragma unroll
+                for (int j = 0; j < NS / 4; ++j) {
+                    const int qd = R::slot_query(4 * j, hf) >> 2;                        // slots 4j .. 4j+3: four consecutive queries
+                    float4 *dst = reinterpret_cast<float4 *>(a.abar) + ((int64_t)w.p * (W / 4) + qd) * d.L + t;
+                    *dst = make_float4(ab[4 * j], ab[4 * j + 1], ab[4 * j + 2], ab[4 * j + 3]);
+                }
+            }
+            continue;
+        }
         float s_part = 0.f;
 #pragma unroll
         for (int i = 0; i < NS; ++i) s_part += ab[i];
@@ -1013,7 +1030,7 @@ score_mfma_columns_g(ScoreArgs a)
 template <int G, int W> constexpr int stats_g_lds() { return 4 * 4 * BUF_BYTES + 4 * G * W * 2 * 4 + 4 * G * W * 4; }
 template <int G, int W> constexpr int columns_g_lds() { return 4 * 4 * BUF_BYTES + G * W * 4; }
 
-template <int G, int W>
+template <int G, int W, bool STORE>
 hipError_t launch_score_g(const ScoreArgs &a, dim3 grid, bool with_stats, hipStream_t st)
 {
     static bool attr_done = false;
@@ -1021,15 +1038,50 @@ hipError_t launch_score_g(const ScoreArgs &a, dim3 grid, bool with_stats, hipStr
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats_g<G, W>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, stats_g_lds<G, W>());
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_g<G, W>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_g<G, W, STORE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, columns_g_lds<G, W>());
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     constexpr int lds1 = stats_g_lds<G, W>(), lds2 = columns_g_lds<G, W>();
     if (with_stats) hipLaunchKernelGGL((score_mfma_stats_g<G, W>), grid, dim3(WAVES * 64), lds1, st, a);
-    hipLaunchKernelGGL((score_mfma_columns_g<G, W>), grid, dim3(WAVES * 64), lds2, st, a);
+    hipLaunchKernelGGL((score_mfma_columns_g<G, W, STORE>), grid, dim3(WAVES * 64), lds2, st, a);
     return hipGetLastError();
+}
+
+// Mean over the KV heads of a layer of the head-group means, then column sum and entropy term (Eqs. barA with
+// all H heads, st, inner sum of Dk): one thread per key.  grid (ceil(L / 256), n_seq * n_layers)
+template <int W>
+__global__ void __launch_bounds__(256)
+abar_reduce_kernel(const float *abar, int Hkv, int L, float eps, float *s_out, float *e_out)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= L) return;
+    const int sl = blockIdx.y;
+    float ab[W];
+#pragma unroll
+    for (int i = 0; i < W; ++i) ab[i] = 0.f;
+    for (int kv = 0; kv < Hkv; ++kv) {
+        const float4 *src = reinterpret_cast<const float4 *>(abar) + ((int64_t)(sl * Hkv + kv) * (W / 4)) * L + t;
+#pragma unroll
+        for (int j = 0; j < W / 4; ++j) {
+            const float4 v = src[(int64_t)j * L];
+            ab[4 * j] += v.x; ab[4 * j + 1] += v.y; ab[4 * j + 2] += v.z; ab[4 * j + 3] += v.w;
+        }
+    }
+    const float inv_h = 1.0f / (float)Hkv;
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < W; ++i) { ab[i] *= inv_h; s += ab[i]; }
+    const float inv_s = s > 0.f ? 1.0f / s : 0.f;
+    float e = 0.f;
+#pragma unroll
+    for (int i = 0; i < W; ++i) {
+        const float ah = ab[i] * inv_s;
+        e = fmaf(ah, __builtin_amdgcn_logf(ah + eps), e);
+    }
+    s_out[(int64_t)sl * L + t] = s;
+    e_out[(int64_t)sl * L + t] = -LN2 * e;
 }
 
 // the (G, W) pairs served by the generic-row kernels
@@ -1108,10 +1160,11 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.e_out = ent_out;
     a.partial = static_cast<float *>(ws);
     a.lse = row_lse;
+    a.abar = nullptr;
     a.p0 = 0;
     a.nv = d.G * d.W > M_ROWS ? d.G * d.W / M_ROWS : 1;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
-#define X(GV, WV) if (d.G == GV && d.W == WV) return launch_score_g<GV, WV>(a, grid, !row_lse, st);
+#define X(GV, WV) if (d.G == GV && d.W == WV) return launch_score_g<GV, WV, false>(a, grid, !row_lse, st);
     SABLOCK_SMALL_SHAPES(X)
 #undef X
     dim3 grid1((unsigned)((int64_t)d.P * a.nv * pl.n_chunks));
@@ -1119,6 +1172,51 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     if (d.W == 64) hipLaunchKernelGGL(score_mfma_columns8t<64>, grid, dim3(WAVES * 64), P2W_LDS, st, a);
     else if (d.G == 8) hipLaunchKernelGGL(score_mfma_columns8t<32>, grid, dim3(WAVES * 64), P2W_LDS, st, a);
     else hipLaunchKernelGGL(score_mfma_columns, grid, dim3(WAVES * 64), P2_LDS, st, a);
+    return hipGetLastError();
+}
+
+// ---- head mean over all query heads of a layer (Eq. barA, literal): shapes with up to 128 window-query rows
+bool score_all_heads_supported(const Dims &d)
+{
+    return d.dtype == SABLOCK_BF16 && d.D == 128 && ((d.G == 4 && d.W == 32) || small_shape(d));
+}
+
+size_t score_all_heads_ws_bytes(const Dims &d)
+{
+    const Plan pl = make_plan(d);
+    return align256((size_t)d.P * pl.n_chunks * d.G * d.W * 2 * 4) + align256((size_t)d.P * d.L * d.W * 4);
+}
+
+hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
+                                  float *s_out, float *ent_out, void *ws, hipStream_t st)
+{
+    const Plan pl = make_plan(d);
+    ScoreArgs a;
+    a.d = d;
+    a.q = static_cast<const uint16_t *>(q);
+    a.k = static_cast<const uint16_t *>(k);
+    a.chunk_len = pl.chunk_len;
+    a.n_chunks = pl.n_chunks;
+    a.nv = 1;
+    a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
+    a.eps = eps;
+    a.s_out = nullptr;
+    a.e_out = nullptr;
+    a.partial = static_cast<float *>(ws);
+    a.abar = reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.P * pl.n_chunks * d.G * d.W * 2 * 4));
+    a.lse = row_lse;
+    a.p0 = 0;
+    dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
+    hipError_t e = hipErrorInvalidValue;
+#define X(GV, WV) if (d.G == GV && d.W == WV) e = launch_score_g<GV, WV, true>(a, grid, !row_lse, st);
+    SABLOCK_SMALL_SHAPES(X)
+    X(4, 32)
+#undef X
+    if (e != hipSuccess) return e;
+    dim3 rgrid((unsigned)((d.L + 255) / 256), (unsigned)(d.n_seq * d.n_layers));
+#define X(WV) if (d.W == WV) hipLaunchKernelGGL(abar_reduce_kernel<WV>, rgrid, dim3(256), 0, st, a.abar, d.Hkv, d.L, eps, s_out, ent_out);
+    X(8) X(16) X(32)
+#undef X
     return hipGetLastError();
 }
 

@@ -632,3 +632,61 @@ def test_decode_attention_128k_full_and_compacted(oracle, torch_cuda):
         ref = oracle.decode_attention(H.widen(H.to_np(qn[0, l, h * w.G:(h + 1) * w.G])), H.widen(H.to_np(kc[0, l, h])),
                                       H.widen(H.to_np(vc[0, l, h])))
         np.testing.assert_allclose(out_c[0, l, h * w.G:(h + 1) * w.G], ref, rtol=2e-4, atol=2e-5)
+
+
+@pytest.mark.parametrize("G,W", [(4, 32), (4, 8), (2, 32)])
+def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, monkeypatch, G, W):
+    # Eq. barA taken literally: one score row and one retained set per (sequence, layer).  Scores against the
+    # oracle's all-head mean; refine / search / select stage-wise on the per-layer rows; shared compaction
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "2048")
+    Hkv, D, nl, ns = 3, 128, 2, 1
+    L = 2 * 2048 + 300 + W
+    T = L - W
+    q = synth.normal_torch(606 + W, 1, (ns, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(606 + W, 2, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(606 + W, 3, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    k[0, 0, 1, 1234, :] = (q[0, 0, G + 1, W - 1, :].float() * 5.0).to(torch.bfloat16)      # a row reference moves
+    off = synth.segment_offsets(606, T, mean=32.0, min_len=1, max_len=256)
+    seg = B.make_segments(off, [0, len(off)], "cuda")
+    cand, budget, eps, alpha, eta, tau = [1, 2, 4, 8, 16, 32], 400, 1e-6, 0.9, 1.0, 0.85
+    shape = B.make_shape(q, k, v)
+    ls = B.layer_shape(shape)
+    buf = B.Buffers(ls, seg, budget, "cuda", dtype=torch.bfloat16)       # per-layer rows (P' = n_seq * n_layers)
+    ws = torch.empty((B.sablock_score_all_heads_workspace_bytes(shape),), dtype=torch.uint8, device="cuda")
+    B.sablock_score_all_heads(shape, q, k, buf.s, buf.ent, ws, eps)
+    B.sablock_refine(ls, buf.s, buf.ent, seg, buf.s_tilde, buf.ws, alpha, eta, buf.omega)
+    B.sablock_search_blocks(ls, buf.s_tilde, seg, cand, budget, tau, buf.seg_budget, buf.block_size, buf.ws,
+                            topb_out=buf.topb)
+    B.sablock_select(ls, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws,
+                     topb=buf.topb)
+    rows = budget + W
+    ko = torch.empty((ns * nl * Hkv, rows, D), dtype=torch.bfloat16, device="cuda")
+    vo = torch.empty_like(ko)
+    B.sablock_compact_shared(shape, k, v, buf.idx, buf.n_sel, budget, True, ko, vo)
+    torch.cuda.synchronize()
+    K = len(off) - 1
+    for l in range(nl):
+        s_ref, e_ref = oracle.score_layer(H.widen(H.to_np(q[0, l])), H.widen(H.to_np(k[0, l])), eps)
+        s_g, e_g = H.to_np(buf.s)[l], H.to_np(buf.ent)[l]
+        H.close(s_g, s_ref, f"s[layer {l}]")
+        H.close(e_g, e_ref, f"ent[layer {l}]")
+        assert abs(s_g.sum() - W) < 1e-3
+        st_ref, _ = oracle.refine(s_g, e_g, off, H.f32(alpha), H.f32(eta))
+        st_g = H.to_np(buf.s_tilde)[l]
+        np.testing.assert_allclose(st_g, st_ref, rtol=3e-7, atol=0)
+        b_ref, g_ref = oracle.search_blocks(st_g, off, cand, budget, H.f32(tau))
+        np.testing.assert_array_equal(H.to_np(buf.seg_budget)[l][:K], b_ref)
+        np.testing.assert_array_equal(H.to_np(buf.block_size)[l][:K], g_ref)
+        idx_ref, n_ref = oracle.select(st_g, off, b_ref, g_ref, budget)
+        assert H.to_np(buf.n_sel)[l] == n_ref == budget
+        idx_g = H.to_np(buf.idx)[l]
+        np.testing.assert_array_equal(idx_g, idx_ref)
+        for h in range(Hkv):
+            ke, ve = oracle.compact(H.to_np(k[0, l, h]), H.to_np(v[0, l, h]), W, idx_g, int(n_ref), budget, True)
+            np.testing.assert_array_equal(H.to_np(ko[l * Hkv + h]), ke)
+            np.testing.assert_array_equal(H.to_np(vo[l * Hkv + h]), ve)
+    # the per-layer retained set differs from what a single KV head would keep
+    assert (H.to_np(buf.block_size) > 1).any()
