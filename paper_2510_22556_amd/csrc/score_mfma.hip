@@ -34,6 +34,7 @@
 // as A operands (256 accumulation registers), the keys in ordinary registers and the C operands in LDS.
 #include "sablock_internal.h"
 
+#include <algorithm>
 #include <cstdlib>
 
 namespace sablock {
@@ -65,9 +66,11 @@ struct ScoreArgs {
     int chunk_len;         // keys per workgroup, multiple of STRIDE
     int n_chunks;          // workgroups per problem
     int nv;                // 128-row blocks per problem in pass 1 (G * W / 128)
+    int pc;                // (reference, sum) pairs per row that pass 2 reads: n_chunks, or 1 once they are merged
     float c1;              // log2(e) / sqrt(D)
     float eps;
-    float *partial;        // pass 1 out / pass 2 in: [problem][query block][chunk][128][2] (reference, sum), log2 domain
+    float *partial;        // pass 1 out: [problem][query block][chunk][128][2] (reference, sum), log2 domain
+    const float *merged;   // pass 2 in: the same layout with pc chunks
     const float *lse;      // pass 2 in, optional: [P][G * W] natural-log sum-exp per row (NULL: use partial)
     float *s_out, *e_out;  // pass 2 out: [P][L]
     float *abar;           // pass 2 out of the all-head variant: head-group means [P][W / 4][L][4]
@@ -559,9 +562,9 @@ score_mfma_columns(ScoreArgs a)
             m = a.lse[(int64_t)w.p * M_ROWS + row] * LOG2E;
             zz = half == 0 ? 1.f : 0.f;
         } else {
-            const float *pp = a.partial + ((int64_t)w.p * a.n_chunks * M_ROWS + row) * 2;
+            const float *pp = a.merged + ((int64_t)w.p * a.pc * M_ROWS + row) * 2;
 #pragma unroll 4
-            for (int c = half; c < a.n_chunks; c += 2) {
+            for (int c = half; c < a.pc; c += 2) {
                 const float2 e = *reinterpret_cast<const float2 *>(pp + (int64_t)c * M_ROWS * 2);
                 if (e.y > 0.f) {
                     const float mn = fmaxf(m, e.x);
@@ -743,8 +746,8 @@ score_mfma_columns8t(ScoreArgs a)
             m = a.lse[(int64_t)w.p * M_ROWS64 + r] * LOG2E;
             zz = 1.f;
         } else {
-            const float *pp = a.partial + (((int64_t)(w.p * 2 + TL::p1_block(j)) * a.n_chunks) * M_ROWS + TL::p1_group(j) * 32 + (i & 31)) * 2;
-            for (int c = 0; c < a.n_chunks; ++c) {
+            const float *pp = a.merged + (((int64_t)(w.p * 2 + TL::p1_block(j)) * a.pc) * M_ROWS + TL::p1_group(j) * 32 + (i & 31)) * 2;
+            for (int c = 0; c < a.pc; ++c) {
                 const float2 e = *reinterpret_cast<const float2 *>(pp + (int64_t)c * M_ROWS * 2);
                 if (e.y > 0.f) {
                     const float mn = fmaxf(m, e.x);
@@ -950,8 +953,8 @@ score_mfma_columns_g(ScoreArgs a)
             m = a.lse[(int64_t)w.p * M + r] * LOG2E;
             zz = 1.f;
         } else {
-            const float *pp = a.partial + ((int64_t)w.p * a.n_chunks * M + r) * 2;
-            for (int c = 0; c < a.n_chunks; ++c) {
+            const float *pp = a.merged + ((int64_t)w.p * a.pc * M + r) * 2;
+            for (int c = 0; c < a.pc; ++c) {
                 const float2 e = *reinterpret_cast<const float2 *>(pp + (int64_t)c * M * 2);
                 if (e.y > 0.f) {
                     const float mn = fmaxf(m, e.x);
@@ -1030,6 +1033,47 @@ score_mfma_columns_g(ScoreArgs a)
 template <int G, int W> constexpr int stats_g_lds() { return 4 * 4 * BUF_BYTES + 4 * G * W * 2 * 4 + 4 * G * W * 4; }
 template <int G, int W> constexpr int columns_g_lds() { return 4 * 4 * BUF_BYTES + G * W * 4; }
 
+// Folds the chunk partials of pass 1 into one (reference, sum) pair per row, one wavefront per row, so that
+// with many chunks per problem the workgroups of pass 2 do not each repeat the fold.
+// partial [blocks][n_chunks][M][2] -> merged [blocks][M][2]; grid ceil(blocks * M / 4), 256 threads
+__global__ void __launch_bounds__(256)
+merge_partials_kernel(const float *partial, float *merged, int n_chunks, int M, int n_rows)
+{
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= n_rows) return;
+    const int blk = r / M, row = r - blk * M;
+    const float *pp = partial + ((int64_t)blk * n_chunks * M + row) * 2;
+    float m = -INFINITY, z = 0.f;
+    for (int c = lane; c < n_chunks; c += 64) {
+        const float2 e = *reinterpret_cast<const float2 *>(pp + (int64_t)c * M * 2);
+        if (e.y > 0.f) {
+            const float mn = fmaxf(m, e.x);
+            z = z * __builtin_amdgcn_exp2f(m - mn) + e.y * __builtin_amdgcn_exp2f(e.x - mn);
+            m = mn;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float m2 = __shfl_xor(m, off), z2 = __shfl_xor(z, off);
+        const float mn = fmaxf(m, m2);
+        z = (z > 0.f ? z * __builtin_amdgcn_exp2f(m - mn) : 0.f) + (z2 > 0.f ? z2 * __builtin_amdgcn_exp2f(m2 - mn) : 0.f);
+        m = mn;
+    }
+    if (lane == 0) {
+        merged[(int64_t)r * 2] = m;
+        merged[(int64_t)r * 2 + 1] = z;
+    }
+}
+
+// enqueues the fold when pass 2 is to read merged pairs (a.pc == 1 with more than one chunk)
+void launch_merge(const ScoreArgs &a, int blocks, int M, hipStream_t st)
+{
+    if (a.merged == a.partial) return;
+    const int n_rows = blocks * M;
+    hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)((n_rows + 3) / 4)), dim3(256), 0, st,
+                       a.partial, const_cast<float *>(a.merged), a.n_chunks, M, n_rows);
+}
+
 template <int G, int W, bool STORE>
 hipError_t launch_score_g(const ScoreArgs &a, dim3 grid, bool with_stats, hipStream_t st)
 {
@@ -1044,7 +1088,10 @@ hipError_t launch_score_g(const ScoreArgs &a, dim3 grid, bool with_stats, hipStr
         attr_done = true;
     }
     constexpr int lds1 = stats_g_lds<G, W>(), lds2 = columns_g_lds<G, W>();
-    if (with_stats) hipLaunchKernelGGL((score_mfma_stats_g<G, W>), grid, dim3(WAVES * 64), lds1, st, a);
+    if (with_stats) {
+        hipLaunchKernelGGL((score_mfma_stats_g<G, W>), grid, dim3(WAVES * 64), lds1, st, a);
+        launch_merge(a, a.d.P, G * W, st);
+    }
     hipLaunchKernelGGL((score_mfma_columns_g<G, W, STORE>), grid, dim3(WAVES * 64), lds2, st, a);
     return hipGetLastError();
 }
@@ -1098,20 +1145,62 @@ bool small_shape(const Dims &d)
 struct Plan {
     int chunk_len;    // keys per workgroup
     int n_chunks;     // workgroups per problem
+    bool merge;       // fold the chunk partials in a kernel of its own between the passes
 };
+
+constexpr int MERGE_FROM = 8;       // chunks per problem from which the separate fold pays
+
+int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        cus = n;
+    }
+    return cus;
+}
 
 Plan make_plan(const Dims &d)
 {
-    // One launch per pass covers every problem.  A workgroup owns chunk_len consecutive keys of one problem;
-    // long chunks amortise its prologue (window queries into registers, first loads), but there should be at
-    // least a few workgroups per CU so that the 256 CUs stay evenly loaded.
+    // One launch per pass covers every problem.  A workgroup owns chunk_len consecutive keys of one problem, and
+    // one workgroup fills a CU (registers and the load ring).  Each round of workgroups costs a prologue and an
+    // epilogue during which its CU loads nothing (measured: about 17 us per round and pass), so the plan aims at
+    // a whole number of rounds, as few as keep a chunk at or under MAX_CHUNK keys.
+    constexpr int MAX_CHUNK = 32768;
     Plan pl;
-    int len = 32768;
-    if (const char *e = getenv("SABLOCK_SCORE_CHUNK")) { int v = atoi(e); if (v >= STRIDE) len = (v / STRIDE) * STRIDE; }
-    else while (len > STRIDE && (int64_t)d.P * ((d.L + len - 1) / len) < 1024) len /= 2;
+    int len;
+    if (const char *e = getenv("SABLOCK_SCORE_CHUNK"); e && atoi(e) >= STRIDE) len = (atoi(e) / STRIDE) * STRIDE;
+    else {
+        const int64_t cus = compute_units();
+        const int64_t rounds = ((int64_t)d.P * d.L + cus * MAX_CHUNK - 1) / (cus * MAX_CHUNK);
+        const int64_t per_problem = std::max<int64_t>(1, (cus * rounds + d.P / 2) / d.P);     // chunks per problem
+        len = (int)(((d.L + per_problem - 1) / per_problem + STRIDE - 1) / STRIDE) * STRIDE;
+        len = std::min(std::max(len, STRIDE), MAX_CHUNK);
+    }
     pl.chunk_len = len;
     pl.n_chunks = (d.L + len - 1) / len;
+    pl.merge = pl.n_chunks >= MERGE_FROM;
     return pl;
+}
+
+// bytes of the chunk partials, and of their merged form behind them
+size_t partial_bytes(const Dims &d, const Plan &pl) { return align256((size_t)d.P * pl.n_chunks * d.G * d.W * 2 * 4); }
+size_t merged_bytes(const Dims &d) { return align256((size_t)d.P * d.G * d.W * 2 * 4); }
+
+// pass-1 bookkeeping of both entry points: where the partials go and what pass 2 reads
+void plan_partials(ScoreArgs &a, const Dims &d, const Plan &pl, void *ws)
+{
+    a.chunk_len = pl.chunk_len;
+    a.n_chunks = pl.n_chunks;
+    a.partial = static_cast<float *>(ws);
+    a.merged = a.partial;
+    a.pc = pl.n_chunks;
+    if (pl.merge) {
+        a.merged = reinterpret_cast<float *>(static_cast<char *>(ws) + partial_bytes(d, pl));
+        a.pc = 1;
+    }
 }
 
 }  // namespace
@@ -1124,8 +1213,8 @@ bool score_mfma_supported(const Dims &d)
 
 size_t score_mfma_ws_bytes(const Dims &d)
 {
-    Plan pl = make_plan(d);
-    return align256((size_t)d.P * pl.n_chunks * d.G * d.W * 2 * 4);
+    const Plan pl = make_plan(d);
+    return partial_bytes(d, pl) + merged_bytes(d);
 }
 
 hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
@@ -1152,13 +1241,11 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.d = d;
     a.q = static_cast<const uint16_t *>(q);
     a.k = static_cast<const uint16_t *>(k);
-    a.chunk_len = pl.chunk_len;
-    a.n_chunks = pl.n_chunks;
+    plan_partials(a, d, pl, ws);
     a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
     a.eps = eps;
     a.s_out = s_out;
     a.e_out = ent_out;
-    a.partial = static_cast<float *>(ws);
     a.lse = row_lse;
     a.abar = nullptr;
     a.p0 = 0;
@@ -1168,7 +1255,10 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     SABLOCK_SMALL_SHAPES(X)
 #undef X
     dim3 grid1((unsigned)((int64_t)d.P * a.nv * pl.n_chunks));
-    if (!row_lse) hipLaunchKernelGGL(score_mfma_stats, grid1, dim3(WAVES * 64), P1_LDS, st, a);
+    if (!row_lse) {
+        hipLaunchKernelGGL(score_mfma_stats, grid1, dim3(WAVES * 64), P1_LDS, st, a);
+        launch_merge(a, d.P * a.nv, M_ROWS, st);
+    }
     if (d.W == 64) hipLaunchKernelGGL(score_mfma_columns8t<64>, grid, dim3(WAVES * 64), P2W_LDS, st, a);
     else if (d.G == 8) hipLaunchKernelGGL(score_mfma_columns8t<32>, grid, dim3(WAVES * 64), P2W_LDS, st, a);
     else hipLaunchKernelGGL(score_mfma_columns, grid, dim3(WAVES * 64), P2_LDS, st, a);
@@ -1184,7 +1274,7 @@ bool score_all_heads_supported(const Dims &d)
 size_t score_all_heads_ws_bytes(const Dims &d)
 {
     const Plan pl = make_plan(d);
-    return align256((size_t)d.P * pl.n_chunks * d.G * d.W * 2 * 4) + align256((size_t)d.P * d.L * d.W * 4);
+    return partial_bytes(d, pl) + merged_bytes(d) + align256((size_t)d.P * d.L * d.W * 4);
 }
 
 hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
@@ -1195,15 +1285,13 @@ hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, c
     a.d = d;
     a.q = static_cast<const uint16_t *>(q);
     a.k = static_cast<const uint16_t *>(k);
-    a.chunk_len = pl.chunk_len;
-    a.n_chunks = pl.n_chunks;
+    plan_partials(a, d, pl, ws);
     a.nv = 1;
     a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
     a.eps = eps;
     a.s_out = nullptr;
     a.e_out = nullptr;
-    a.partial = static_cast<float *>(ws);
-    a.abar = reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.P * pl.n_chunks * d.G * d.W * 2 * 4));
+    a.abar = reinterpret_cast<float *>(static_cast<char *>(ws) + partial_bytes(d, pl) + merged_bytes(d));
     a.lse = row_lse;
     a.p0 = 0;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));

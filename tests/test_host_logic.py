@@ -124,6 +124,38 @@ def test_decode_calls_validate_host_arguments(lib):
         assert ei.value.status == status, bad
 
 
+def test_all_head_calls_validate_host_arguments(lib):
+    def llama_shape(**kw):
+        T, W, D = 4096, 32, 128
+        s = _shape(dtype=B.SABLOCK_BF16, head_dim=D, n_q_heads=8, n_kv_heads=2, seq_len=T, window=W)
+        for a, (qv, kv) in enumerate([(8 * W * D, 2 * T * D), (8 * W * D, 2 * T * D), (W * D, T * D), (D, D)]):
+            s.q_stride[a], s.k_stride[a], s.v_stride[a] = qv, kv, kv
+        for k, v in kw.items():
+            setattr(s, k, v)
+        return s
+
+    n = B.sablock_score_all_heads_workspace_bytes(llama_shape())
+    L = 4096 - 32
+    assert n >= 2 * L * 32 * 4            # at least the head-group means of both KV heads
+    fake = ctypes.c_void_p(0x1000)
+    sp = ctypes.byref(llama_shape())
+    assert lib.sablock_score_all_heads(sp, None, fake, None, 1e-6, fake, fake, fake, n, None) == 1
+    assert lib.sablock_score_all_heads(sp, fake, fake, None, 1e-6, fake, fake, fake, n - 1, None) == 3
+    assert lib.sablock_score_all_heads(sp, fake, fake, None, 1e-6, fake, fake, None, n, None) == 3
+    assert lib.sablock_score_all_heads(sp, fake, ctypes.c_void_p(0x1008), None, 1e-6, fake, fake, fake, n, None) == 1
+    assert lib.sablock_score_all_heads(sp, fake, fake, None, -1.0, fake, fake, fake, n, None) == 1
+    for bad in (dict(dtype=B.SABLOCK_F32), dict(head_dim=64), dict(window=64)):
+        with pytest.raises(B.SablockError) as ei:
+            B.sablock_score_all_heads_workspace_bytes(llama_shape(**bad))
+        assert ei.value.status == 2, bad
+    assert lib.sablock_compact_shared(sp, fake, None, fake, fake, 8, 1, fake, fake, None) == 1
+    assert lib.sablock_compact_shared(sp, fake, fake, fake, fake, -8, 1, fake, fake, None) == 1
+    assert lib.sablock_compact_shared(sp, fake, fake, None, fake, 8, 1, fake, fake, None) == 1
+    assert lib.sablock_compact_shared(sp, fake, fake, fake, fake, 8, 1, None, fake, None) == 1
+    ls = B.layer_shape(llama_shape())
+    assert (ls.n_q_heads, ls.n_kv_heads, ls.seq_len, ls.window) == (1, 1, 4096, 32)
+
+
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
