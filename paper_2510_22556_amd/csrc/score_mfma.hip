@@ -1168,7 +1168,7 @@ Plan make_plan(const Dims &d)
     // one workgroup fills a CU (registers and the load ring).  Each round of workgroups costs a prologue and an
     // epilogue during which its CU loads nothing (measured: about 17 us per round and pass), so the plan aims at
     // a whole number of rounds, as few as keep a chunk at or under MAX_CHUNK keys.
-    constexpr int MAX_CHUNK = 32768;
+    constexpr int MAX_CHUNK = 131072;
     Plan pl;
     int len;
     if (const char *e = getenv("SABLOCK_SCORE_CHUNK"); e && atoi(e) >= STRIDE) len = (atoi(e) / STRIDE) * STRIDE;
