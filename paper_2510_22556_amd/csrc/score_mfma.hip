@@ -818,6 +818,237 @@ score_mfma_columns8t(ScoreArgs a)
     }
 }
 
+// ------------------------------------------------------------------ pass 2, all heads of a layer
+// Head mean over all 32 heads of a layer with 8 KV heads (Eq. barA taken literally) without writing the
+// per-KV-head means to memory.  A workgroup owns a chunk of keys of one (sequence, layer).  Wavefront w multiplies
+// the keys of KV heads 2w and 2w+1 (two load streams interleaved in one ring) by those heads' 8 query heads (256
+// accumulation registers of A operands) and adds exp2 over its 8 heads; the four partial sums of a subtile meet
+// in LDS, where the wavefronts take turns (subtile u: wavefront u % 4) to add them and to form the column sum
+// and the entropy term.  One barrier per subtile; it waits for LDS only, never for the loads in flight.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+constexpr int LAYER_KV = 8;                   // KV heads of a layer this kernel is built for (two per wavefront)
+constexpr int XCH_BYTES = 16 * 64 * 4;        // one wavefront's partial sums of a subtile, [4][64 lanes][4]
+constexpr int PL_LDS = WAVES * RING_BYTES + 2 * 3 * XCH_BYTES + WAVES * 8 * 32 * 4;   // rings + exchange + C operands
+
+// Two key streams of one wavefront as one sequence of half-steps: element e = 2u + s is subtile u of stream s and
+// lives in ring buffer e % NBUF, refilled with element e + NBUF right after it is read.  Subtile u covers keys
+// [first + u * SUB, +SUB): here all wavefronts of a workgroup walk the same keys.
+struct PairStream {
+    const uint16_t *kp0, *kp1;
+    int64_t ks3;
+    uint32_t lane_addr0, ring_lds;
+    uint32_t lane_off[4];
+    int first, n_el, L, lane;
+
+    __device__ __forceinline__ void init(const uint16_t *k0, const uint16_t *k1, int64_t ks3_, char *ring, int first_, int n_sub, int L_, int lane_)
+    {
+        kp0 = k0; kp1 = k1; ks3 = ks3_; first = first_; n_el = 2 * n_sub; L = L_; lane = lane_;
+        const int n = lane & 31, hf = lane >> 5, r4 = lane >> 4, pos = lane & 15;
+        ring_lds = __builtin_amdgcn_readfirstlane(lds_addr(ring));
+        lane_addr0 = ring_lds + n * ROW_BYTES + ((hf ^ (n & 15)) << 4);
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) lane_off[jj] = (uint32_t)(r4 * ks3 * 2) + (uint32_t)(((pos ^ r4 ^ (4 * jj)) & 15) << 4);
+    }
+    __device__ __forceinline__ void issue(int e) const
+    {
+        const int t0 = first + (e >> 1) * SUB;                 // wave-uniform, < L
+        const char *base = reinterpret_cast<const char *>((e & 1) ? kp1 : kp0) + (int64_t)t0 * ks3 * 2;
+        const uint32_t buf_lds = ring_lds + (e % NBUF) * BUF_BYTES;
+        if (t0 + SUB <= L) issue_subtile_fast(base, ks3 * 2, lane_off, buf_lds);
+        else issue_subtile_clamped(base, ks3 * 2, L - t0, buf_lds, lane);
+    }
+    __device__ __forceinline__ void prime() const
+    {
+#pragma unroll
+        for (int e = 0; e < NBUF; ++e)
+            if (e < n_el) issue(e);
+    }
+    __device__ __forceinline__ void fetch(int e, bf16x8 (&kb)[8]) const
+    {
+        wait_loads(min(NBUF - 1, n_el - 1 - e));
+        read_subtile_vgpr(lane_addr0 + (e % NBUF) * BUF_BYTES, kb);
+        if (e + NBUF < n_el) issue(e + NBUF);
+    }
+};
+
+// this lane's 16 partial sums into an exchange slot / the sum of `ab` and the three slots of a buffer
+__device__ __forceinline__ void xch_write(uint32_t addr, const float (&ab)[16])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const floatx4 v = {ab[4 * j], ab[4 * j + 1], ab[4 * j + 2], ab[4 * j + 3]};
+        asm volatile("ds_write_b128 %0, %1" : : "v"(addr + j * 1024), "v"(v) : "memory");
+    }
+}
+__device__ __forceinline__ void xch_add(uint32_t addr, float (&ab)[16])
+{
+    floatx4 v[3][4];
+#pragma unroll
+    for (int sl = 0; sl < 3; ++sl)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            asm volatile("ds_read_b128 %0, %1" : "=v"(v[sl][j]) : "v"(addr + sl * XCH_BYTES + j * 1024) : "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[0][2]), "+v"(v[0][3]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[1][2]),
+                   "+v"(v[1][3]), "+v"(v[2][0]), "+v"(v[2][1]), "+v"(v[2][2]), "+v"(v[2][3])
+                 :
+                 : "memory");
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ab[4 * j + c] += v[0][j][c] + v[1][j][c] + v[2][j][c];
+}
+// all LDS writes of this wavefront done, then the workgroup barrier (global loads stay in flight)
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+struct LayerCtx {
+    uint32_t xch_lds;      // exchange area
+    int wave, lane, n, hf;
+    int lo;                // first key of the chunk
+    float c1, eps;
+    int T, L;
+    float *out;            // s (lane half 0) or entropy term (lane half 1) row of this (sequence, layer)
+};
+
+// the partial sums `ab` of subtile `up` are complete in every wavefront: hand them to wavefront up % 4 ...
+__device__ __forceinline__ void layer_give(const LayerCtx &c, int up, const float (&ab)[16])
+{
+    const int fin = up & 3;
+    if (c.wave != fin) xch_write(c.xch_lds + (uint32_t)(((up & 1) * 3 + ((c.wave - fin - 1) & 3)) * XCH_BYTES + c.lane * 16), ab);
+}
+// ... which, after the barrier, adds them up and stores the two results of its key
+__device__ __forceinline__ void layer_take(const LayerCtx &c, int up, float (&ab)[16])
+{
+    if (c.wave != (up & 3)) return;
+    xch_add(c.xch_lds + (uint32_t)((up & 1) * 3 * XCH_BYTES + c.lane * 16), ab);
+    const float v = columns_finish(ab, c.eps, c.hf);
+    const int t = c.lo + up * SUB + c.n;
+    if (t < c.L) c.out[t] = v;
+}
+
+// One subtile u: tiles 0-3 (KV head 2w) then 4-7 (KV head 2w+1), rotating through two accumulators; tile 7 of the
+// previous subtile is exponentiated first, which completes that subtile's partial sums (handed over mid-way).
+template <bool EDGE>
+__device__ __forceinline__ void layer_body(const LayerCtx &c, const bf16x8 (&qa)[8][8], const PairStream &ps, const float *cm,
+                                           floatx16 (&acc)[2], float (&ab)[16], int u)
+{
+    const int t_cur = c.lo + u * SUB + c.n, t_prev = t_cur - SUB;
+    bf16x8 kb[8];
+    ps.fetch(2 * u, kb);
+    acc[0] = chain<0, 8>(qa[0], kb, load_c64(cm, 0, c.hf));
+    columns_head<EDGE, false>(acc[1], ab, c.c1, t_prev, c.hf, c.T, c.L);
+    float abp[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) abp[i] = ab[i];
+    if (u > 0) layer_give(c, u - 1, abp);
+    acc[1] = chain<0, 8>(qa[1], kb, load_c64(cm, 1, c.hf));
+    columns_head<EDGE, true>(acc[0], ab, c.c1, t_cur, c.hf, c.T, c.L);
+    acc[0] = chain<0, 8>(qa[2], kb, load_c64(cm, 2, c.hf));
+    columns_head<EDGE, false>(acc[1], ab, c.c1, t_cur, c.hf, c.T, c.L);
+    acc[1] = chain<0, 8>(qa[3], kb, load_c64(cm, 3, c.hf));
+    columns_head<EDGE, false>(acc[0], ab, c.c1, t_cur, c.hf, c.T, c.L);
+    ps.fetch(2 * u + 1, kb);
+    acc[0] = chain<0, 8>(qa[4], kb, load_c64(cm, 4, c.hf));
+    columns_head<EDGE, false>(acc[1], ab, c.c1, t_cur, c.hf, c.T, c.L);
+    if (u > 0) {                                               // u is uniform over the workgroup
+        lds_barrier();
+        layer_take(c, u - 1, abp);
+    }
+    acc[1] = chain<0, 8>(qa[5], kb, load_c64(cm, 5, c.hf));
+    columns_head<EDGE, false>(acc[0], ab, c.c1, t_cur, c.hf, c.T, c.L);
+    acc[0] = chain<0, 8>(qa[6], kb, load_c64(cm, 6, c.hf));
+    columns_head<EDGE, false>(acc[1], ab, c.c1, t_cur, c.hf, c.T, c.L);
+    acc[1] = chain<0, 8>(qa[7], kb, load_c64(cm, 7, c.hf));
+    columns_head<EDGE, false>(acc[0], ab, c.c1, t_cur, c.hf, c.T, c.L);
+}
+
+__global__ void __launch_bounds__(WAVES * 64)
+score_mfma_columns_layer(ScoreArgs a)
+{
+    extern __shared__ __attribute__((aligned(8192))) char lds[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Dims &d = a.d;
+    char *ring = lds + wave * RING_BYTES;
+    char *xch = lds + WAVES * RING_BYTES;                                     // [2 buffers][3 slots][4][64 lanes][4]
+    float *cmat = reinterpret_cast<float *>(xch + 2 * 3 * XCH_BYTES);         // [wave][8 tiles][2 halves][16] C operands
+    const int sl = blockIdx.x / a.n_chunks, chunk = blockIdx.x - sl * a.n_chunks;
+    const int p_first = sl * LAYER_KV;                                        // the layer's first problem
+    const int lo = chunk * a.chunk_len, hi = min(lo + a.chunk_len, d.L);
+    const int n_sub = hi > lo ? (hi - lo + SUB - 1) / SUB : 0;                // the same for the four wavefronts
+
+    PairStream ps;
+    ps.init(a.k + k_problem_offset(d, p_first + 2 * wave), a.k + k_problem_offset(d, p_first + 2 * wave + 1), d.ks[3], ring, lo,
+            n_sub, d.L, lane);
+    ps.prime();
+
+    // C operands: minus (row log-sum-exp + log2 of the number of heads) / c1, so that exp2(c1 * acc) = A / H.
+    // Row R = kv * 128 + h * 32 + query; four rows per thread.
+    {
+        const float inv_c1 = 1.0f / a.c1, log2_heads = __builtin_amdgcn_logf((float)(d.G * LAYER_KV));
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) {
+            const int R = threadIdx.x + 256 * k4, kv = R >> 7, row = R & (M_ROWS - 1);
+            float m = -INFINITY, zz = 0.f;
+            if (a.lse) {
+                m = a.lse[(int64_t)(p_first + kv) * M_ROWS + row] * LOG2E;
+                zz = 1.f;
+            } else {
+                const float *pp = a.merged + ((int64_t)(p_first + kv) * a.pc * M_ROWS + row) * 2;
+                for (int c = 0; c < a.pc; ++c) {
+                    const float2 e = *reinterpret_cast<const float2 *>(pp + (int64_t)c * M_ROWS * 2);
+                    if (e.y > 0.f) {
+                        const float mn = fmaxf(m, e.x);
+                        zz = zz * __builtin_amdgcn_exp2f(m - mn) + e.y * __builtin_amdgcn_exp2f(e.x - mn);
+                        m = mn;
+                    }
+                }
+            }
+            const int qy = row & 31, j = (kv & 1) * 4 + (row >> 5);
+            const int hq = (qy >> 2) & 1, iq = ((qy >> 3) << 2) | (qy & 3);   // inverse of query_of
+            cmat[((kv >> 1) * 8 + j) * 32 + hq * 16 + iq] = -(m + __builtin_amdgcn_logf(zz) + log2_heads) * inv_c1;
+        }
+    }
+    __syncthreads();
+
+    LayerCtx c;
+    c.xch_lds = __builtin_amdgcn_readfirstlane(lds_addr(xch));
+    c.wave = wave; c.lane = lane; c.n = lane & 31; c.hf = lane >> 5;
+    c.lo = lo; c.c1 = a.c1; c.eps = a.eps; c.T = d.T; c.L = d.L;
+    c.out = (c.hf == 0 ? a.s_out : a.e_out) + (int64_t)sl * d.L;
+    const float *cm = cmat + wave * 8 * 32;
+
+    bf16x8 qa[8][8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint16_t *row = a.q + q_row_offset(d, p_first + 2 * wave + j / 4, j % 4, c.n);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) qa[j][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + c.hf) * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qa[j][s]));       // all 256 accumulation registers
+
+    floatx16 acc[2];
+    float ab[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc[0][i] = acc[1][i] = -INFINITY; ab[i] = 0.f; }
+
+    const int n_plain = lo + SUB <= d.T ? min(n_sub, (d.T - SUB - lo) / SUB + 1) : 0;
+    int u = 0;
+    for (; u < n_plain; ++u) layer_body<false>(c, qa, ps, cm, acc, ab, u);
+    for (; u < n_sub; ++u) layer_body<true>(c, qa, ps, cm, acc, ab, u);
+    if (n_sub > 0) {                                           // tile 7 of the last subtile, then its hand-over
+        columns_head<true, false>(acc[1], ab, c.c1, lo + (n_sub - 1) * SUB + c.n, c.hf, c.T, c.L);
+        layer_give(c, n_sub - 1, ab);
+        lds_barrier();
+        layer_take(c, n_sub - 1, ab);
+    }
+}
+
 // ------------------------------------------------------------------ other head / window shapes
 // G * W = 32, 64 or 128 rows in one to four 32-row tiles, row = head * W + window query.  For W < 32 a tile holds
 // several heads, so the head mean adds REGISTERS of one accumulator (register i of lane half hf is row
@@ -1271,10 +1502,14 @@ bool score_all_heads_supported(const Dims &d)
     return d.dtype == SABLOCK_BF16 && d.D == 128 && ((d.G == 4 && d.W == 32) || small_shape(d));
 }
 
+// the shape whose layers one workgroup can sum in registers and LDS (score_mfma_columns_layer)
+static bool layer_kernel_shape(const Dims &d) { return d.G == 4 && d.W == 32 && d.Hkv == LAYER_KV; }
+
 size_t score_all_heads_ws_bytes(const Dims &d)
 {
     const Plan pl = make_plan(d);
-    return partial_bytes(d, pl) + merged_bytes(d) + align256((size_t)d.P * d.L * d.W * 4);
+    const size_t abar = layer_kernel_shape(d) ? 0 : align256((size_t)d.P * d.L * d.W * 4);
+    return partial_bytes(d, pl) + merged_bytes(d) + abar;
 }
 
 hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
@@ -1289,12 +1524,45 @@ hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, c
     a.nv = 1;
     a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
     a.eps = eps;
+    a.lse = row_lse;
+    a.p0 = 0;
+    a.abar = nullptr;
+    dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
+    if (layer_kernel_shape(d)) {
+        static bool attr_done = false;
+        if (!attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, P1_LDS);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_layer),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, PL_LDS);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        a.s_out = s_out;
+        a.e_out = ent_out;
+        if (!row_lse) {
+            hipLaunchKernelGGL(score_mfma_stats, grid, dim3(WAVES * 64), P1_LDS, st, a);
+            launch_merge(a, d.P, M_ROWS, st);
+        }
+        // pass 2 has its own decomposition: a workgroup walks a chunk of keys through all 8 KV heads of a layer,
+        // again in whole rounds of one workgroup per CU
+        constexpr int MAX_LAYER_CHUNK = 32768;
+        const int64_t n_sl = (int64_t)d.n_seq * d.n_layers, cus = compute_units();
+        const int64_t rounds = (n_sl * d.L + cus * MAX_LAYER_CHUNK - 1) / (cus * MAX_LAYER_CHUNK);
+        const int64_t per_layer = std::max<int64_t>(1, (cus * rounds + n_sl / 2) / n_sl);
+        int len = (int)(((d.L + per_layer - 1) / per_layer + SUB - 1) / SUB) * SUB;
+        len = std::min(std::max(len, SUB), MAX_LAYER_CHUNK);
+        ScoreArgs a2 = a;
+        a2.chunk_len = len;
+        a2.n_chunks = (d.L + len - 1) / len;
+        hipLaunchKernelGGL(score_mfma_columns_layer, dim3((unsigned)(n_sl * a2.n_chunks)), dim3(WAVES * 64), PL_LDS, st, a2);
+        return hipGetLastError();
+    }
+    // other shapes: every KV head's head-group means go to memory, a second kernel averages them over the KV heads
     a.s_out = nullptr;
     a.e_out = nullptr;
     a.abar = reinterpret_cast<float *>(static_cast<char *>(ws) + partial_bytes(d, pl) + merged_bytes(d));
-    a.lse = row_lse;
-    a.p0 = 0;
-    dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
     hipError_t e = hipErrorInvalidValue;
 #define X(GV, WV) if (d.G == GV && d.W == WV) e = launch_score_g<GV, WV, true>(a, grid, !row_lse, st);
     SABLOCK_SMALL_SHAPES(X)

@@ -634,15 +634,18 @@ def test_decode_attention_128k_full_and_compacted(oracle, torch_cuda):
         np.testing.assert_allclose(out_c[0, l, h * w.G:(h + 1) * w.G], ref, rtol=2e-4, atol=2e-5)
 
 
-@pytest.mark.parametrize("G,W", [(4, 32), (4, 8), (2, 32)])
-def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, monkeypatch, G, W):
+@pytest.mark.parametrize("G,W,Hkv", [(4, 32, 8), (4, 32, 3), (4, 8, 3), (2, 32, 3)])
+def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, monkeypatch, G, W, Hkv):
     # Eq. barA taken literally: one score row and one retained set per (sequence, layer).  Scores against the
-    # oracle's all-head mean; refine / search / select stage-wise on the per-layer rows; shared compaction
+    # oracle's all-head mean; refine / search / select stage-wise on the per-layer rows; shared compaction.
+    # 8 KV heads with G = 4, W = 32 run the kernel that sums a layer's heads on chip (many short chunks here,
+    # the last one ragged), the other shapes the one that averages stored head-group means.
     torch = torch_cuda
     from paper_2510_22556_amd import binding as B
+    from scipy.special import logsumexp
 
     monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "2048")
-    Hkv, D, nl, ns = 3, 128, 2, 1
+    D, nl, ns = 128, 2, 1
     L = 2 * 2048 + 300 + W
     T = L - W
     q = synth.normal_torch(606 + W, 1, (ns, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
@@ -690,3 +693,16 @@ def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, monkeypatch, G,
             np.testing.assert_array_equal(H.to_np(vo[l * Hkv + h]), ve)
     # the per-layer retained set differs from what a single KV head would keep
     assert (H.to_np(buf.block_size) > 1).any()
+    # the caller's row log-sum-exp instead of the first pass
+    s0, e0 = H.to_np(buf.s).copy(), H.to_np(buf.ent).copy()
+    lse = np.zeros((ns, nl, G * Hkv, W), dtype=np.float32)
+    for l in range(nl):
+        qn, kn = H.widen(H.to_np(q[0, l])), H.widen(H.to_np(k[0, l]))
+        for h in range(G * Hkv):
+            x = qn[h] @ kn[h // G].T / np.sqrt(D)
+            for i in range(W):
+                lse[0, l, h, i] = logsumexp(x[i, :T + i + 1])
+    B.sablock_score_all_heads(shape, q, k, buf.s, buf.ent, ws, eps, row_lse=torch.as_tensor(lse).cuda())
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(H.to_np(buf.s), s0, rtol=2e-5, atol=1e-9)
+    np.testing.assert_allclose(H.to_np(buf.ent), e0, rtol=2e-5, atol=1e-6)
