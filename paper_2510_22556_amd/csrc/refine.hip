@@ -51,17 +51,21 @@ refine_kernel(Dims d, const float *s, const float *ent, SegView sv, sablock_hpar
     const int lo = sv.seg_off[base + k0], hi = sv.seg_off[base + k1];
     const bool staged = hi - lo <= RCAP;
     if (staged) {
+        // only as many rounds of loads as the range has tokens (uniform over the workgroup), all in flight together
+        const int nj = (hi - lo + NT - 1) / NT;
         float rs[RPT], re[RPT];
 #pragma unroll
         for (int j = 0; j < RPT; ++j) {
-            const int t = min(lo + j * NT + (int)threadIdx.x, hi - 1);
-            rs[j] = sp[t];
-            re[j] = ep[t];
+            if (j < nj) {
+                const int t = min(lo + j * NT + (int)threadIdx.x, hi - 1);
+                rs[j] = sp[t];
+                re[j] = ep[t];
+            }
         }
 #pragma unroll
         for (int j = 0; j < RPT; ++j) {
             const int i = j * NT + (int)threadIdx.x;
-            if (lo + i < hi) { sh_s[i] = rs[j]; sh_e[i] = re[j]; }
+            if (j < nj && lo + i < hi) { sh_s[i] = rs[j]; sh_e[i] = re[j]; }
         }
         __syncthreads();
     }
