@@ -706,3 +706,45 @@ def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, monkeypatch, G,
     torch.cuda.synchronize()
     np.testing.assert_allclose(H.to_np(buf.s), s0, rtol=2e-5, atol=1e-9)
     np.testing.assert_allclose(H.to_np(buf.ent), e0, rtol=2e-5, atol=1e-6)
+
+
+def test_whole_path_replays_in_a_hip_graph(torch_cuda):
+    # The five calls enqueue kernels only (no allocation, no synchronisation, no memset node), so a caller may
+    # capture them in a HIP graph.  Several replays, with eager work and synchronisations between them and the
+    # outputs cleared before each, must all reproduce the eager run bit for bit.
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    w = synth.WORKLOADS["llama8b_8k"]
+    q, k, v = synth.device_tensors(w, "cuda")
+    off, ptr = synth.workload_segments(w)
+    seg = B.make_segments(off, ptr, "cuda")
+    shape = B.make_shape(q, k, v)
+    budget = w.budget()
+    buf = B.Buffers(shape, seg, budget, "cuda", True)
+
+    def path():
+        B.compress(shape, q, k, v, seg, w.cand, budget, buf, w.eps, w.alpha, w.eta, w.tau)
+
+    outs = lambda: [buf.s, buf.ent, buf.s_tilde, buf.seg_budget, buf.block_size, buf.idx, buf.n_sel, buf.k_out, buf.v_out]
+    path()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in outs()]
+    assert int(buf.n_sel.min()) == budget
+    side = torch.cuda.Stream()                     # capture needs a non-default stream; first a warm-up run on it
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        path()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        path()
+    for rep in range(3):
+        for t in outs():
+            t.zero_()
+        (q.float().sum() + k.float().sum()).item()      # eager work and a synchronisation between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip("s ent s_tilde seg_budget block_size idx n_sel k_out v_out".split(), eager, outs()):
+            assert torch.equal(a, b), f"replay {rep}: {name} differs from the eager run"
