@@ -748,3 +748,43 @@ def test_whole_path_replays_in_a_hip_graph(torch_cuda):
         torch.cuda.synchronize()
         for name, a, b in zip("s ent s_tilde seg_budget block_size idx n_sel k_out v_out".split(), eager, outs()):
             assert torch.equal(a, b), f"replay {rep}: {name} differs from the eager run"
+
+
+def test_maximum_problem_count_per_call(oracle, torch_cuda):
+    # 65 535 problems in one call (the documented limit): 13 107 layers x 5 KV heads of a tiny fp32 shape.  Sampled
+    # problems at both ends and in the middle against the oracle; invariants on every problem.
+    torch = torch_cuda
+    ns, nl, Hkv, G, D, W, L = 1, 13107, 5, 2, 8, 4, 44
+    T = L - W
+    q = synth.normal_torch(911, 1, (ns, nl, G * Hkv, W, D), "cuda", torch.float32)
+    k = synth.normal_torch(911, 2, (ns, nl, Hkv, L, D), "cuda", torch.float32)
+    v = synth.normal_torch(911, 3, (ns, nl, Hkv, L, D), "cuda", torch.float32)
+    off = synth.segment_offsets(911, T, mean=6.0, min_len=1, max_len=16)
+    ptr = [0, len(off)]
+    w = synth.Workload("max_p", 0, ns, nl, G * Hkv, Hkv, D, L, W, "f32", (1, 2, 4), (12 + W,), (6.0,))
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget())
+    P = ns * nl * Hkv
+    assert P == 65535 and run.s.shape == (P, L)
+    assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
+    assert (run.n_sel == w.budget()).all() and (run.b.sum(axis=1) == w.budget()).all()
+    assert (np.diff(run.idx, axis=1) > 0).all() and run.idx.min() >= 0 and run.idx.max() < T
+    _check_all(oracle, w, run, q, k, v, off, ptr, [0, 1, 32767, 32768, 65533, 65534])
+
+
+def test_one_million_token_context(oracle, torch_cuda):
+    # one sequence of 2^20 tokens (Llama head shape, bf16, 2 KV heads): 16 K segments, far beyond the on-chip lists
+    # of the selection kernels; one problem against the oracle end to end, invariants on both
+    torch = torch_cuda
+    ns, nl, Hkv, G, D, W, L = 1, 1, 2, 4, 128, 32, 1 << 20
+    T = L - W
+    q = synth.normal_torch(912, 1, (ns, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(912, 2, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(912, 3, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    off = synth.segment_offsets(912, T, mean=64.0, min_len=2, max_len=512)
+    ptr = [0, len(off)]
+    w = synth.Workload("one_million", 0, ns, nl, G * Hkv, Hkv, D, L, W, "bf16", (1, 2, 4, 8, 16, 32, 64), (4096,), (64.0,))
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget())
+    assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
+    assert (run.n_sel == w.budget()).all() and (run.b.sum(axis=1) == w.budget()).all()
+    assert (np.diff(run.idx, axis=1) > 0).all() and run.idx.min() >= 0 and run.idx.max() < T
+    _check_all(oracle, w, run, q, k, v, off, ptr, [1])
