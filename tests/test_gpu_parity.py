@@ -788,3 +788,37 @@ def test_one_million_token_context(oracle, torch_cuda):
     assert (run.n_sel == w.budget()).all() and (run.b.sum(axis=1) == w.budget()).all()
     assert (np.diff(run.idx, axis=1) > 0).all() and run.idx.min() >= 0 and run.idx.max() < T
     _check_all(oracle, w, run, q, k, v, off, ptr, [1])
+
+
+def test_ablation_switches_as_degenerate_configurations(oracle, torch_cuda):
+    # The paper's ablations (Sec. 4.4) are settings of the same path: token-level eviction (candidates {1}), a fixed
+    # block size (candidates {1, g} with tau = 0, so g is taken wherever it fits), no segment-guided scoring
+    # (alpha = 0).  Each against the oracle, plus what defines it.
+    import dataclasses
+
+    torch = torch_cuda
+    w = synth.WORKLOADS["llama8b_8k"]
+    q, k, v, off, ptr = _device_workload(torch, w)
+    B_ = w.budget()
+    # token level: the retained set is the plain Top-B of the refined scores (value descending, index ascending)
+    w1 = dataclasses.replace(w, cand=(1,))
+    run = H.GpuRun(q, k, v, off, ptr, w1.cand, B_, w.eps, w.alpha, w.eta, w.tau)
+    _check_all(oracle, w1, run, q, k, v, off, ptr, [0, 5])
+    for p in (0, 5):
+        order = np.lexsort((np.arange(w.T), -run.st[p].astype(np.float64)))
+        assert np.array_equal(run.idx[p], np.sort(order[:B_]))
+    assert set(np.unique(run.g)) <= {0, 1}
+    # fixed block size 4: every segment that can hold a block of 4 within its budget gets 4, the others 1
+    w4 = dataclasses.replace(w, cand=(1, 4), tau=0.0)
+    run = H.GpuRun(q, k, v, off, ptr, w4.cand, B_, w.eps, w.alpha, w.eta, 0.0)
+    _check_all(oracle, w4, run, q, k, v, off, ptr, [2, 7], tau=0.0)
+    seg_len = np.diff(off)
+    for p in (2, 7):
+        b = run.b[p][:len(seg_len)]
+        expect = np.where(b == 0, 0, np.where(np.minimum(seg_len, b) >= 4, 4, 1))
+        assert np.array_equal(run.g[p][:len(seg_len)], expect)
+    # no segment-guided scoring: the refined scores are the raw scores, bit for bit
+    w0 = dataclasses.replace(w, alpha=0.0)
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, B_, w.eps, 0.0, w.eta, w.tau)
+    _check_all(oracle, w0, run, q, k, v, off, ptr, [3])
+    assert np.array_equal(run.st, run.s[:, :w.T])
