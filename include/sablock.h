@@ -168,10 +168,11 @@ SABLOCK_API sablock_status sablock_compact(const sablock_shape *shape, const voi
  * The head mean taken literally (Eq. barA averages over ALL H query heads of a layer): ONE score row, hence one
  * retained set, per (sequence, layer) instead of one per KV head.
  *   sablock_score_all_heads   as sablock_score, but Abar[i, t] is the mean over all n_q_heads heads of the layer;
- *       s_out / ent_out are [n_seq * n_layers][L].  row_lse as in sablock_score.  The workspace
- *       (sablock_score_all_heads_workspace_bytes) holds the head-group means of every KV head, 4 * W bytes per key
- *       and KV head, before they are averaged.  Supported: bf16, head_dim 128, (G, W) in {(4, 32), (4, 8), (4, 16),
- *       (8, 8), (8, 16), (2, 32), (1, 32)}; otherwise UNSUPPORTED.
+ *       s_out / ent_out are [n_seq * n_layers][L].  row_lse as in sablock_score.  Supported: bf16, head_dim 128,
+ *       (G, W) in {(4, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)}; otherwise UNSUPPORTED.  With 8 KV
+ *       heads, G = 4 and W = 32 the heads of a layer are summed on chip and the workspace
+ *       (sablock_score_all_heads_workspace_bytes) holds row statistics only; for the other shapes it also holds
+ *       the head-group means of every KV head, 4 * W bytes per key and KV head, before they are averaged.
  *   refine / search_blocks / select then run on the per-layer rows: pass them a shape whose n_q_heads and
  *       n_kv_heads are 1 (a problem is then a (sequence, layer)).
  *   sablock_compact_shared    as sablock_compact with the real head counts, but idx is [n_seq * n_layers][budget]
