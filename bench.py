@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the SABlock compression hot path on one MI355X.
 
-A step is one pass of the whole path (score, refine, search_blocks, select,
-compact: five C-ABI calls) over every layer of one synthetic workload whose
+A step is one pass of the whole path (score, refine, search_blocks + select in
+their one-call form, compact: four C-ABI calls) over every layer of one synthetic workload whose
 Q/K/V already sit in HBM.  Prints ONE JSON line:
   value     tokens/s per layer = n_seq * L * n_layers / step time
   roofline  the scoring step (the kernels that stream K): algorithmic bytes per
@@ -143,7 +143,7 @@ def main():
             dst.copy_(src)          # elementwise copy kernel: reads and writes calibrate_copy MiB each
         torch.cuda.synchronize()
         del src, dst
-    names = ["score", "refine", "search", "select", "compact"]
+    names = ["score", "refine", "search_select", "compact"]
 
     def step(events=None, score_only_events=None):
         def mark(i):
@@ -158,14 +158,11 @@ def main():
         mark(1)
         B.sablock_refine(shape, buf.s, buf.ent, seg, buf.s_tilde, buf.ws, w.alpha, w.eta, buf.omega)
         mark(2)
-        B.sablock_search_blocks(shape, buf.s_tilde, seg, w.cand, budget, w.tau, buf.seg_budget, buf.block_size, buf.ws,
-                                topb_out=buf.topb)
+        B.sablock_search_select(shape, buf.s_tilde, seg, w.cand, budget, w.tau, buf.seg_budget, buf.block_size,
+                                buf.idx, buf.n_sel, buf.ws, topb_out=buf.topb)
         mark(3)
-        B.sablock_select(shape, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws,
-                         topb=buf.topb)
-        mark(4)
         B.sablock_compact(shape, k, v, buf.idx, buf.n_sel, budget, True, buf.k_out, buf.v_out)
-        mark(5)
+        mark(4)
 
     for _ in range(args.warmup):
         step()
@@ -182,7 +179,7 @@ def main():
     score_ms = sum(e[0].elapsed_time(e[1]) for e in sev) / args.steps
     # per-stage breakdown from a second, untimed loop with an event after every call (the extra events cost a
     # few per cent, so they stay out of the timed region)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     for i in range(args.steps):
         step(evs[i])
     torch.cuda.synchronize()
@@ -213,7 +210,7 @@ def main():
     if args.headline_only:
         print(json.dumps(result))
         return
-    # the same work issued layer by layer, the way a prefill loop would call it: n_layers x 5 calls on per-layer
+    # the same work issued layer by layer, the way a prefill loop would call it: n_layers x 4 calls on per-layer
     # views (outputs of all layers land in one per-layer set of buffers, which is enough for timing)
     if w.n_layers > 1:
         shape_l = B.make_shape(q[:, :1], k[:, :1], v[:, :1])
@@ -224,10 +221,8 @@ def main():
                 ql, kl, vl = q[:, l:l + 1], k[:, l:l + 1], v[:, l:l + 1]
                 B.sablock_score(shape_l, ql, kl, buf_l.s, buf_l.ent, buf_l.ws, w.eps)
                 B.sablock_refine(shape_l, buf_l.s, buf_l.ent, seg, buf_l.s_tilde, buf_l.ws, w.alpha, w.eta, buf_l.omega)
-                B.sablock_search_blocks(shape_l, buf_l.s_tilde, seg, w.cand, budget, w.tau, buf_l.seg_budget,
-                                        buf_l.block_size, buf_l.ws, topb_out=buf_l.topb)
-                B.sablock_select(shape_l, buf_l.s_tilde, seg, buf_l.seg_budget, buf_l.block_size, budget, buf_l.idx,
-                                 buf_l.n_sel, buf_l.ws, topb=buf_l.topb)
+                B.sablock_search_select(shape_l, buf_l.s_tilde, seg, w.cand, budget, w.tau, buf_l.seg_budget,
+                                        buf_l.block_size, buf_l.idx, buf_l.n_sel, buf_l.ws, topb_out=buf_l.topb)
                 B.sablock_compact(shape_l, kl, vl, buf_l.idx, buf_l.n_sel, budget, True, buf_l.k_out, buf_l.v_out)
 
         layer_calls()
@@ -332,10 +327,8 @@ def main():
             if score_events is not None:
                 score_events[1].record()
             B.sablock_refine(shape, buf.s, buf.ent, seg, buf.s_tilde, buf.ws, w.alpha, w.eta, buf.omega)
-            B.sablock_search_blocks(shape, buf.s_tilde, seg, w.cand, budget, w.tau, buf.seg_budget, buf.block_size,
-                                    buf.ws, topb_out=buf.topb)
-            B.sablock_select(shape, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel,
-                             buf.ws, topb=buf.topb)
+            B.sablock_search_select(shape, buf.s_tilde, seg, w.cand, budget, w.tau, buf.seg_budget, buf.block_size,
+                                    buf.idx, buf.n_sel, buf.ws, topb_out=buf.topb)
             B.sablock_compact(shape, k, v, buf.idx, buf.n_sel, budget, True, buf.k_out, buf.v_out)
 
         for _ in range(args.warmup):

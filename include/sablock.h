@@ -156,6 +156,21 @@ SABLOCK_API sablock_status sablock_select(const sablock_shape *shape, const floa
                               int32_t *idx_out, int32_t *n_sel_out,
                               void *ws, size_t ws_bytes, void *stream);
 
+/* Search and selection in one call: the outputs of sablock_search_blocks and of sablock_select for the same
+ * arguments, bit for bit (Alg. 2 as a whole).  When 0 < budget < T, budget <= 4096 and every sequence has fewer
+ * than 4095 segments, the Top-B kernel also lays out the output rows and the search writes the selected tokens
+ * itself, which saves the selection's own passes; otherwise the two sequences simply run one after the other.
+ * Workspace: sablock_workspace_bytes covers it. */
+SABLOCK_API sablock_status sablock_search_select(const sablock_shape *shape, const float *s_tilde,
+                                     const int32_t *seg_off, const int32_t *seg_ptr /* host */,
+                                     int32_t max_segments,
+                                     const int32_t *cand /* host */, int32_t n_cand,
+                                     int32_t budget, float tau,
+                                     int32_t *seg_budget_out, int32_t *block_size_out,
+                                     int32_t *topb_out /* nullable */,
+                                     int32_t *idx_out, int32_t *n_sel_out,
+                                     void *ws, size_t ws_bytes, void *stream);
+
 /* Cache construction (end of Sec. 3.3): per problem, rows idx[0..n_sel) of K and V copied
  * bit for bit, rows n_sel..budget-1 zero-filled, then, if append_window, the W most
  * recent rows T..L-1 in order.  k, v: shape->dtype, laid out by k_stride / v_stride.

@@ -25,7 +25,7 @@ EXPORTS = ("sablock_version", "sablock_last_error", "sablock_workspace_bytes", "
            "sablock_refine", "sablock_search_blocks", "sablock_select", "sablock_compact",
            "sablock_segment_count", "sablock_segment_offsets", "sablock_decode_workspace_bytes",
            "sablock_decode_attention", "sablock_score_all_heads_workspace_bytes", "sablock_score_all_heads",
-           "sablock_compact_shared")
+           "sablock_compact_shared", "sablock_search_select")
 
 
 class SablockError(RuntimeError):
@@ -67,6 +67,8 @@ def load():
         lib.sablock_select.argtypes = [sp, vp, vp, ctypes.POINTER(i32), i32, vp, vp, vp, i32, vp, vp, vp,
                                        ctypes.c_size_t, vp]
         lib.sablock_compact.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        lib.sablock_search_select.argtypes = [sp, vp, vp, ctypes.POINTER(i32), i32, ctypes.POINTER(i32), i32, i32, f32,
+                                              vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.sablock_segment_count.argtypes = [vp, ctypes.c_int64, i32, i32, ctypes.POINTER(i32), i32, vp, vp]
         lib.sablock_segment_offsets.argtypes = [vp, ctypes.c_int64, i32, i32, ctypes.POINTER(i32), i32,
                                                 ctypes.POINTER(i32), vp, vp]
@@ -175,6 +177,15 @@ def sablock_select(shape: CShape, s_tilde, seg: Segments, seg_budget, block_size
                                  seg.max_segments, _ptr(seg_budget), _ptr(block_size), _ptr(topb), budget,
                                  _ptr(idx_out), _ptr(n_sel_out), _ptr(ws), ws.numel() * ws.element_size(),
                                  _stream(stream)))
+
+
+def sablock_search_select(shape: CShape, s_tilde, seg: Segments, cand: Sequence[int], budget: int, tau: float,
+                          seg_budget_out, block_size_out, idx_out, n_sel_out, ws, stream=None, topb_out=None):
+    c = (ctypes.c_int32 * len(cand))(*[int(x) for x in cand])
+    _check(load().sablock_search_select(ctypes.byref(shape), _ptr(s_tilde), _ptr(seg.seg_off), seg.c_ptr(),
+                                        seg.max_segments, c, len(cand), budget, tau, _ptr(seg_budget_out),
+                                        _ptr(block_size_out), _ptr(topb_out), _ptr(idx_out), _ptr(n_sel_out),
+                                        _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def sablock_compact(shape: CShape, k, v, idx, n_sel, budget: int, append_window: bool, k_out, v_out,
@@ -301,13 +312,18 @@ class Buffers:
 
 
 def compress(shape: CShape, q, k, v, seg: Segments, cand: Sequence[int], budget: int, buf: Buffers,
-             eps=1e-6, alpha=0.9, eta=1.0, tau=0.85, row_lse=None, stream=None) -> Buffers:
-    """The whole hot path: score, refine, search_blocks, select, compact (five ABI calls, in order)."""
+             eps=1e-6, alpha=0.9, eta=1.0, tau=0.85, row_lse=None, stream=None, fused=True) -> Buffers:
+    """The whole hot path: score, refine, search_blocks + select (one call for both, or the two separate calls with
+    ``fused=False``: same results), compact."""
     sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, eps, row_lse, stream)
     sablock_refine(shape, buf.s, buf.ent, seg, buf.s_tilde, buf.ws, alpha, eta, buf.omega, stream)
-    sablock_search_blocks(shape, buf.s_tilde, seg, cand, budget, tau, buf.seg_budget, buf.block_size, buf.ws, stream,
-                          topb_out=buf.topb)
-    sablock_select(shape, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws, stream,
-                   topb=buf.topb)
+    if fused:
+        sablock_search_select(shape, buf.s_tilde, seg, cand, budget, tau, buf.seg_budget, buf.block_size, buf.idx,
+                              buf.n_sel, buf.ws, stream, topb_out=buf.topb)
+    else:
+        sablock_search_blocks(shape, buf.s_tilde, seg, cand, budget, tau, buf.seg_budget, buf.block_size, buf.ws,
+                              stream, topb_out=buf.topb)
+        sablock_select(shape, buf.s_tilde, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws,
+                       stream, topb=buf.topb)
     sablock_compact(shape, k, v, buf.idx, buf.n_sel, budget, buf.append_window, buf.k_out, buf.v_out, stream)
     return buf

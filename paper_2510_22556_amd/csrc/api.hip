@@ -149,6 +149,21 @@ sablock_status sablock_refine(const sablock_shape *shape, const float *s, const 
                "sablock_refine");
 }
 
+// candidate block sizes: 1 = cand[0] < cand[1] < ... <= 64
+static sablock_status make_candlist(const char *who, const int32_t *cand, int32_t n_cand, CandList *cl)
+{
+    if (n_cand < 1 || n_cand > MAX_CAND) return fail(SABLOCK_ERR_INVALID_ARG, "%s: n_cand must be in [1, %d]", who, MAX_CAND);
+    if (cand[0] != 1) return fail(SABLOCK_ERR_INVALID_ARG, "%s: cand[0] must be 1", who);
+    memset(cl, 0, sizeof(*cl));
+    cl->n = n_cand;
+    for (int c = 0; c < n_cand; ++c) {
+        if (c && cand[c] <= cand[c - 1]) return fail(SABLOCK_ERR_INVALID_ARG, "%s: cand must be strictly ascending", who);
+        if (cand[c] > 64) return fail(SABLOCK_ERR_UNSUPPORTED, "%s: block size %d > 64", who, cand[c]);
+        cl->g[c] = cand[c];
+    }
+    return SABLOCK_OK;
+}
+
 sablock_status sablock_search_blocks(const sablock_shape *shape, const float *s_tilde,
                                      const int32_t *seg_off, const int32_t *seg_ptr, int32_t max_segments,
                                      const int32_t *cand, int32_t n_cand, int32_t budget, float tau,
@@ -162,16 +177,9 @@ sablock_status sablock_search_blocks(const sablock_shape *shape, const float *s_
         return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: NULL argument");
     if (budget < 0) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: budget < 0");
     if (!(tau >= 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: tau must be >= 0");
-    if (n_cand < 1 || n_cand > MAX_CAND) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: n_cand must be in [1, %d]", MAX_CAND);
-    if (cand[0] != 1) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: cand[0] must be 1");
     CandList cl;
-    memset(&cl, 0, sizeof(cl));
-    cl.n = n_cand;
-    for (int c = 0; c < n_cand; ++c) {
-        if (c && cand[c] <= cand[c - 1]) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_blocks: cand must be strictly ascending");
-        if (cand[c] > 64) return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_search_blocks: block size %d > 64", cand[c]);
-        cl.g[c] = cand[c];
-    }
+    st = make_candlist("sablock_search_blocks", cand, n_cand, &cl);
+    if (st != SABLOCK_OK) return st;
     SegView sv;
     st = make_segview(d, seg_off, seg_ptr, max_segments, &sv);
     if (st != SABLOCK_OK) return st;
@@ -203,6 +211,32 @@ sablock_status sablock_select(const sablock_shape *shape, const float *s_tilde,
         return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_select: workspace %zu < %zu bytes", ws_bytes, need);
     return dev(launch_select(d, s_tilde, sv, seg_budget, block_size, topb, budget, idx_out, n_sel_out, ws,
                              static_cast<hipStream_t>(stream)), "sablock_select");
+}
+
+sablock_status sablock_search_select(const sablock_shape *shape, const float *s_tilde,
+                                     const int32_t *seg_off, const int32_t *seg_ptr, int32_t max_segments,
+                                     const int32_t *cand, int32_t n_cand, int32_t budget, float tau,
+                                     int32_t *seg_budget_out, int32_t *block_size_out, int32_t *topb_out,
+                                     int32_t *idx_out, int32_t *n_sel_out, void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!s_tilde || !seg_budget_out || !block_size_out || !cand || !n_sel_out || (!idx_out && budget > 0))
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_select: NULL argument");
+    if (budget < 0) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_select: budget < 0");
+    if (!(tau >= 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_search_select: tau must be >= 0");
+    CandList cl;
+    st = make_candlist("sablock_search_select", cand, n_cand, &cl);
+    if (st != SABLOCK_OK) return st;
+    SegView sv;
+    st = make_segview(d, seg_off, seg_ptr, max_segments, &sv);
+    if (st != SABLOCK_OK) return st;
+    const size_t need = search_select_ws_bytes(d, max_segments, budget);
+    if (!ws || ws_bytes < need)
+        return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_search_select: workspace %zu < %zu bytes", ws_bytes, need);
+    return dev(launch_search_select(d, s_tilde, sv, cl, budget, tau, seg_budget_out, block_size_out, topb_out, idx_out,
+                                    n_sel_out, ws, static_cast<hipStream_t>(stream)), "sablock_search_select");
 }
 
 sablock_status sablock_compact(const sablock_shape *shape, const void *k, const void *v,

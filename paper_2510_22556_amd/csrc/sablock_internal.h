@@ -110,6 +110,15 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
                          const int32_t *block_size, const int32_t *topb, int32_t budget, int32_t *idx_out,
                          int32_t *n_sel_out, void *ws, hipStream_t st);
 
+// search and select in one sequence: same results as launch_search followed by launch_select; when the Top-B
+// tokens and the segment counters of a problem fit on chip (search_select_fused) the Top-B kernel also plans the
+// output rows and the search kernel writes the selected tokens, so no select kernel runs
+bool search_select_fused(const Dims &d, const SegView &sv, int32_t budget);
+size_t search_select_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget);
+hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
+                                int32_t budget, float tau, int32_t *seg_budget, int32_t *block_size, int32_t *topb_out,
+                                int32_t *idx_out, int32_t *n_sel_out, void *ws, hipStream_t st);
+
 hipError_t launch_compact(const Dims &d, const void *k, const void *v, const int32_t *idx,
                           const int32_t *n_sel, int32_t budget, int32_t append_window,
                           void *k_out, void *v_out, int32_t shared_rows, hipStream_t st);

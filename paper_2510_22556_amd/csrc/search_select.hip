@@ -38,7 +38,7 @@ struct __attribute__((aligned(32))) SegRec {
     int32_t bk;          // implicit budget b_k
     int32_t g;           // select: block size g_k*;  search: ordered key of the Top-B threshold
     int32_t pos;         // select: offset of the segment's tokens in the problem's idx_out row;  search: index cut
-    int32_t pad;
+    int32_t out;         // search that also selects: offset of the segment's tokens in the problem's idx_out row
 };
 
 // LDS slices of a search/select wavefront: tokens whose scores are staged, blocks whose Phi / class are kept.
@@ -160,9 +160,22 @@ __device__ inline void find_bin_from_top(const uint32_t *hist, int nbins, uint32
 // the remaining 20 bits are resolved without touching global memory again.  If the bin holds more candidates
 // than the list (or k exceeds the token list), three histogram passes over the row (11 + 11 + 10 bits) do it.
 // Ties at the threshold are cut by ascending index with one ordered pass over the row.
+//
+// PLAN (the search that also selects; the host launches it only when 0 < B < T, B <= TB_HITS and every sequence
+// has fewer than TB_OFFS segments, so the Top-B tokens and the segment counters are in LDS): the same workgroup
+// goes on to the exclusive prefix of b_k (each segment's offset in the problem's idx_out row), writes n_sel, the
+// single token of every segment with b_k == 1 (g_k* = 1) straight to its place, and appends the segments with
+// b_k >= 2 to the call's search lists with their output offset.  `counter` must then be zero on entry.
+struct PlanArgs {
+    SegRec *list, *list_long;
+    int capacity;
+    int32_t *idx_out, *n_sel_out;
+};
+
+template <bool PLAN>
 __global__ void __launch_bounds__(TB_THREADS)
 topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, int32_t *seg_budget,
-            int32_t *block_size, int32_t *counter)
+            int32_t *block_size, int32_t *counter, PlanArgs pa)
 {
     __shared__ uint32_t hist[TB_HITS];           // pass-A histogram (4096 bins), later the list of Top-B tokens
     __shared__ uint32_t hist2[2048];             // histograms of the later passes
@@ -183,7 +196,7 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
     const int64_t row = (int64_t)p * sv.max_segments;
     if (seg_budget) {
         for (int i = tid; i < sv.max_segments; i += TB_THREADS) { seg_budget[row + i] = 0; block_size[row + i] = 0; }
-        if (counter && p == 0 && tid < 2) counter[tid] = 0;
+        if (!PLAN && counter && p == 0 && tid < 2) counter[tid] = 0;
     }
 
     uint32_t prefix = 0, mask = 0, krem = (uint32_t)max(k, 0), n_eq = 0;
@@ -314,6 +327,61 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         for (int i = tid; i < sh_nhit; i += TB_THREADS) atomicAdd(&sh_cnt[segment_of(sh_off, K, sh_hit[i])], 1);
         __syncthreads();
         for (int j = tid; j < K; j += TB_THREADS) seg_budget[row + j] = sh_cnt[j];
+        if (PLAN) {
+            // exclusive prefix of the counters in place (K + 1 entries: b_k = pos[k + 1] - pos[k]); four
+            // consecutive entries per thread, wavefront scan, then the sixteen wavefront totals
+            __syncthreads();
+            const int j0 = 4 * tid;
+            int c[4], tot = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { c[i] = j0 + i < K ? sh_cnt[j0 + i] : 0; tot += c[i]; }
+            int incl = tot;
+            for (int o = 1; o < 64; o <<= 1) { const int x = __shfl_up(incl, o); if (lane >= o) incl += x; }
+            if (lane == 63) sh_wcnt[wave] = incl;
+            __syncthreads();
+            int run = incl - tot;
+            for (int w = 0; w < wave; ++w) run += sh_wcnt[w];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { if (j0 + i <= K) sh_cnt[j0 + i] = run; run += c[i]; }
+            __syncthreads();
+            int32_t *out = pa.idx_out + (int64_t)p * budget;
+            if (tid == 0) pa.n_sel_out[p] = k;                 // k = B < T here, so there is nothing to pad
+            // the token of every single-token segment goes straight to its place
+            for (int i = tid; i < sh_nhit; i += TB_THREADS) {
+                const int t = sh_hit[i], sg = segment_of(sh_off, K, t);
+                if (sh_cnt[sg + 1] - sh_cnt[sg] == 1) { out[sh_cnt[sg]] = t; block_size[row + sg] = 1; }
+            }
+            // the others to the search lists (as in heavy_list_kernel), with their output offset
+            const int32_t thr_key = (int32_t)prefix;
+            for (int c0 = 0; c0 < K; c0 += TB_THREADS) {
+                const int sg = c0 + tid;
+                const int bk = sg < K ? sh_cnt[sg + 1] - sh_cnt[sg] : 0;
+                const int a = sg < K ? sh_off[sg] : 0, b = sg < K ? sh_off[sg + 1] : 0;
+                const bool hv = bk >= 2 && b - a <= CAPT, hx = bk >= 2 && b - a > CAPT;
+                const unsigned long long bal = __ballot(hv), bax = __ballot(hx);
+                __syncthreads();                               // the previous round's sh_pair reads are done
+                if (lane == 0) { sh_wcnt[wave] = __popcll(bal) | (__popcll(bax) << 16); }
+                __syncthreads();
+                int before = 0, total = 0, before_x = 0, total_x = 0;
+                for (int w = 0; w < TB_THREADS / 64; ++w) {
+                    const int n0 = sh_wcnt[w] & 0xffff, n1 = sh_wcnt[w] >> 16;
+                    if (w < wave) { before += n0; before_x += n1; }
+                    total += n0; total_x += n1;
+                }
+                if (tid == 0 && total > 0) sh_pair[0] = (uint32_t)atomicAdd(&counter[0], total);
+                if (tid == 1 && total_x > 0) sh_pair[1] = (uint32_t)atomicAdd(&counter[1], total_x);
+                __syncthreads();
+                if (hv || hx) {
+                    const unsigned long long lt = (1ull << lane) - 1ull;
+                    const int pos = hv ? (int)sh_pair[0] + before + __popcll(bal & lt) : (int)sh_pair[1] + before_x + __popcll(bax & lt);
+                    if (pos < pa.capacity) {
+                        SegRec r;
+                        r.p = p; r.k = sg; r.a = a; r.b = b; r.bk = bk; r.g = thr_key; r.pos = cut; r.out = sh_cnt[sg];
+                        (hv ? pa.list : pa.list_long)[pos] = r;
+                    }
+                }
+            }
+        }
     } else if (have_hits) {
         for (int i = tid; i < sh_nhit; i += TB_THREADS) atomicAdd(&seg_budget[row + segment_of(off, K, sh_hit[i])], 1);
     } else {
@@ -521,7 +589,7 @@ heavy_list_kernel(Dims d, SegView sv, const int32_t *thr, const int32_t *seg_bud
             const int pos = hv ? sh_base[0] + before + __popcll(bal & lt) : sh_base[1] + before_x + __popcll(bax & lt);
             if (pos < capacity) {
                 SegRec r;
-                r.p = p; r.k = k; r.a = a; r.b = b; r.bk = bk; r.g = thr_key; r.pos = thr_cut; r.pad = 0;
+                r.p = p; r.k = k; r.a = a; r.b = b; r.bk = bk; r.g = thr_key; r.pos = thr_cut; r.out = 0;
                 (hv ? list : list_long)[pos] = r;
             }
         }
@@ -531,14 +599,17 @@ heavy_list_kernel(Dims d, SegView sv, const int32_t *thr, const int32_t *seg_bud
 // one wavefront per workgroup, striding over the call's search list
 constexpr int SEARCH_WGS = 65536;
 
-template <int CT, int CB>
+// EMIT: the wavefront also writes T_k(g_k*) in ascending order at the segment's offset in idx_out (the record's
+// `out`), so that no select pass over the segment is needed.
+template <int CT, int CB, bool EMIT>
 __global__ void __launch_bounds__(64)
 search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau,
-              const SegRec *list, const int32_t *counter, int capacity, int32_t *block_size)
+              const SegRec *list, const int32_t *counter, int capacity, int32_t *block_size, int budget, int32_t *idx_out)
 {
     __shared__ double sh_phi[CB];
     __shared__ float sh_val[CT];
     __shared__ uint8_t sh_cls[CB];
+    __shared__ unsigned long long sh_mask[EMIT ? CT / 64 : 1];   // the taken tokens of the candidate just tried
     const int lane = threadIdx.x;
     int j = blockIdx.x;                                     // < capacity: the grid is no larger than the list can get
     SegRec r = list[j];                                     // fetched together with the list length
@@ -576,8 +647,10 @@ search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau
             if (g > gcap) continue;
             if (g == 1) { gstar = 1; break; }               // token level: the unconditional last resort
             double score = 0.0;
-            segment_fill(val, a, b, g, bk, ws,
-                         [&](int, unsigned long long m, float v) { score = add_in_order(score, m, v); });
+            segment_fill(val, a, b, g, bk, ws, [&](int c0, unsigned long long m, float v) {
+                score = add_in_order(score, m, v);
+                if (EMIT && staged && lane == 0) sh_mask[(c0 - a) >> 6] = m;
+            });
             if (score >= need) { gstar = g; break; }        // Eq. gk_star: first accepted, largest first
         }
     };
@@ -585,6 +658,30 @@ search_kernel(Dims d, const float *s_tilde, SegView sv, CandList cand, float tau
     if (staged) run([lv, a](int t) { return lv[t - a]; });
     else run([sp](int t) { return sp[t]; });
     if (lane == 0) block_size[o] = gstar;
+    if (EMIT) {
+        int32_t *out = idx_out + (int64_t)p * budget;
+        int pos = r.out;
+        const unsigned long long lt = (1ull << lane) - 1ull;
+        auto put = [&](int c0, unsigned long long m, float) {
+            const int jo = pos + __popcll(m & lt);
+            if (((m >> lane) & 1ull) && jo < budget) out[jo] = c0 + lane;
+            pos += __popcll(m);
+        };
+        if (gstar == 1) {                                   // T_k(1) = T_topB & S_k (b_k is the implicit budget)
+            for (int c0 = a; c0 < b; c0 += 64) {
+                const int t = c0 + lane;
+                const float v = staged ? lv[min(t, b - 1) - a] : sp[min(t, b - 1)];
+                put(c0, __ballot(t < b && in_topb(v, t, thr_key, thr_cut)), 0.f);
+            }
+        } else if (gstar > 1) {
+            if (staged) {                                   // the accepted candidate was the last one tried
+                __builtin_amdgcn_wave_barrier();
+                for (int c0 = a; c0 < b; c0 += 64) put(c0, sh_mask[(c0 - a) >> 6], 0.f);
+            } else {
+                segment_fill([sp](int t) { return sp[t]; }, a, b, gstar, bk, ws, put);
+            }
+        }
+    }
     __builtin_amdgcn_wave_barrier();                        // the LDS slices are reused by the next segment
     }
 }
@@ -641,7 +738,7 @@ seg_prefix_kernel(Dims d, SegView sv, const int32_t *seg_budget, const int32_t *
                                      : sh_base[2] + before_x + __popcll(bx & lt);
             if (slot < capacity) {
                 SegRec r;
-                r.p = p; r.k = k; r.a = sa; r.b = sb; r.bk = v; r.g = g; r.pos = carry + before + incl - v; r.pad = 0;
+                r.p = p; r.k = k; r.a = sa; r.b = sb; r.bk = v; r.g = g; r.pos = carry + before + incl - v; r.out = 0;
                 (is_light ? light : is_full ? full : full_long)[slot] = r;
             }
         }
@@ -773,8 +870,8 @@ hipError_t launch_topb(const Dims &d, const float *s_tilde, int32_t budget, int3
 {
     if (d.P <= 0) return hipSuccess;
     SegView none{};
-    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, none,
-                       (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr);
+    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, none,
+                       (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, PlanArgs{});
     return hipGetLastError();
 }
 
@@ -808,16 +905,17 @@ hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv,
     SegRec *list = reinterpret_cast<SegRec *>(w);
     w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
     SegRec *list_long = reinterpret_cast<SegRec *>(w);
-    hipLaunchKernelGGL(topb_kernel, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, sv, seg_budget,
-                       block_size, counters);
+    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, sv, seg_budget,
+                       block_size, counters, PlanArgs{});
     if (budget > 0 && d.T > 0) {
         hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, thr, seg_budget, block_size,
                            list, list_long, counters, (int)cap);
         if (cap > 0) {
-            hipLaunchKernelGGL((search_kernel<CAPT, CAPB>), dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64),
-                               0, st, d, s_tilde, sv, cand, tau, list, counters, (int)cap, block_size);
-            hipLaunchKernelGGL((search_kernel<CAPT_LONG, CAPB_LONG>), dim3((unsigned)(cap < LONG_WGS ? cap : LONG_WGS)),
-                               dim3(64), 0, st, d, s_tilde, sv, cand, tau, list_long, counters + 1, (int)cap, block_size);
+            hipLaunchKernelGGL((search_kernel<CAPT, CAPB, false>), dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64),
+                               0, st, d, s_tilde, sv, cand, tau, list, counters, (int)cap, block_size, 0, (int32_t *)nullptr);
+            hipLaunchKernelGGL((search_kernel<CAPT_LONG, CAPB_LONG, false>), dim3((unsigned)(cap < LONG_WGS ? cap : LONG_WGS)),
+                               dim3(64), 0, st, d, s_tilde, sv, cand, tau, list_long, counters + 1, (int)cap, block_size, 0,
+                               (int32_t *)nullptr);
         }
     }
     return hipGetLastError();
@@ -868,6 +966,54 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
                            st, d, s_tilde, thr, full, counters + 1, (int)cap, budget, idx_out);
         hipLaunchKernelGGL((select_kernel<CAPT_LONG, CAPB_LONG>), dim3((unsigned)(cap < LONG_WGS ? cap : LONG_WGS)), dim3(64),
                            0, st, d, s_tilde, thr, full_long, counters + 2, (int)cap, budget, idx_out);
+    }
+    return hipGetLastError();
+}
+
+// ---- search and select in one sequence (same results as launch_search followed by launch_select)
+bool search_select_fused(const Dims &d, const SegView &sv, int32_t budget)
+{
+    return budget > 0 && budget < d.T && budget <= TB_HITS && sv.max_segments + 1 <= TB_OFFS;
+}
+
+size_t search_select_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget)
+{
+    const size_t a = search_ws_bytes(d, max_segments, budget), b = select_ws_bytes(d, max_segments, budget);
+    return a > b ? a : b;
+}
+
+hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
+                                int32_t budget, float tau, int32_t *seg_budget, int32_t *block_size, int32_t *topb_out,
+                                int32_t *idx_out, int32_t *n_sel_out, void *ws, hipStream_t st)
+{
+    if (d.P <= 0) return hipSuccess;
+    if (!search_select_fused(d, sv, budget)) {
+        hipError_t e = launch_search(d, s_tilde, sv, cand, budget, tau, seg_budget, block_size, topb_out, ws, st);
+        if (e != hipSuccess) return e;
+        // the select lists reuse the workspace of the search lists, which are consumed by then; the Top-B state
+        // sits in front of both layouts
+        const int32_t *thr = topb_out ? topb_out : static_cast<const int32_t *>(ws);
+        return launch_select(d, s_tilde, sv, seg_budget, block_size, thr, budget, idx_out, n_sel_out, ws, st);
+    }
+    const size_t cap = max_heavy_segments(d, sv.max_segments, budget);
+    char *w = static_cast<char *>(ws);
+    int32_t *thr = topb_out ? topb_out : reinterpret_cast<int32_t *>(w);
+    w += align256((size_t)d.P * 2 * 4);
+    int32_t *counters = reinterpret_cast<int32_t *>(w);
+    w += align256(8);
+    SegRec *list = reinterpret_cast<SegRec *>(w);
+    w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
+    SegRec *list_long = reinterpret_cast<SegRec *>(w);
+    hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, counters);
+    PlanArgs pa{list, list_long, (int)cap, idx_out, n_sel_out};
+    hipLaunchKernelGGL(topb_kernel<true>, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, sv, seg_budget,
+                       block_size, counters, pa);
+    if (cap > 0) {
+        hipLaunchKernelGGL((search_kernel<CAPT, CAPB, true>), dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64),
+                           0, st, d, s_tilde, sv, cand, tau, list, counters, (int)cap, block_size, budget, idx_out);
+        hipLaunchKernelGGL((search_kernel<CAPT_LONG, CAPB_LONG, true>), dim3((unsigned)(cap < LONG_WGS ? cap : LONG_WGS)),
+                           dim3(64), 0, st, d, s_tilde, sv, cand, tau, list_long, counters + 1, (int)cap, block_size, budget,
+                           idx_out);
     }
     return hipGetLastError();
 }

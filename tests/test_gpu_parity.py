@@ -137,7 +137,17 @@ def _search_select_gpu(torch, st_rows, off, cand, budget, tau):
     st = torch.as_tensor(st_rows.astype(np.float32)).cuda().contiguous()
     B.sablock_search_blocks(shape, st, seg, cand, budget, tau, buf.seg_budget, buf.block_size, buf.ws)
     B.sablock_select(shape, st, seg, buf.seg_budget, buf.block_size, budget, buf.idx, buf.n_sel, buf.ws)
+    # the one-call form of the two (the Top-B kernel plans the output rows, the search writes the tokens, where
+    # the sizes allow it): every output bit for bit the same
+    buf2 = B.Buffers(shape, seg, budget, "cuda")
+    for t in (buf2.seg_budget, buf2.block_size, buf2.idx, buf2.n_sel):
+        t.fill_(-7)
+    B.sablock_search_select(shape, st, seg, cand, budget, tau, buf2.seg_budget, buf2.block_size, buf2.idx, buf2.n_sel,
+                            buf2.ws)
     torch.cuda.synchronize()
+    for name in ("seg_budget", "block_size", "n_sel"):
+        assert torch.equal(getattr(buf, name), getattr(buf2, name)), f"one-call search+select: {name} differs"
+    assert torch.equal(buf.idx[:, :budget], buf2.idx[:, :budget]), "one-call search+select: idx differs"
     return H.to_np(buf.seg_budget), H.to_np(buf.block_size), H.to_np(buf.idx), H.to_np(buf.n_sel)
 
 
