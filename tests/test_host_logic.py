@@ -83,6 +83,11 @@ def test_calls_reject_bad_host_arguments_before_launch(lib):
     assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, cand_ok, 3, 10, 0.85, fake, fake, None, fake, 0, None) == 3
     big = (ctypes.c_int32 * 2)(1, 128)
     assert lib.sablock_search_blocks(sp, fake, fake, ptr2, 4, big, 2, 10, 0.85, fake, fake, None, fake, 1 << 20, None) == 2
+    assert lib.sablock_search_select(sp, fake, fake, ptr2, 4, cand_bad, 3, 10, 0.85, fake, fake, None, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_select(sp, fake, fake, ptr2, 4, cand_ok, 3, -1, 0.85, fake, fake, None, fake, fake, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_select(sp, fake, fake, ptr2, 4, cand_ok, 3, 10, 0.85, fake, fake, None, None, fake, fake, 1 << 20, None) == 1
+    assert lib.sablock_search_select(sp, fake, fake, ptr2, 4, cand_ok, 3, 10, 0.85, fake, fake, None, fake, fake, fake, 64, None) == 3
+    assert lib.sablock_search_select(sp, fake, fake, ptr2, 4, big, 2, 10, 0.85, fake, fake, None, fake, fake, fake, 1 << 20, None) == 2
     assert lib.sablock_select(sp, fake, fake, ptr2, 4, fake, fake, None, -5, fake, fake, fake, 1 << 20, None) == 1
     assert lib.sablock_select(sp, fake, fake, ptr2, 4, fake, fake, None, 5, fake, fake, fake, 8, None) == 3
     assert lib.sablock_compact(sp, fake, None, fake, fake, 8, 1, fake, fake, None) == 1
