@@ -48,23 +48,65 @@ constexpr int CAPT = 512, CAPB = 256;
 constexpr int CAPT_LONG = 4096, CAPB_LONG = 2048;
 constexpr int MAX_G = 64;           // largest candidate block size
 
+// Wavefront reductions without LDS round trips: four DPP steps inside each row of 16 lanes (lane ^ 1, lane ^ 2,
+// mirror inside 8, mirror inside 16: together they pair every lane with every other lane of its row), then the
+// four row results are read as scalars.  The results are wave-uniform.
+template <int CTRL>
+__device__ inline int dpp_i(int v) { return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false); }
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+
 __device__ inline int wave_sum_i(int v)
 {
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
+    v += dpp_i<DPP_XOR1>(v);
+    v += dpp_i<DPP_XOR2>(v);
+    v += dpp_i<DPP_HALF_MIRROR>(v);
+    v += dpp_i<DPP_MIRROR>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
 }
 __device__ inline int wave_max_i(int v)
 {
-    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off));
-    return v;
+    v = max(v, dpp_i<DPP_XOR1>(v));
+    v = max(v, dpp_i<DPP_XOR2>(v));
+    v = max(v, dpp_i<DPP_HALF_MIRROR>(v));
+    v = max(v, dpp_i<DPP_MIRROR>(v));
+    return max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+// best (value descending, index ascending) of the lanes' (value, index) pairs
+__device__ inline bool pair_better(double op, int om, double bp, int bm) { return op > bp || (op == bp && om < bm); }
+template <int CTRL>
+__device__ inline void argmax_step(double &bp, int &bm)
+{
+    const int olo = dpp_i<CTRL>(__double2loint(bp)), ohi = dpp_i<CTRL>(__double2hiint(bp)), om = dpp_i<CTRL>(bm);
+    const double op = __hiloint2double(ohi, olo);
+    if (pair_better(op, om, bp, bm)) { bp = op; bm = om; }
+}
+__device__ inline void wave_argmax(double &bp, int &bm)
+{
+    argmax_step<DPP_XOR1>(bp, bm);
+    argmax_step<DPP_XOR2>(bp, bm);
+    argmax_step<DPP_HALF_MIRROR>(bp, bm);
+    argmax_step<DPP_MIRROR>(bp, bm);
+    const int lo = __double2loint(bp), hi = __double2hiint(bp);
+    double rp = __hiloint2double(__builtin_amdgcn_readlane(hi, 0), __builtin_amdgcn_readlane(lo, 0));
+    int rm = __builtin_amdgcn_readlane(bm, 0);
+#pragma unroll
+    for (int r = 16; r < 64; r += 16) {
+        const double op = __hiloint2double(__builtin_amdgcn_readlane(hi, r), __builtin_amdgcn_readlane(lo, r));
+        const int om = __builtin_amdgcn_readlane(bm, r);
+        if (pair_better(op, om, rp, rm)) { rp = op; rm = om; }
+    }
+    bp = rp;
+    bm = rm;
 }
 
 // acc += v[j] for every set bit j of mask, ascending; mask and acc are wave-uniform
 __device__ inline double add_in_order(double acc, unsigned long long mask, float v)
 {
     while (mask) {
-        int j = __builtin_ctzll(mask);
-        acc += (double)__shfl(v, j);
+        const int j = __builtin_ctzll(mask);                 // wave-uniform, so the value comes by v_readlane
+        acc += (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), j));
         mask &= mask - 1;
     }
     return acc;
@@ -482,12 +524,7 @@ __device__ inline void segment_fill(V val, int a, int b, int g, int bk, WaveScra
                 const double pm = ws.phi[m];
                 if (ws.cls[m] == 0 && (pm > bp || (pm == bp && m < bm))) { bp = pm; bm = m; }
             }
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const double op = __shfl_xor(bp, o);
-                const int om = __shfl_xor(bm, o);
-                if (op > bp || (op == bp && om < bm)) { bp = op; bm = om; }
-            }
+            wave_argmax(bp, bm);
             if (lane == 0) ws.cls[bm] = sel < rstar ? 1 : 2;
             if (sel == rstar) mp_local = bm;
             __builtin_amdgcn_wave_barrier();
