@@ -17,9 +17,22 @@ constexpr int RSEG = NT / GROUP;           // segments per workgroup
 constexpr int RPT = 8;                     // staged tokens per thread
 constexpr int RCAP = RPT * NT;             // tokens per workgroup whose inputs are staged in LDS
 
+// sum over the 16 lanes of a group = one DPP row: lane ^ 1, lane ^ 2, mirror inside 8, mirror inside 16 (no LDS
+// round trips); every lane of the group gets the sum
+template <int CTRL>
+__device__ inline double dpp_add(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    return v + __hiloint2double(hi, lo);
+}
 __device__ inline double group_sum(double v)
 {
-    for (int off = GROUP / 2; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    static_assert(GROUP == 16, "a group is one DPP row");
+    v = dpp_add<0xB1>(v);
+    v = dpp_add<0x4E>(v);
+    v = dpp_add<0x141>(v);
+    v = dpp_add<0x140>(v);
     return v;
 }
 
