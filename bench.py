@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM traffic of the scoring kernels per step (bytes) from two rocprofv3 --pmc runs, FETCH_SIZE then WRITE_SIZE,
 # each scaled by what the counter reads for a plain copy of known size
 # (profiles/score_mfma_llama8b_128k_hbm_traffic.md); None for workloads that were not measured.
-MEASURED_TRAFFIC = {"llama8b_128k": 17.66e9}
+MEASURED_TRAFFIC = {"llama8b_128k": 17.60e9}
 
 
 def algorithmic_bytes(w, budget, append_window=True):
