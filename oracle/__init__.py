@@ -17,4 +17,5 @@ from .sablock_ref import (  # noqa: F401
     pipeline_head,
     segment,
     decode_attention,
+    window_attention,
 )

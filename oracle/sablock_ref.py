@@ -204,6 +204,34 @@ def segment(token_ids, delims: Sequence[int]) -> np.ndarray:
     return np.asarray(off, dtype=np.int32)
 
 
+def window_attention(q_win, k, v):
+    """Causal attention of the observation-window queries of one KV head over all L keys (Sec. 2.1, Eq. 1): the part
+    of the prefill attention whose softmax statistics the scoring step reuses.
+
+    ``q_win [G, W, D]`` (window query i sits at position T + i, T = L - W), ``k, v [L, D]``.  Query i attends to
+    keys t <= T + i.  Returns ``(out [G, W, Dv], lse [G, W])`` in float64: ``out = softmax(q . k / sqrt(D)) @ v`` and
+    ``lse`` the natural logarithm of the softmax denominator, i.e. log sum_t exp(q . k_t / sqrt(D)) over the visible
+    keys.
+    """
+    q = np.asarray(q_win, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    G, W, D = q.shape
+    L = k.shape[0]
+    T = L - W
+    out = np.zeros((G, W, v.shape[1]), dtype=np.float64)
+    lse = np.zeros((G, W), dtype=np.float64)
+    for g in range(G):
+        for i in range(W):
+            x = k[:T + i + 1] @ q[g, i] / np.sqrt(float(D))       # the visible keys only
+            m = x.max()
+            w = np.exp(x - m)
+            z = w.sum()
+            out[g, i] = (w / z) @ v[:T + i + 1]
+            lse[g, i] = m + np.log(z)
+    return out, lse
+
+
 def decode_attention(q, k_rows, v_rows) -> np.ndarray:
     """Attention of one new token over a cache, one KV head (Sec. 2.1, Eq. 1 with a single query position).
 

@@ -386,6 +386,53 @@ def test_decode_attention_pins(oracle):
     assert (oracle.decode_attention(q, k[:0], v[:0]) == 0).all()
 
 
+# ---------------------------------------------------------------- attention of the window queries (Sec. 2.1, Eq. 1)
+def test_window_attention_pins(oracle):
+    from scipy.special import logsumexp, softmax
+
+    rng = np.random.default_rng(8)
+    G, W, D, L = 3, 5, 12, 41
+    T = L - W
+    q, k, v = rng.standard_normal((G, W, D)), rng.standard_normal((L, D)), rng.standard_normal((L, 7))
+    out, lse = oracle.window_attention(q, k, v)
+    # library routines on the masked logits: softmax then a matrix product; logsumexp for the denominator
+    for g in range(G):
+        x = q[g] @ k.T / np.sqrt(D)
+        x[np.arange(L)[None, :] > T + np.arange(W)[:, None]] = -np.inf        # query i sees keys t <= T + i
+        np.testing.assert_allclose(out[g], softmax(x, axis=1) @ v, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(lse[g], logsumexp(x, axis=1), rtol=1e-13)
+    # the mask matters and sits where it should: changing a key or value row that query i cannot see changes nothing
+    # for queries <= i and something for the later ones
+    k2, v2 = k.copy(), v.copy()
+    k2[T + 3] += 1.0; v2[T + 3] -= 2.0
+    out2, lse2 = oracle.window_attention(q, k2, v2)
+    assert np.array_equal(out2[:, :3], out[:, :3]) and np.array_equal(lse2[:, :3], lse[:, :3])
+    assert (np.abs(out2[:, 3:] - out[:, 3:]).max(axis=2) > 1e-6).all() and (lse2[:, 3:] != lse[:, 3:]).all()
+    # q = 0: uniform weights over the T + i + 1 visible keys -> the running mean of V, lse = log(T + i + 1)
+    out0, lse0 = oracle.window_attention(np.zeros((1, W, D)), k, v)
+    for i in range(W):
+        np.testing.assert_allclose(out0[0, i], v[:T + i + 1].mean(axis=0), rtol=1e-12)
+        np.testing.assert_allclose(lse0[0, i], np.log(T + i + 1.0), rtol=1e-13)
+    # the same denominators as the scoring step: its attention rows are exp(logit - lse), so the column sums of
+    # exp(logit - lse) over the window rows of the G heads, averaged over the heads, are the oracle's scores
+    s_ref, _ = oracle.score(q, k, 1e-6)
+    acc = np.zeros(L)
+    for g in range(G):
+        x = q[g] @ k.T / np.sqrt(D)
+        a = np.exp(x - lse[g][:, None])
+        a[np.arange(L)[None, :] > T + np.arange(W)[:, None]] = 0.0
+        acc += a.sum(axis=0)
+    np.testing.assert_allclose(acc / G, s_ref, rtol=1e-10, atol=1e-14)
+    # a decode step is the window of one query at the end: both oracle functions agree there
+    o1, _ = oracle.window_attention(q[:, -1:, :], k, v)
+    np.testing.assert_allclose(o1[:, 0], oracle.decode_attention(q[:, -1], k, v), rtol=1e-12, atol=1e-14)
+    # the 1/sqrt(D) scale: zero-padding D -> 4D halves the logits
+    pad = lambda a: np.concatenate([a, np.zeros(a.shape[:-1] + (3 * D,))], axis=-1)
+    o_pad, l_pad = oracle.window_attention(pad(q), pad(k), v)
+    o_half, l_half = oracle.window_attention(q / 2, k, v)
+    np.testing.assert_allclose(o_pad, o_half, rtol=1e-12); np.testing.assert_allclose(l_pad, l_half, rtol=1e-12)
+
+
 # ---------------------------------------------------------------- head mean over all heads of a layer (Eq. barA, literal)
 def test_score_layer_pins(oracle):
     from scipy.special import softmax
