@@ -202,6 +202,21 @@ SABLOCK_API sablock_status sablock_compact_shared(const sablock_shape *shape, co
                                       int32_t append_window, void *k_out, void *v_out, void *stream);
 
 /*
+ * The producer of row_lse (Sec. 2.1, Eq. 1): causal attention of the W window queries over all L keys, i.e. the
+ * rows of the prefill attention that the scoring step looks at.  Query i (position T + i) attends to keys
+ * t <= T + i.  A prefill that computes these rows here (or takes the same two outputs from its own attention
+ * kernel) hands row_lse to sablock_score, which then reads K once.
+ *   out          [n_seq][n_layers][n_q_heads][W][D] fp32: softmax(q . k / sqrt(D)) @ v
+ *   row_lse_out  [P][G * W] fp32, natural log of the softmax denominators, in the layout sablock_score takes
+ * Supported: bf16, head_dim 128, 4 query heads per KV head, W = 32; otherwise UNSUPPORTED.  Probabilities enter
+ * the second product rounded to bf16 (the denominators are summed in fp32 before rounding).
+ */
+SABLOCK_API sablock_status sablock_window_attention_workspace_bytes(const sablock_shape *shape, size_t *bytes_out);
+SABLOCK_API sablock_status sablock_window_attention(const sablock_shape *shape, const void *q_win, const void *k,
+                                        const void *v, float *out, float *row_lse_out,
+                                        void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Punctuation-based segmentation of the compressible region (Sec. 3.1), the step in front of the five calls:
  * delimiter tokens (commas, periods, ...) mark segment boundaries.  A delimiter closes the segment it belongs to:
  * a new segment starts after every token t < n_tokens - 1 whose id is in `delims`; consecutive delimiters give

@@ -25,7 +25,8 @@ EXPORTS = ("sablock_version", "sablock_last_error", "sablock_workspace_bytes", "
            "sablock_refine", "sablock_search_blocks", "sablock_select", "sablock_compact",
            "sablock_segment_count", "sablock_segment_offsets", "sablock_decode_workspace_bytes",
            "sablock_decode_attention", "sablock_score_all_heads_workspace_bytes", "sablock_score_all_heads",
-           "sablock_compact_shared", "sablock_search_select")
+           "sablock_compact_shared", "sablock_search_select", "sablock_window_attention_workspace_bytes",
+           "sablock_window_attention")
 
 
 class SablockError(RuntimeError):
@@ -77,6 +78,8 @@ def load():
         lib.sablock_score_all_heads_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
         lib.sablock_score_all_heads.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp, ctypes.c_size_t, vp]
         lib.sablock_compact_shared.argtypes = [sp, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        lib.sablock_window_attention_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
+        lib.sablock_window_attention.argtypes = [sp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         for n in EXPORTS[2:]:
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
@@ -246,6 +249,17 @@ def sablock_compact_shared(shape: CShape, k, v, idx, n_sel, budget: int, append_
                            stream=None):
     _check(load().sablock_compact_shared(ctypes.byref(shape), _ptr(k), _ptr(v), _ptr(idx), _ptr(n_sel), budget,
                                          1 if append_window else 0, _ptr(k_out), _ptr(v_out), _stream(stream)))
+
+
+def sablock_window_attention_workspace_bytes(shape: CShape) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().sablock_window_attention_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)))
+    return int(out.value)
+
+
+def sablock_window_attention(shape: CShape, q, k, v, out, row_lse_out, ws, stream=None):
+    _check(load().sablock_window_attention(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(row_lse_out),
+                                           _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def make_cache_shape(q, k_cache, v_cache=None) -> CShape:

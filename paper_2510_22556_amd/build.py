@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsablock.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-SOURCES = ["api.hip", "score_generic.hip", "score_mfma.hip", "refine.hip", "search_select.hip", "compact.hip", "segment.hip", "decode.hip"]
+SOURCES = ["api.hip", "score_generic.hip", "score_mfma.hip", "refine.hip", "search_select.hip", "compact.hip", "segment.hip", "decode.hip", "window_attn.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
          # keep packed fp32 instructions out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -306,6 +306,37 @@ sablock_status sablock_score_all_heads(const sablock_shape *shape, const void *q
                "sablock_score_all_heads");
 }
 
+sablock_status sablock_window_attention_workspace_bytes(const sablock_shape *shape, size_t *bytes_out)
+{
+    if (!bytes_out) return fail(SABLOCK_ERR_INVALID_ARG, "bytes_out is NULL");
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!window_attention_supported(d))
+        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_window_attention: needs bf16, head_dim 128, 4 query heads per KV head and a window of 32");
+    *bytes_out = window_attention_ws_bytes(d);
+    return SABLOCK_OK;
+}
+
+sablock_status sablock_window_attention(const sablock_shape *shape, const void *q_win, const void *k, const void *v,
+                                        float *out, float *row_lse_out, void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!q_win || !k || !v || !out || !row_lse_out) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_window_attention: NULL argument");
+    if (!aligned16(q_win) || !aligned16(k) || !aligned16(v))
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_window_attention: Q/K/V must be 16-byte aligned");
+    if (shape->v_stride[3] < d.D) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_window_attention: V token stride smaller than head_dim");
+    if (!window_attention_supported(d))
+        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_window_attention: needs bf16, head_dim 128, 4 query heads per KV head and a window of 32");
+    const size_t need = window_attention_ws_bytes(d);
+    if (!ws || ws_bytes < need)
+        return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_window_attention: workspace %zu < %zu bytes", ws_bytes, need);
+    return dev(launch_window_attention(d, q_win, k, v, out, row_lse_out, ws, static_cast<hipStream_t>(stream)),
+               "sablock_window_attention");
+}
+
 static sablock_status make_delims(const int32_t *delims, int32_t n_delim, DelimSet *ds)
 {
     if (n_delim < 0 || (n_delim > 0 && !delims)) return fail(SABLOCK_ERR_INVALID_ARG, "delims is NULL or n_delim < 0");

@@ -129,6 +129,12 @@ hipError_t launch_segment_count(const int32_t *tok, int64_t stride, int32_t n_se
 hipError_t launch_segment_offsets(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,
                                   const SeqPtr &sp, int32_t *seg_off, hipStream_t st);
 
+// attention of the window queries over all keys, with the rows' log-sum-exp (the producer of sablock_score's row_lse)
+bool window_attention_supported(const Dims &d);
+size_t window_attention_ws_bytes(const Dims &d);
+hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, const void *v, float *out, float *lse,
+                                   void *ws, hipStream_t st);
+
 // decode-time attention over a cache (the step after the path); d.L = rows of the cache buffers
 bool decode_supported(const Dims &d);
 size_t decode_ws_bytes(const Dims &d);

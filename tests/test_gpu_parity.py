@@ -832,3 +832,53 @@ def test_ablation_switches_as_degenerate_configurations(oracle, torch_cuda):
     run = H.GpuRun(q, k, v, off, ptr, w.cand, B_, w.eps, 0.0, w.eta, w.tau)
     _check_all(oracle, w0, run, q, k, v, off, ptr, [3])
     assert np.array_equal(run.st, run.s[:, :w.T])
+
+
+@pytest.mark.parametrize("chunk", [0, 512])
+def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, monkeypatch, chunk):
+    # Attention of the window queries (the producer of row_lse) against the oracle: outputs and log-sum-exp; keys
+    # planted along query rows so that the running reference moves late in the stream, inside the window and in a
+    # chunk's first subtile; one chunk per problem and many (merge kernel); ragged length.  Its row_lse then drives
+    # sablock_score, whose scores must equal those of the two-pass run.
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    if chunk:
+        monkeypatch.setenv("SABLOCK_WINDOW_CHUNK", str(chunk))
+    ns, nl, Hkv, G, W, D = 1, 2, 2, 4, 32, 128
+    L = 3 * 1024 + 77 + W
+    T = L - W
+    q = synth.normal_torch(808, 1, (ns, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(808, 2, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(808, 3, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    for (l, h, g, i, t, scale) in [(0, 0, 1, 5, 2000, 5.0), (0, 0, 1, 5, 2600, 9.0), (0, 1, 3, 31, T + 20, 6.0),
+                                   (1, 0, 0, 0, 512, 7.0), (1, 1, 2, 17, 40, 8.0)]:
+        k[0, l, h, t, :] = (q[0, l, h * G + g, i, :].float() * scale).to(torch.bfloat16)
+    shape = B.make_shape(q, k, v)
+    ws = torch.empty((B.sablock_window_attention_workspace_bytes(shape),), dtype=torch.uint8, device="cuda")
+    out = torch.full((ns, nl, G * Hkv, W, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((ns * nl * Hkv, G * W), float("nan"), dtype=torch.float32, device="cuda")
+    B.sablock_window_attention(shape, q, k, v, out, lse, ws)
+    torch.cuda.synchronize()
+    out_g, lse_g = H.to_np(out), H.to_np(lse)
+    vmax = float(v.float().abs().max())
+    for l in range(nl):
+        for h in range(Hkv):
+            o_ref, l_ref = oracle.window_attention(H.widen(H.to_np(q[0, l, h * G:(h + 1) * G])), H.widen(H.to_np(k[0, l, h])),
+                                                   H.widen(H.to_np(v[0, l, h])))
+            p = l * Hkv + h
+            np.testing.assert_allclose(lse_g[p].reshape(G, W), l_ref, rtol=0, atol=2e-5)
+            # probabilities enter the second product rounded to bf16 (relative 2^-9 each, signs random)
+            np.testing.assert_allclose(out_g[0, l, h * G:(h + 1) * G], o_ref, rtol=0, atol=4e-3 * vmax)
+            assert np.abs(out_g[0, l, h * G:(h + 1) * G] - o_ref).mean() < 4e-4 * vmax
+    # the planted keys dominate their rows: the output is (nearly) that key's value row
+    np.testing.assert_allclose(out_g[0, 0, 1, 5], H.widen(H.to_np(v[0, 0, 0, 2600])), rtol=0, atol=2e-2)
+    # scoring from this row_lse = scoring with its own first pass
+    seg = B.make_segments(np.array([0, T], dtype=np.int32), [0, 2], "cuda")
+    buf = B.Buffers(shape, seg, 16, "cuda")
+    B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, 1e-6)
+    s0, e0 = H.to_np(buf.s).copy(), H.to_np(buf.ent).copy()
+    B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, 1e-6, row_lse=lse)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(H.to_np(buf.s), s0, rtol=1e-4, atol=1e-9)
+    np.testing.assert_allclose(H.to_np(buf.ent), e0, rtol=1e-4, atol=1e-6)
