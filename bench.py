@@ -306,19 +306,41 @@ def main():
         result["score_all_heads"] = {"unsupported": str(ex)}
     if not args.no_row_lse:
         # The path handed the rows' log-sum-exp, which a prefill attention kernel has anyway (single pass over K).
-        # The values are computed here with library calls, outside every timed region: they are an INPUT.
+        # Where the shape allows it the values come from this library's own attention of the window queries
+        # (sablock_window_attention, timed below as an entry of its own), else from library calls; in both cases
+        # outside the timed region of the step: they are an INPUT of the path.
         lse = torch.empty((w.n_seq, w.n_layers, w.n_q_heads, w.window), dtype=torch.float32, device=dev)
         G = w.n_q_heads // w.n_kv_heads
-        qi = torch.arange(w.window, device=dev)[:, None]
-        for b in range(w.n_seq):
-            for l in range(w.n_layers):
-                for h in range(w.n_kv_heads):
-                    qq = q[b, l, h * G:(h + 1) * G].reshape(G * w.window, w.head_dim).float()
-                    sc = (qq @ k[b, l, h].float().T) / math.sqrt(w.head_dim)          # [G * W, seq_len]
-                    tail = sc[:, w.T:].view(G, w.window, w.window)                     # causal inside the window
-                    tail.masked_fill_(torch.arange(w.window, device=dev)[None, :] > qi, float("-inf"))
-                    lse[b, l, h * G:(h + 1) * G] = torch.logsumexp(sc, dim=1).view(G, w.window)
-        del sc, qq, tail
+        try:
+            wws = torch.empty((B.sablock_window_attention_workspace_bytes(shape),), dtype=torch.uint8, device=dev)
+            wout = torch.empty((w.n_seq, w.n_layers, w.n_q_heads, w.window, w.head_dim), dtype=torch.float32, device=dev)
+            B.sablock_window_attention(shape, q, k, v, wout, lse, wws)
+            w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            w0.record()
+            for _ in range(5):
+                B.sablock_window_attention(shape, q, k, v, wout, lse, wws)
+            w1.record()
+            torch.cuda.synchronize()
+            wms = w0.elapsed_time(w1) / 5
+            kv_bytes = 2 * w.n_seq * w.n_layers * w.n_kv_heads * w.seq_len * w.head_dim * elt
+            result["window_attention"] = {"ms": wms, "GBps": kv_bytes / (wms * 1e-3) / 1e9,
+                                          "frac_hbm_peak": kv_bytes / (wms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                          "TFLOPs": 4.0 * w.n_seq * w.n_layers * w.n_q_heads * w.window * w.seq_len
+                                                    * w.head_dim / (wms * 1e-3) / 1e12}
+            lse_from = "sablock_window_attention"
+            del wws, wout
+        except B.SablockError:
+            qi = torch.arange(w.window, device=dev)[:, None]
+            for b in range(w.n_seq):
+                for l in range(w.n_layers):
+                    for h in range(w.n_kv_heads):
+                        qq = q[b, l, h * G:(h + 1) * G].reshape(G * w.window, w.head_dim).float()
+                        sc = (qq @ k[b, l, h].float().T) / math.sqrt(w.head_dim)          # [G * W, seq_len]
+                        tail = sc[:, w.T:].view(G, w.window, w.window)                     # causal inside the window
+                        tail.masked_fill_(torch.arange(w.window, device=dev)[None, :] > qi, float("-inf"))
+                        lse[b, l, h * G:(h + 1) * G] = torch.logsumexp(sc, dim=1).view(G, w.window)
+            del sc, qq, tail
+            lse_from = "torch.logsumexp"
 
         def step_lse(score_events=None):
             if score_events is not None:
@@ -343,7 +365,7 @@ def main():
         ms = sum(e[0].elapsed_time(e[1]) for e in lev) / args.steps
         result["score_with_row_lse"] = {"ms": ms, "GBps": alg["score"] / (ms * 1e-3) / 1e9,
                                         "frac": alg["score"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-        result["step_with_row_lse"] = {"ms_per_step": dt2 * 1e3, "value": w.n_seq * w.seq_len * w.n_layers / dt2,
+        result["step_with_row_lse"] = {"row_lse_from": lse_from, "ms_per_step": dt2 * 1e3, "value": w.n_seq * w.seq_len * w.n_layers / dt2,
                                        "GBps": sum(alg.values()) / dt2 / 1e9,
                                        "frac_hbm_peak": sum(alg.values()) / dt2 / 1e9 / HBM_PEAK_GBS}
     if args.cpu_layers > 0:

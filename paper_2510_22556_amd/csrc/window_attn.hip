@@ -6,7 +6,10 @@
 // problem (sequence, layer, KV head); its four wavefronts are the four query heads.  K and V subtiles of 32 keys
 // go global -> LDS by direct-to-LDS loads into a workgroup-wide ring of NSTAGE stages (each wavefront issues a
 // quarter of a stage); one LDS-only barrier per subtile tells that the stage has landed and that the stage of
-// the previous iteration is free to be refilled.
+// the previous iteration is free to be refilled.  The score product, the exponentials and the second product of
+// a subtile depend on each other, so a wavefront alone leaves its SIMD idle between them: the ring is kept to
+// 64 KiB so that two workgroups share a CU, and a problem is split over at least two workgroups (partial results
+// are merged by a second kernel).
 //
 // Scores are formed TRANSPOSED, S^T = K Q^T (the same operand registers as Q K^T with the MFMA's A and B swapped):
 // a lane then owns ONE query (column) and 16 of the subtile's 32 keys, so the row maximum and the row sum are
@@ -35,7 +38,7 @@ constexpr int SUB = 32;                        // keys per subtile
 constexpr int ROW_BYTES = 256;                 // D = 128 bf16
 constexpr int TILE_BYTES = SUB * ROW_BYTES;    // 8 KiB: one K or V subtile
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // K tile, then V tile
-constexpr int NSTAGE = 8;                      // 128 KiB ring per workgroup
+constexpr int NSTAGE = 4;                      // 64 KiB ring per workgroup: two workgroups (8 wavefronts) per CU
 constexpr int WA_WAVES = 4;                    // = G
 constexpr int ROWS = 32;                       // = W
 constexpr int WA_LDS = NSTAGE * STAGE_BYTES + WA_WAVES * ROWS * 4;   // ring + a 32-float exchange slice per wavefront
@@ -74,12 +77,16 @@ __device__ __forceinline__ float other_half(float x, bool take_max)
 // all LDS traffic of this wavefront done, then the workgroup barrier (global loads stay in flight)
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// one 1 KiB piece (4 rows) of a K or V subtile whose first row is t0: rows past L-1 read row L-1 (masked later)
-template <bool SWIZZLE>
+// one 1 KiB piece (4 rows) of a K or V subtile whose first row is t0: rows past L-1 read row L-1 (masked later).
+// LDS slot (row, pos) of a K tile receives the row's 16-byte chunk pos ^ (row & 15) (conflict-free 16-byte operand
+// reads, one row per lane); of a V tile chunk pos ^ 4 ((row >> 1) & 3), i.e. the row's four 64-byte groups are
+// rotated by the row pair: a transposing read touches one 64-byte group of 8 consecutive rows, which then fall on
+// four different bank groups, two rows each: the two LDS passes that 512 bytes need anyway.
+template <bool IS_K>
 __device__ __forceinline__ void issue_piece(const char *tile_base, int64_t row_bytes, int t0, int L, int j, int lane, uint32_t lds_dst)
 {
     const int r4 = lane >> 4, pos = lane & 15, row = 4 * j + r4;
-    const uint32_t chunk = SWIZZLE ? (uint32_t)((pos ^ row) & 15) : (uint32_t)pos;
+    const uint32_t chunk = IS_K ? (uint32_t)((pos ^ row) & 15) : (uint32_t)(pos ^ (4 * ((row >> 1) & 3)));
     if (t0 + SUB <= L) {
         dma_1k((uint32_t)(r4 * row_bytes) + (chunk << 4), tile_base + (int64_t)(4 * j) * row_bytes, lds_dst);
     } else {
@@ -104,7 +111,7 @@ window_attention_kernel(WinArgs a)
     const int64_t krow = d.ks[3] * 2, vrow = d.vs[3] * 2;
 
     // ---- loads: stage u % NSTAGE holds subtile u; this wavefront brings K pieces 2w, 2w+1 and V pieces 2w, 2w+1.
-    // K rows are stored with their 16-byte chunks XOR-swizzled by the row (conflict-free operand reads), V plainly.
+    // (both tiles are stored swizzled, see issue_piece)
     auto issue = [&](int u) {
         const int t0 = lo + u * SUB;                           // < L
         const uint32_t st = ring + (u % NSTAGE) * STAGE_BYTES;
@@ -135,17 +142,20 @@ window_attention_kernel(WinArgs a)
     // V operand reads: lane = 16 g + pp; receiver of column 16 (g % 2) + pp of the 32-column tile, key block kb = g / 2;
     // as a provider it points at row (pp / 4) of a 4-key group, columns 4 (pp % 4) .. +4 of its 16-column half
     const int g16 = lane >> 4, pp = lane & 15;
-    const uint32_t v_lane = (uint32_t)((4 * (g16 >> 1) + (pp >> 2)) * ROW_BYTES + (16 * (g16 & 1) + 4 * (pp & 3)) * 2);
+    uint32_t v_lane[4];                                        // per 32-column tile t: its 64-byte group sits at t ^ sw
+    {
+        const int sw = (2 * (g16 >> 1) + (pp >> 3)) & 3;       // ((row >> 1) & 3) of the rows this lane points at
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            v_lane[t] = (uint32_t)((4 * (g16 >> 1) + (pp >> 2)) * ROW_BYTES + 64 * (t ^ sw) + 32 * (g16 & 1) + 8 * (pp & 3));
+    }
 
     for (int u = 0; u < n_sub; ++u) {
         // the pieces this wavefront issued for subtile u have landed (later stages: 4 loads each stay in flight) ...
         {
+            static_assert(NSTAGE - 2 <= 2, "the wait below knows up to two later stages");
             const int after = min(NSTAGE - 2, n_sub - 1 - u);
-            if (after >= 6) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-            else if (after == 5) asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
-            else if (after == 4) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-            else if (after == 3) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-            else if (after == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            if (after >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
             else if (after == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
@@ -219,7 +229,7 @@ window_attention_kernel(WinArgs a)
         for (int s = 0; s < 2; ++s) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const uint32_t va = st + TILE_BYTES + v_lane + (uint32_t)(16 * s * ROW_BYTES + 32 * t * 2);
+                const uint32_t va = st + TILE_BYTES + v_lane[t] + (uint32_t)(16 * s * ROW_BYTES);
                 short4v v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)(uintptr_t)va);
                 short4v v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (__attribute__((address_space(3))) short4v *)(uintptr_t)(va + 8 * ROW_BYTES));
@@ -293,11 +303,12 @@ int wa_compute_units()
     return cus;
 }
 
-// keys per workgroup: whole rounds of one workgroup per CU, as few as keep a chunk within 131 072 keys
+// keys per workgroup: whole rounds of two workgroups per CU (two wavefronts per SIMD: while one waits for its
+// LDS reads or an MFMA result the other computes), as few as keep a chunk within 131 072 keys
 void wa_plan(const Dims &d, int *chunk_len, int *n_chunks)
 {
     constexpr int MAX_CHUNK = 131072;
-    const int64_t cus = wa_compute_units();
+    const int64_t cus = 2 * (int64_t)wa_compute_units();
     const int64_t rounds = ((int64_t)d.P * d.L + cus * MAX_CHUNK - 1) / (cus * MAX_CHUNK);
     const int64_t per_problem = std::max<int64_t>(1, (cus * rounds + d.P / 2) / d.P);
     int len = (int)(((d.L + per_problem - 1) / per_problem + SUB - 1) / SUB) * SUB;
