@@ -153,6 +153,18 @@ def test_all_head_calls_validate_host_arguments(lib):
         with pytest.raises(B.SablockError) as ei:
             B.sablock_score_all_heads_workspace_bytes(llama_shape(**bad))
         assert ei.value.status == 2, bad
+    # attention of the window queries (same shape family): validation only, nothing is launched
+    nw = B.sablock_window_attention_workspace_bytes(llama_shape())
+    assert nw >= 256
+    assert lib.sablock_window_attention(sp, None, fake, fake, fake, fake, fake, nw, None) == 1
+    assert lib.sablock_window_attention(sp, fake, fake, fake, fake, None, fake, nw, None) == 1
+    assert lib.sablock_window_attention(sp, fake, fake, ctypes.c_void_p(0x1008), fake, fake, fake, nw, None) == 1
+    assert lib.sablock_window_attention(sp, fake, fake, fake, fake, fake, fake, nw - 1, None) == 3
+    assert lib.sablock_window_attention(sp, fake, fake, fake, fake, fake, None, nw, None) == 3
+    for bad in (dict(dtype=B.SABLOCK_F32), dict(head_dim=64), dict(window=16), dict(n_q_heads=16)):
+        with pytest.raises(B.SablockError) as ei:
+            B.sablock_window_attention_workspace_bytes(llama_shape(**bad))
+        assert ei.value.status == 2, bad
     assert lib.sablock_compact_shared(sp, fake, None, fake, fake, 8, 1, fake, fake, None) == 1
     assert lib.sablock_compact_shared(sp, fake, fake, fake, fake, -8, 1, fake, fake, None) == 1
     assert lib.sablock_compact_shared(sp, fake, fake, None, fake, 8, 1, fake, fake, None) == 1
