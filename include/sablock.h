@@ -8,9 +8,12 @@
  *   sablock_search_blocks  Top-B, implicit budgets, block-size search    (Alg. 2, Eqs. topk, implicit_budget, rk, gk_star)
  *   sablock_select         per-segment token sets and their union        (Alg. 2, Eq. final_selection)
  *   sablock_compact        gather of K/V rows into the retained cache    (end of Sec. 3.3)
+ * (sablock_search_select is sablock_search_blocks and sablock_select in one call, with the same results.)
  * In front of them, sablock_segment_count / sablock_segment_offsets turn token ids and a delimiter set into the
- * segment offsets the five calls take (Sec. 3.1); behind them, sablock_decode_attention is one decode step
- * over the cache they leave (or over the full cache, for comparison).
+ * segment offsets the five calls take (Sec. 3.1), and sablock_window_attention computes the attention of the window
+ * queries together with the row statistics that let sablock_score read K once; behind them,
+ * sablock_decode_attention is one decode step over the cache they leave (or over the full cache, for comparison).
+ * sablock_score_all_heads / sablock_compact_shared are the variant with one retained set per layer.
  *
  * Conventions shared by all calls
  * -------------------------------
