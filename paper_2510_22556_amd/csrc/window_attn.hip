@@ -2,8 +2,9 @@
 // softmax denominators of its rows as a second output: the part of a prefill attention whose row statistics the
 // scoring step (Sec. 3.2) needs.  With them sablock_score reads K once (its column pass alone).
 //
-// bf16, D = 128, G = 4 query heads per KV head, W = 32 window queries.  A workgroup owns a chunk of keys of one
-// problem (sequence, layer, KV head); its four wavefronts are the four query heads.  K and V subtiles of 32 keys
+// bf16, D = 128; (G, W) = (4, 32) with four wavefronts per workgroup, (4, 64) or (8, 32) with eight: a wavefront
+// is one block of 32 window-query rows (one head, or one half of a head's window of 64).  A workgroup owns a chunk
+// of keys of one problem (sequence, layer, KV head).  K and V subtiles of 32 keys
 // go global -> LDS by direct-to-LDS loads into a workgroup-wide ring of NSTAGE stages (each wavefront issues a
 // quarter of a stage); one LDS-only barrier per subtile tells that the stage has landed and that the stage of
 // the previous iteration is free to be refilled.  The score product, the exponentials and the second product of
@@ -39,9 +40,8 @@ constexpr int ROW_BYTES = 256;                 // D = 128 bf16
 constexpr int TILE_BYTES = SUB * ROW_BYTES;    // 8 KiB: one K or V subtile
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // K tile, then V tile
 constexpr int NSTAGE = 4;                      // 64 KiB ring per workgroup: two workgroups (8 wavefronts) per CU
-constexpr int WA_WAVES = 4;                    // = G
-constexpr int ROWS = 32;                       // = W
-constexpr int WA_LDS = NSTAGE * STAGE_BYTES + WA_WAVES * ROWS * 4;   // ring + a 32-float exchange slice per wavefront
+constexpr int ROWS = 32;                       // window-query rows of a wavefront
+constexpr int wa_lds(int nw) { return NSTAGE * STAGE_BYTES + nw * ROWS * 4; }   // ring + a 32-float exchange slice per wavefront
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float RESCALE_AT = 64.f;
@@ -53,8 +53,8 @@ struct WinArgs {
     float c1;                  // log2(e) / sqrt(D)
     float *out;                // [P * G][W][D] fp32 (n_chunks == 1) ...
     float *lse;                // [P][G * W] natural log
-    float *o_part;             // ... or partial results [P * G][n_chunks][W][D], unnormalised
-    float *ml_part;            // [P * G][n_chunks][W][2]: reference (log2 domain), sum
+    float *o_part;             // ... or partial results [P * NW][n_chunks][32][D], unnormalised (NW row blocks per problem)
+    float *ml_part;            // [P * NW][n_chunks][32][2]: reference (log2 domain), sum
 };
 
 __device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)(lptr_t)p; }
@@ -94,38 +94,50 @@ __device__ __forceinline__ void issue_piece(const char *tile_base, int64_t row_b
     }
 }
 
-__global__ void __launch_bounds__(WA_WAVES * 64)
+// NW: wavefronts = 32-row blocks per problem (G * W / 32)
+template <int NW>
+__global__ void __launch_bounds__(NW * 64)
 window_attention_kernel(WinArgs a)
 {
+    constexpr int LOADS = 16 / NW;                             // direct-to-LDS loads per wavefront and stage (K and V pieces)
+    constexpr int KPIECES = 8 / NW;                            // of which K pieces (as many V pieces)
     extern __shared__ __attribute__((aligned(8192))) char lds[];
     const Dims &d = a.d;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 31, hf = lane >> 5;                   // n: query (score tiles) or d column (output tiles)
     const int p = blockIdx.x / a.n_chunks, chunk = blockIdx.x - p * a.n_chunks;
     const int lo = chunk * a.chunk_len, hi = min(lo + a.chunk_len, d.L);
-    const int n_sub = hi > lo ? (hi - lo + SUB - 1) / SUB : 0;                 // the same for the four wavefronts
+    const int n_sub = hi > lo ? (hi - lo + SUB - 1) / SUB : 0;                 // the same for all wavefronts
+    const int blocks_per_head = d.W / ROWS;                    // 1 or 2
+    const int head = wave / blocks_per_head, qoff = ROWS * (wave - head * blocks_per_head);
     const uint32_t ring = __builtin_amdgcn_readfirstlane(lds_addr(lds));
-    float *fac = reinterpret_cast<float *>(lds + NSTAGE * STAGE_BYTES) + wave * ROWS;
+    float *fac = reinterpret_cast<float *>(lds + NSTAGE * STAGE_BYTES) + wave * ROWS;        // this wavefront's exchange slice
     const char *kp = reinterpret_cast<const char *>(a.k + k_problem_offset(d, p));
     const char *vp = reinterpret_cast<const char *>(a.v + v_problem_offset(d, p));
     const int64_t krow = d.ks[3] * 2, vrow = d.vs[3] * 2;
 
-    // ---- loads: stage u % NSTAGE holds subtile u; this wavefront brings K pieces 2w, 2w+1 and V pieces 2w, 2w+1.
-    // (both tiles are stored swizzled, see issue_piece)
+    // ---- loads: stage u % NSTAGE holds subtile u; this wavefront brings its share of the 8 K pieces and of the 8 V
+    // pieces (both tiles are stored swizzled, see issue_piece)
     auto issue = [&](int u) {
         const int t0 = lo + u * SUB;                           // < L
         const uint32_t st = ring + (u % NSTAGE) * STAGE_BYTES;
-        issue_piece<true>(kp + (int64_t)t0 * krow, krow, t0, d.L, 2 * wave, lane, st + (2 * wave) * 1024);
-        issue_piece<true>(kp + (int64_t)t0 * krow, krow, t0, d.L, 2 * wave + 1, lane, st + (2 * wave + 1) * 1024);
-        issue_piece<false>(vp + (int64_t)t0 * vrow, vrow, t0, d.L, 2 * wave, lane, st + TILE_BYTES + (2 * wave) * 1024);
-        issue_piece<false>(vp + (int64_t)t0 * vrow, vrow, t0, d.L, 2 * wave + 1, lane, st + TILE_BYTES + (2 * wave + 1) * 1024);
+#pragma unroll
+        for (int jj = 0; jj < KPIECES; ++jj) {
+            const int j = KPIECES * wave + jj;
+            issue_piece<true>(kp + (int64_t)t0 * krow, krow, t0, d.L, j, lane, st + j * 1024);
+        }
+#pragma unroll
+        for (int jj = 0; jj < KPIECES; ++jj) {
+            const int j = KPIECES * wave + jj;
+            issue_piece<false>(vp + (int64_t)t0 * vrow, vrow, t0, d.L, j, lane, st + TILE_BYTES + j * 1024);
+        }
     };
     for (int u = 0; u < NSTAGE - 1 && u < n_sub; ++u) issue(u);
 
-    // ---- this head's window queries: B operand of S^T = K Q^T, lane (query n, half hf) holds Q[n][(2s + hf) * 8 .. +8]
+    // ---- this block's window queries: B operand of S^T = K Q^T, lane (query n, half hf) holds Q[n][(2s + hf) * 8 .. +8]
     bf16x8 qa[8];
     {
-        const uint16_t *row = a.q + q_row_offset(d, p, wave, n);
+        const uint16_t *row = a.q + q_row_offset(d, p, head, qoff + n);
 #pragma unroll
         for (int s = 0; s < 8; ++s) qa[s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
     }
@@ -155,8 +167,8 @@ window_attention_kernel(WinArgs a)
         {
             static_assert(NSTAGE - 2 <= 2, "the wait below knows up to two later stages");
             const int after = min(NSTAGE - 2, n_sub - 1 - u);
-            if (after >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-            else if (after == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            if (after >= 2) { if (LOADS == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); }
+            else if (after == 1) { if (LOADS == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); }
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
         // ... and after the barrier so have everyone's; the stage of the previous iteration is free: refill it
@@ -185,7 +197,7 @@ window_attention_kernel(WinArgs a)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int t = t0 + row_of(i, hf);
-                if (!(t < d.L && t <= d.T + n)) acc[i] = -INFINITY;
+                if (!(t < d.L && t <= d.T + qoff + n)) acc[i] = -INFINITY;
             }
         }
         // ---- reference: anchored at the first subtile, moved when a logit runs more than `lim` ahead of it
@@ -243,21 +255,22 @@ window_attention_kernel(WinArgs a)
     // unnormalised with (reference, sum) for the merge
     const float l_tot = other_half(l, false);
     const float ref2 = r * a.c1;                               // log2 domain
-    const int ph = p * WA_WAVES + wave;                        // (problem, head)
+    const int pb = p * NW + wave;                              // (problem, row block)
+    const int64_t out_row0 = ((int64_t)p * d.G + head) * d.W + qoff;           // first output row of this block
     if (a.n_chunks == 1) {
         if (hf == 0) {
             fac[n] = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-            a.lse[(int64_t)p * (WA_WAVES * ROWS) + wave * ROWS + n] = (ref2 + __builtin_amdgcn_logf(l_tot)) * LN2;
+            a.lse[out_row0 + n] = (ref2 + __builtin_amdgcn_logf(l_tot)) * LN2;
         }
     } else if (hf == 0) {
         fac[n] = 1.f;
-        float *ml = a.ml_part + (((int64_t)ph * a.n_chunks + chunk) * ROWS + n) * 2;
+        float *ml = a.ml_part + (((int64_t)pb * a.n_chunks + chunk) * ROWS + n) * 2;
         ml[0] = ref2;
         ml[1] = l_tot;
     }
     __builtin_amdgcn_wave_barrier();
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    float *ob = a.n_chunks == 1 ? a.out + (int64_t)ph * ROWS * 128 : a.o_part + ((int64_t)ph * a.n_chunks + chunk) * ROWS * 128;
+    float *ob = a.n_chunks == 1 ? a.out + out_row0 * 128 : a.o_part + ((int64_t)pb * a.n_chunks + chunk) * ROWS * 128;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int qy = row_of(i, hf);
@@ -267,24 +280,26 @@ window_attention_kernel(WinArgs a)
     }
 }
 
-// merge of the chunks' partial results: one workgroup per (problem, head, query), one thread per output column
+// merge of the chunks' partial results: one workgroup per output row (problem, head, window query), one thread per
+// output column; the row's partial results sit in row block (head, window half) of its problem
 __global__ void __launch_bounds__(128)
-window_attention_merge_kernel(const float *o_part, const float *ml_part, int n_chunks, float *out, float *lse)
+window_attention_merge_kernel(const float *o_part, const float *ml_part, int n_chunks, int G, int W, float *out, float *lse)
 {
-    const int row = blockIdx.x;                                // (p * G + h) * W + query
-    const int ph = row / ROWS, qy = row - ph * ROWS;
+    const int row = blockIdx.x;                                // (p * G + h) * W + i
+    const int i = row % W, ph = row / W, h = ph % G, p = ph / G;
+    const int pb = (p * G + h) * (W / ROWS) + i / ROWS, qy = i % ROWS;
     float m = -INFINITY;
     for (int c = 0; c < n_chunks; ++c) {
-        const float *ml = ml_part + (((int64_t)ph * n_chunks + c) * ROWS + qy) * 2;
+        const float *ml = ml_part + (((int64_t)pb * n_chunks + c) * ROWS + qy) * 2;
         if (ml[1] > 0.f) m = fmaxf(m, ml[0]);
     }
     float acc = 0.f, z = 0.f;
     for (int c = 0; c < n_chunks; ++c) {
-        const float *ml = ml_part + (((int64_t)ph * n_chunks + c) * ROWS + qy) * 2;
+        const float *ml = ml_part + (((int64_t)pb * n_chunks + c) * ROWS + qy) * 2;
         if (ml[1] > 0.f) {
             const float w = __builtin_amdgcn_exp2f(ml[0] - m);
             z += ml[1] * w;
-            acc += o_part[(((int64_t)ph * n_chunks + c) * ROWS + qy) * 128 + threadIdx.x] * w;
+            acc += o_part[(((int64_t)pb * n_chunks + c) * ROWS + qy) * 128 + threadIdx.x] * w;
         }
     }
     out[(int64_t)row * 128 + threadIdx.x] = z > 0.f ? acc / z : 0.f;
@@ -305,10 +320,10 @@ int wa_compute_units()
 
 // keys per workgroup: whole rounds of two workgroups per CU (two wavefronts per SIMD: while one waits for its
 // LDS reads or an MFMA result the other computes), as few as keep a chunk within 131 072 keys
-void wa_plan(const Dims &d, int *chunk_len, int *n_chunks)
+void wa_plan(const Dims &d, int *chunk_len, int *n_chunks, int wgs_per_cu)
 {
     constexpr int MAX_CHUNK = 131072;
-    const int64_t cus = 2 * (int64_t)wa_compute_units();
+    const int64_t cus = wgs_per_cu * (int64_t)wa_compute_units();
     const int64_t rounds = ((int64_t)d.P * d.L + cus * MAX_CHUNK - 1) / (cus * MAX_CHUNK);
     const int64_t per_problem = std::max<int64_t>(1, (cus * rounds + d.P / 2) / d.P);
     int len = (int)(((d.L + per_problem - 1) / per_problem + SUB - 1) / SUB) * SUB;
@@ -322,15 +337,17 @@ void wa_plan(const Dims &d, int *chunk_len, int *n_chunks)
 
 bool window_attention_supported(const Dims &d)
 {
-    return d.dtype == SABLOCK_BF16 && d.D == 128 && d.G == WA_WAVES && d.W == ROWS;
+    return d.dtype == SABLOCK_BF16 && d.D == 128 &&
+           ((d.G == 4 && d.W == 32) || (d.G == 4 && d.W == 64) || (d.G == 8 && d.W == 32));
 }
 
 size_t window_attention_ws_bytes(const Dims &d)
 {
     int len, nc;
-    wa_plan(d, &len, &nc);
+    wa_plan(d, &len, &nc, d.G * d.W / ROWS == 4 ? 2 : 1);
     if (nc == 1) return 256;
-    return align256((size_t)d.P * d.G * nc * ROWS * 128 * 4) + align256((size_t)d.P * d.G * nc * ROWS * 2 * 4);
+    const size_t blocks = (size_t)d.P * (d.G * d.W / ROWS);
+    return align256(blocks * nc * ROWS * 128 * 4) + align256(blocks * nc * ROWS * 2 * 4);
 }
 
 hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, const void *v, float *out, float *lse,
@@ -338,26 +355,33 @@ hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, 
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, WA_LDS);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<4>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(4));
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<8>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(8));
         if (e != hipSuccess) return e;
         attr_done = true;
     }
+    const int nw = d.G * d.W / ROWS;                           // 4 or 8 row blocks = wavefronts per workgroup
     WinArgs a;
     a.d = d;
     a.q = static_cast<const uint16_t *>(q);
     a.k = static_cast<const uint16_t *>(k);
     a.v = static_cast<const uint16_t *>(v);
-    wa_plan(d, &a.chunk_len, &a.n_chunks);
+    // four-wavefront workgroups pair up on a CU; eight-wavefront ones already put two wavefronts on every SIMD
+    wa_plan(d, &a.chunk_len, &a.n_chunks, nw == 4 ? 2 : 1);
     a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
     a.out = out;
     a.lse = lse;
     a.o_part = static_cast<float *>(ws);
-    a.ml_part = reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.P * d.G * a.n_chunks * ROWS * 128 * 4));
-    hipLaunchKernelGGL(window_attention_kernel, dim3((unsigned)((int64_t)d.P * a.n_chunks)), dim3(WA_WAVES * 64), WA_LDS, st, a);
+    a.ml_part = reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.P * nw * a.n_chunks * ROWS * 128 * 4));
+    const dim3 grid((unsigned)((int64_t)d.P * a.n_chunks));
+    if (nw == 4) hipLaunchKernelGGL(window_attention_kernel<4>, grid, dim3(4 * 64), wa_lds(4), st, a);
+    else hipLaunchKernelGGL(window_attention_kernel<8>, grid, dim3(8 * 64), wa_lds(8), st, a);
     if (a.n_chunks > 1)
-        hipLaunchKernelGGL(window_attention_merge_kernel, dim3((unsigned)((int64_t)d.P * d.G * ROWS)), dim3(128), 0, st,
-                           a.o_part, a.ml_part, a.n_chunks, out, lse);
+        hipLaunchKernelGGL(window_attention_merge_kernel, dim3((unsigned)((int64_t)d.P * d.G * d.W)), dim3(128), 0, st,
+                           a.o_part, a.ml_part, a.n_chunks, d.G, d.W, out, lse);
     return hipGetLastError();
 }
 

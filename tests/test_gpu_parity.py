@@ -834,8 +834,8 @@ def test_ablation_switches_as_degenerate_configurations(oracle, torch_cuda):
     assert np.array_equal(run.st, run.s[:, :w.T])
 
 
-@pytest.mark.parametrize("chunk", [0, 512])
-def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, monkeypatch, chunk):
+@pytest.mark.parametrize("G,W,chunk", [(4, 32, 0), (4, 32, 512), (4, 64, 0), (4, 64, 512), (8, 32, 0), (8, 32, 1024)])
+def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, monkeypatch, G, W, chunk):
     # Attention of the window queries (the producer of row_lse) against the oracle: outputs and log-sum-exp; keys
     # planted along query rows so that the running reference moves late in the stream, inside the window and in a
     # chunk's first subtile; one chunk per problem and many (merge kernel); ragged length.  Its row_lse then drives
@@ -845,14 +845,14 @@ def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, m
 
     if chunk:
         monkeypatch.setenv("SABLOCK_WINDOW_CHUNK", str(chunk))
-    ns, nl, Hkv, G, W, D = 1, 2, 2, 4, 32, 128
+    ns, nl, Hkv, D = 1, 2, 2, 128
     L = 3 * 1024 + 77 + W
     T = L - W
     q = synth.normal_torch(808, 1, (ns, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
     k = synth.normal_torch(808, 2, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
     v = synth.normal_torch(808, 3, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
-    for (l, h, g, i, t, scale) in [(0, 0, 1, 5, 2000, 5.0), (0, 0, 1, 5, 2600, 9.0), (0, 1, 3, 31, T + 20, 6.0),
-                                   (1, 0, 0, 0, 512, 7.0), (1, 1, 2, 17, 40, 8.0)]:
+    for (l, h, g, i, t, scale) in [(0, 0, 1, 5, 2000, 5.0), (0, 0, 1, 5, 2600, 9.0), (0, 1, 3, W - 1, T + 20, 6.0),
+                                   (1, 0, 0, 0, 512, 7.0), (1, 1, G - 1, W - 15, 40, 8.0)]:
         k[0, l, h, t, :] = (q[0, l, h * G + g, i, :].float() * scale).to(torch.bfloat16)
     shape = B.make_shape(q, k, v)
     ws = torch.empty((B.sablock_window_attention_workspace_bytes(shape),), dtype=torch.uint8, device="cuda")
