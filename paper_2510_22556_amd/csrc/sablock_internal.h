@@ -129,6 +129,12 @@ hipError_t launch_segment_count(const int32_t *tok, int64_t stride, int32_t n_se
 hipError_t launch_segment_offsets(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,
                                   const SeqPtr &sp, int32_t *seg_off, hipStream_t st);
 
+// row statistics of the scoring step for 256 window-query rows per KV head with one read of K (the attention
+// kernel's first product alone): stats [P][2][row_stats_chunks][128][2] = (reference in the log2 domain, sum)
+bool row_stats_supported(const Dims &d);
+int row_stats_chunks(const Dims &d);
+hipError_t launch_row_stats(const Dims &d, const void *q, const void *k, float *stats, hipStream_t st);
+
 // attention of the window queries over all keys, with the rows' log-sum-exp (the producer of sablock_score's row_lse)
 bool window_attention_supported(const Dims &d);
 size_t window_attention_ws_bytes(const Dims &d);

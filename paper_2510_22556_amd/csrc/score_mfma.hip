@@ -1442,10 +1442,17 @@ bool score_mfma_supported(const Dims &d)
            ((d.G == 4 && (d.W == 32 || d.W == 64)) || (d.G == 8 && d.W == 32) || small_shape(d));
 }
 
+// pass 1 for 256 rows by the transposed-score kernel (csrc/window_attn.hip): K is read once instead of once per
+// block of 128 rows
+static bool stats_by_rows(const Dims &d) { return row_stats_supported(d) && !getenv("SABLOCK_STATS_PER_KEY"); }
+static size_t row_stats_bytes(const Dims &d) { return align256((size_t)d.P * 2 * row_stats_chunks(d) * M_ROWS * 2 * 4); }
+
 size_t score_mfma_ws_bytes(const Dims &d)
 {
     const Plan pl = make_plan(d);
-    return partial_bytes(d, pl) + merged_bytes(d);
+    size_t part = partial_bytes(d, pl);
+    if (row_stats_supported(d)) part = std::max(part, row_stats_bytes(d));
+    return part + merged_bytes(d);
 }
 
 hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
@@ -1486,7 +1493,22 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     SABLOCK_SMALL_SHAPES(X)
 #undef X
     dim3 grid1((unsigned)((int64_t)d.P * a.nv * pl.n_chunks));
-    if (!row_lse) {
+    if (!row_lse && stats_by_rows(d)) {
+        // a lane per window query: one read of K serves all 256 rows; the chunks of this pass are its own
+        const int nc1 = row_stats_chunks(d);
+        hipError_t e = launch_row_stats(d, q, k, a.partial, st);
+        if (e != hipSuccess) return e;
+        a.merged = a.partial;
+        a.pc = nc1;
+        if (nc1 >= MERGE_FROM) {
+            float *merged = reinterpret_cast<float *>(static_cast<char *>(ws) + row_stats_bytes(d));
+            const int n_rows = d.P * 2 * M_ROWS;
+            hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)((n_rows + 3) / 4)), dim3(256), 0, st, a.partial, merged,
+                               nc1, M_ROWS, n_rows);
+            a.merged = merged;
+            a.pc = 1;
+        }
+    } else if (!row_lse) {
         hipLaunchKernelGGL(score_mfma_stats, grid1, dim3(WAVES * 64), P1_LDS, st, a);
         launch_merge(a, d.P * a.nv, M_ROWS, st);
     }

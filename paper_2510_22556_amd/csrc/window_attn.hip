@@ -38,10 +38,11 @@ typedef void __attribute__((address_space(3))) *lptr_t;
 constexpr int SUB = 32;                        // keys per subtile
 constexpr int ROW_BYTES = 256;                 // D = 128 bf16
 constexpr int TILE_BYTES = SUB * ROW_BYTES;    // 8 KiB: one K or V subtile
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // K tile, then V tile
+// with V: a stage of the ring is a K tile then a V tile; statistics only: a K tile
+constexpr int stage_bytes(bool with_v) { return with_v ? 2 * TILE_BYTES : TILE_BYTES; }
 constexpr int NSTAGE = 4;                      // 64 KiB ring per workgroup: two workgroups (8 wavefronts) per CU
 constexpr int ROWS = 32;                       // window-query rows of a wavefront
-constexpr int wa_lds(int nw) { return NSTAGE * STAGE_BYTES + nw * ROWS * 4; }   // ring + a 32-float exchange slice per wavefront
+constexpr int wa_lds(int nw, bool with_v = true) { return NSTAGE * stage_bytes(with_v) + nw * ROWS * 4; }   // ring + a 32-float exchange slice per wavefront
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float RESCALE_AT = 64.f;
@@ -55,6 +56,7 @@ struct WinArgs {
     float *lse;                // [P][G * W] natural log
     float *o_part;             // ... or partial results [P * NW][n_chunks][32][D], unnormalised (NW row blocks per problem)
     float *ml_part;            // [P * NW][n_chunks][32][2]: reference (log2 domain), sum
+    float *stats;              // statistics-only kernel: [P][2 row blocks][n_chunks][128][2] (reference in the log2 domain, sum)
 };
 
 __device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)(lptr_t)p; }
@@ -82,25 +84,30 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // reads, one row per lane); of a V tile chunk pos ^ 4 ((row >> 1) & 3), i.e. the row's four 64-byte groups are
 // rotated by the row pair: a transposing read touches one 64-byte group of 8 consecutive rows, which then fall on
 // four different bank groups, two rows each: the two LDS passes that 512 bytes need anyway.
-template <bool IS_K>
+// FULL: the caller knows that the tile has all its 32 rows
+template <bool IS_K, bool FULL = false>
 __device__ __forceinline__ void issue_piece(const char *tile_base, int64_t row_bytes, int t0, int L, int j, int lane, uint32_t lds_dst)
 {
     const int r4 = lane >> 4, pos = lane & 15, row = 4 * j + r4;
     const uint32_t chunk = IS_K ? (uint32_t)((pos ^ row) & 15) : (uint32_t)(pos ^ (4 * ((row >> 1) & 3)));
-    if (t0 + SUB <= L) {
+    if (FULL || t0 + SUB <= L) {
         dma_1k((uint32_t)(r4 * row_bytes) + (chunk << 4), tile_base + (int64_t)(4 * j) * row_bytes, lds_dst);
     } else {
         dma_1k((uint32_t)min(row, L - t0 - 1) * (uint32_t)row_bytes + (chunk << 4), tile_base, lds_dst);
     }
 }
 
-// NW: wavefronts = 32-row blocks per problem (G * W / 32)
-template <int NW>
+// NW: wavefronts = 32-row blocks per problem (G * W / 32).
+// WITH_V = false: the row statistics alone (reference and sum of exponentials per window-query row and chunk of
+// keys), i.e. the first pass of the scoring step with ONE read of K for all 256 rows: no V tiles, no second
+// product, no output rows.
+template <int NW, bool WITH_V>
 __global__ void __launch_bounds__(NW * 64)
 window_attention_kernel(WinArgs a)
 {
-    constexpr int LOADS = 16 / NW;                             // direct-to-LDS loads per wavefront and stage (K and V pieces)
-    constexpr int KPIECES = 8 / NW;                            // of which K pieces (as many V pieces)
+    constexpr int STAGE_BYTES = stage_bytes(WITH_V);
+    constexpr int KPIECES = 8 / NW;                            // K pieces per wavefront and stage (as many V pieces)
+    constexpr int LOADS = WITH_V ? 2 * KPIECES : KPIECES;      // direct-to-LDS loads per wavefront and stage
     extern __shared__ __attribute__((aligned(8192))) char lds[];
     const Dims &d = a.d;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -113,7 +120,7 @@ window_attention_kernel(WinArgs a)
     const uint32_t ring = __builtin_amdgcn_readfirstlane(lds_addr(lds));
     float *fac = reinterpret_cast<float *>(lds + NSTAGE * STAGE_BYTES) + wave * ROWS;        // this wavefront's exchange slice
     const char *kp = reinterpret_cast<const char *>(a.k + k_problem_offset(d, p));
-    const char *vp = reinterpret_cast<const char *>(a.v + v_problem_offset(d, p));
+    const char *vp = WITH_V ? reinterpret_cast<const char *>(a.v + v_problem_offset(d, p)) : nullptr;
     const int64_t krow = d.ks[3] * 2, vrow = d.vs[3] * 2;
 
     // ---- loads: stage u % NSTAGE holds subtile u; this wavefront brings its share of the 8 K pieces and of the 8 V
@@ -126,10 +133,12 @@ window_attention_kernel(WinArgs a)
             const int j = KPIECES * wave + jj;
             issue_piece<true>(kp + (int64_t)t0 * krow, krow, t0, d.L, j, lane, st + j * 1024);
         }
+        if (WITH_V) {
 #pragma unroll
-        for (int jj = 0; jj < KPIECES; ++jj) {
-            const int j = KPIECES * wave + jj;
-            issue_piece<false>(vp + (int64_t)t0 * vrow, vrow, t0, d.L, j, lane, st + TILE_BYTES + j * 1024);
+            for (int jj = 0; jj < KPIECES; ++jj) {
+                const int j = KPIECES * wave + jj;
+                issue_piece<false>(vp + (int64_t)t0 * vrow, vrow, t0, d.L, j, lane, st + TILE_BYTES + j * 1024);
+            }
         }
     };
     for (int u = 0; u < NSTAGE - 1 && u < n_sub; ++u) issue(u);
@@ -162,14 +171,93 @@ window_attention_kernel(WinArgs a)
             v_lane[t] = (uint32_t)((4 * (g16 >> 1) + (pp >> 2)) * ROW_BYTES + 64 * (t ^ sw) + 32 * (g16 & 1) + 8 * (pp & 3));
     }
 
+    // subtiles 1 .. n_fast - 1 have no masked key, and the subtile refilled while they are worked on exists and is full
+    const int n_fast = min(min(n_sub, (d.L - lo) / SUB) - (NSTAGE - 1), (d.T - lo) / SUB);
+
     for (int u = 0; u < n_sub; ++u) {
+        if constexpr (!WITH_V) {
+            if (u == 1 && n_fast >= 3) {
+                // ---- statistics, steady state: the products of subtile v + 1 are issued before the exponentials of
+                // subtile v, in one basic block, so that the matrix pipe works in the shadow of the exponentials
+                float nrc = -r * a.c1;
+                auto products = [&](int v) -> floatx16 {
+                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+                    lds_barrier();
+                    {
+                        const int w = v + NSTAGE - 1, t0 = lo + w * SUB;
+#pragma unroll
+                        for (int jj = 0; jj < KPIECES; ++jj) {
+                            const int j = KPIECES * wave + jj;
+                            issue_piece<true, true>(kp + (int64_t)t0 * krow, krow, t0, d.L, j, lane,
+                                                    ring + (w % NSTAGE) * STAGE_BYTES + j * 1024);
+                        }
+                    }
+                    const uint32_t st = ring + (v % NSTAGE) * STAGE_BYTES;
+                    bf16x8 kb[8];
+#pragma unroll
+                    for (int s = 0; s < 8; ++s)
+                        asm volatile("ds_read_b128 %0, %1" : "=v"(kb[s]) : "v"((st + k_lane) ^ (uint32_t)(s << 5)) : "memory");
+                    asm volatile("s_waitcnt lgkmcnt(0)"
+                                 : "+v"(kb[0]), "+v"(kb[1]), "+v"(kb[2]), "+v"(kb[3]), "+v"(kb[4]), "+v"(kb[5]), "+v"(kb[6]), "+v"(kb[7])
+                                 :
+                                 : "memory");
+                    floatx16 acc;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[s], qa[s], acc, 0, 0, 0);
+                    return acc;
+                };
+                // a logit may run ahead of the reference by any amount: the reference moves before the exponentials
+                auto anchor = [&](const floatx16 &acc) {
+                    float mx = acc[0];
+#pragma unroll
+                    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, acc[i]);
+                    if (__ballot(mx > r + lim) != 0ull) {
+                        const float m2 = other_half(mx, true);
+                        if (m2 > r + lim) {
+                            l *= __builtin_amdgcn_exp2f(a.c1 * (r - m2));
+                            r = m2;
+                            nrc = -r * a.c1;
+                        }
+                    }
+                };
+                auto sums = [&](const floatx16 &acc) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) l += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i], a.c1, nrc));
+                };
+                int v = 1;
+                floatx16 sa = products(v), sb;
+                while (v + 2 < n_fast) {
+                    anchor(sa);
+                    sb = products(v + 1);
+                    sums(sa);
+                    anchor(sb);
+                    sa = products(v + 2);
+                    sums(sb);
+                    v += 2;
+                }
+                anchor(sa);
+                sums(sa);
+                u = v + 1;                                     // < n_sub: the generic step goes on from here
+            }
+        }
         // the pieces this wavefront issued for subtile u have landed (later stages: 4 loads each stay in flight) ...
         {
             static_assert(NSTAGE - 2 <= 2, "the wait below knows up to two later stages");
             const int after = min(NSTAGE - 2, n_sub - 1 - u);
-            if (after >= 2) { if (LOADS == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); }
-            else if (after == 1) { if (LOADS == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); }
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            static_assert(LOADS == 4 || LOADS == 2 || LOADS == 1, "the waits below are written out for these");
+            if (after >= 2) {
+                if (LOADS == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else if (LOADS == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+            } else if (after == 1) {
+                if (LOADS == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                else if (LOADS == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
         }
         // ... and after the barrier so have everyone's; the stage of the previous iteration is free: refill it
         lds_barrier();
@@ -214,22 +302,25 @@ window_attention_kernel(WinArgs a)
             l *= f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] -= dlt;
-            // the output rows are queries: hand the per-query factors over through LDS
-            if (hf == 0) fac[n] = f;
-            __builtin_amdgcn_wave_barrier();
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (WITH_V) {
+                // the output rows are queries: hand the per-query factors over through LDS
+                if (hf == 0) fac[n] = f;
+                __builtin_amdgcn_wave_barrier();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float fi = fac[row_of(i, hf)];
+                for (int i = 0; i < 16; ++i) {
+                    const float fi = fac[row_of(i, hf)];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) o[t][i] *= fi;
+                    for (int t = 0; t < 4; ++t) o[t][i] *= fi;
+                }
+                __builtin_amdgcn_wave_barrier();
             }
-            __builtin_amdgcn_wave_barrier();
         }
         // ---- probabilities relative to the reference, their sum, and the two A operands of O += P V
         float pr[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) { pr[i] = __builtin_amdgcn_exp2f(acc[i] * a.c1); l += pr[i]; }
+        if (!WITH_V) continue;
         bf16x8 pa[2];
 #pragma unroll
         for (int s = 0; s < 2; ++s)
@@ -255,6 +346,18 @@ window_attention_kernel(WinArgs a)
     // unnormalised with (reference, sum) for the merge
     const float l_tot = other_half(l, false);
     const float ref2 = r * a.c1;                               // log2 domain
+    if (!WITH_V) {
+        // where the column pass for 256 rows looks for a row's statistics: two blocks of 128 rows per problem
+        // (W = 64: the window halves, rows head * 32 + query; G = 8: heads 0-3 and 4-7)
+        const int blk = d.W > ROWS ? qoff / ROWS : head / 4;
+        const int row = d.W > ROWS ? head * ROWS + n : (head & 3) * ROWS + n;
+        if (hf == 0) {
+            float *o2 = a.stats + ((((int64_t)p * 2 + blk) * a.n_chunks + chunk) * 128 + row) * 2;
+            o2[0] = ref2;
+            o2[1] = l_tot;
+        }
+        return;
+    }
     const int pb = p * NW + wave;                              // (problem, row block)
     const int64_t out_row0 = ((int64_t)p * d.G + head) * d.W + qoff;           // first output row of this block
     if (a.n_chunks == 1) {
@@ -335,6 +438,42 @@ void wa_plan(const Dims &d, int *chunk_len, int *n_chunks, int wgs_per_cu)
 
 }  // namespace
 
+// ---- the statistics alone for 256 window-query rows per KV head, as the first pass of the scoring step
+bool row_stats_supported(const Dims &d)
+{
+    return d.dtype == SABLOCK_BF16 && d.D == 128 && ((d.G == 4 && d.W == 64) || (d.G == 8 && d.W == 32));
+}
+
+int row_stats_chunks(const Dims &d)
+{
+    int len, nc;
+    wa_plan(d, &len, &nc, 2);                                  // 32 KiB rings: two 8-wavefront workgroups per CU
+    return nc;
+}
+
+hipError_t launch_row_stats(const Dims &d, const void *q, const void *k, float *stats, hipStream_t st)
+{
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<8, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(8, false));
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    WinArgs a;
+    a.d = d;
+    a.q = static_cast<const uint16_t *>(q);
+    a.k = static_cast<const uint16_t *>(k);
+    a.v = nullptr;
+    wa_plan(d, &a.chunk_len, &a.n_chunks, 2);
+    a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
+    a.out = a.lse = a.o_part = a.ml_part = nullptr;
+    a.stats = stats;
+    hipLaunchKernelGGL((window_attention_kernel<8, false>), dim3((unsigned)((int64_t)d.P * a.n_chunks)), dim3(8 * 64),
+                       wa_lds(8, false), st, a);
+    return hipGetLastError();
+}
+
 bool window_attention_supported(const Dims &d)
 {
     return d.dtype == SABLOCK_BF16 && d.D == 128 &&
@@ -355,10 +494,10 @@ hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, 
 {
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<4>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<4, true>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(4));
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<8>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<8, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(8));
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -377,8 +516,9 @@ hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, 
     a.o_part = static_cast<float *>(ws);
     a.ml_part = reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.P * nw * a.n_chunks * ROWS * 128 * 4));
     const dim3 grid((unsigned)((int64_t)d.P * a.n_chunks));
-    if (nw == 4) hipLaunchKernelGGL(window_attention_kernel<4>, grid, dim3(4 * 64), wa_lds(4), st, a);
-    else hipLaunchKernelGGL(window_attention_kernel<8>, grid, dim3(8 * 64), wa_lds(8), st, a);
+    a.stats = nullptr;
+    if (nw == 4) hipLaunchKernelGGL((window_attention_kernel<4, true>), grid, dim3(4 * 64), wa_lds(4), st, a);
+    else hipLaunchKernelGGL((window_attention_kernel<8, true>), grid, dim3(8 * 64), wa_lds(8), st, a);
     if (a.n_chunks > 1)
         hipLaunchKernelGGL(window_attention_merge_kernel, dim3((unsigned)((int64_t)d.P * d.G * d.W)), dim3(128), 0, st,
                            a.o_part, a.ml_part, a.n_chunks, d.G, d.W, out, lse);
