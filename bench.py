@@ -235,6 +235,34 @@ def main():
         result["layer_by_layer"] = {"ms_per_step": dt3 * 1e3, "ms_per_layer": dt3 * 1e3 / w.n_layers,
                                     "value": w.n_seq * w.seq_len * w.n_layers / dt3}
         del buf_l
+        # the same calls with the layers dealt out to three streams, each with its own buffers: a layer's small
+        # selection kernels (latency bound, few workgroups) then run beside the next layers' scoring, the way a
+        # prefill loop can overlap a layer's compression with the next layer's forward pass
+        n_str = 3
+        streams = [torch.cuda.Stream() for _ in range(n_str)]
+        bufs = [B.Buffers(shape_l, seg, budget, dev, append_window=True) for _ in range(n_str)]
+
+        def layer_calls_streams():
+            for l in range(w.n_layers):
+                st, bl = streams[l % n_str], bufs[l % n_str]
+                ql, kl, vl = q[:, l:l + 1], k[:, l:l + 1], v[:, l:l + 1]
+                B.sablock_score(shape_l, ql, kl, bl.s, bl.ent, bl.ws, w.eps, stream=st)
+                B.sablock_refine(shape_l, bl.s, bl.ent, seg, bl.s_tilde, bl.ws, w.alpha, w.eta, bl.omega, stream=st)
+                B.sablock_search_select(shape_l, bl.s_tilde, seg, w.cand, budget, w.tau, bl.seg_budget,
+                                        bl.block_size, bl.idx, bl.n_sel, bl.ws, stream=st, topb_out=bl.topb)
+                B.sablock_compact(shape_l, kl, vl, bl.idx, bl.n_sel, budget, True, bl.k_out, bl.v_out, stream=st)
+
+        torch.cuda.synchronize()
+        layer_calls_streams()
+        torch.cuda.synchronize()
+        t4 = time.perf_counter()
+        for _ in range(5):
+            layer_calls_streams()
+        torch.cuda.synchronize()
+        dt4 = (time.perf_counter() - t4) / 5
+        result["layer_by_layer"]["three_streams"] = {"ms_per_step": dt4 * 1e3, "ms_per_layer": dt4 * 1e3 / w.n_layers,
+                                                    "value": w.n_seq * w.seq_len * w.n_layers / dt4}
+        del bufs, streams
     # a plain device copy on the same box as a second yardstick (reads and writes 1 GiB each)
     src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
     dst = torch.empty_like(src)

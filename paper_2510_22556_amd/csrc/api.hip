@@ -107,6 +107,7 @@ sablock_status sablock_workspace_bytes(const sablock_shape *shape, int32_t max_s
     size_t b = score_ws(d);
     size_t c = search_ws_bytes(d, max_segments, budget); if (c > b) b = c;
     c = select_ws_bytes(d, max_segments, budget); if (c > b) b = c;
+    c = search_select_ws_bytes(d, max_segments, budget); if (c > b) b = c;
     *bytes_out = b + 256;
     return SABLOCK_OK;
 }

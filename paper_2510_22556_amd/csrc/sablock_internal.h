@@ -129,6 +129,19 @@ hipError_t launch_segment_count(const int32_t *tok, int64_t stride, int32_t n_se
 hipError_t launch_segment_offsets(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,
                                   const SeqPtr &sp, int32_t *seg_off, hipStream_t st);
 
+// compute units of the current device (256 when no device can be asked, e.g. for sizes computed without a GPU)
+inline int device_compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        cus = n;
+    }
+    return cus;
+}
+
 // row statistics of the scoring step for 256 window-query rows per KV head with one read of K (the attention
 // kernel's first product alone): stats [P][2][row_stats_chunks][128][2] = (reference in the log2 domain, sum)
 bool row_stats_supported(const Dims &d);

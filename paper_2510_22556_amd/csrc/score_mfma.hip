@@ -1381,17 +1381,7 @@ struct Plan {
 
 constexpr int MERGE_FROM = 8;       // chunks per problem from which the separate fold pays
 
-int compute_units()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-            n = 256;
-        cus = n;
-    }
-    return cus;
-}
+int compute_units() { return device_compute_units(); }
 
 Plan make_plan(const Dims &d)
 {

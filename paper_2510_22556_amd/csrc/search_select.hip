@@ -28,6 +28,9 @@
 // the work is spread over lanes.  Rankings use (value descending, index ascending).
 #include "sablock_internal.h"
 
+#include <algorithm>
+#include <cstdlib>
+
 namespace sablock {
 namespace {
 
@@ -212,7 +215,82 @@ struct PlanArgs {
     SegRec *list, *list_long;
     int capacity;
     int32_t *idx_out, *n_sel_out;
+    // results of the sliced passes over the rows (null: the workgroup scans its row itself)
+    const uint32_t *pre_hist;    // [P][4096] histogram of the keys' top 12 bits
+    const int32_t *pre_cnt;      // [P][2] entries of pre_hit, pre_cand
+    const int32_t *pre_hit;      // [P][TB_HITS] tokens of the bins above the threshold's bin
+    const uint32_t *pre_cand;    // [P][TB_CAND][2] (key, token) of the threshold's bin
 };
+
+// ---- the two passes over the rows with several workgroups per row (few problems in a call: one workgroup per
+// row leaves most of the chip idle and is bound by the latency of its own loads).  grid (slices, P).
+__device__ inline void slice_of_row(int T, int n_slices, int sl, int &a, int &b)
+{
+    const int per = ((T + n_slices - 1) / n_slices + 3) & ~3;
+    a = min(sl * per, T);
+    b = min(a + per, T);
+}
+
+// pass A: histogram of the top 12 key bits of a slice, added to the row's histogram (zero on entry)
+__global__ void __launch_bounds__(TB_THREADS)
+topb_hist_kernel(Dims d, const float *s_tilde, uint32_t *g_hist)
+{
+    __shared__ uint32_t hist[4096];
+    const int p = blockIdx.y, tid = threadIdx.x;
+    int a, b;
+    slice_of_row(d.T, gridDim.x, blockIdx.x, a, b);
+    for (int i = tid; i < 4096; i += TB_THREADS) hist[i] = 0;
+    __syncthreads();
+    scan_row(s_tilde + (int64_t)p * d.T + a, b - a, tid, [&](int, float v) { atomicAdd(&hist[ordered_key(v) >> 20], 1u); });
+    __syncthreads();
+    for (int i = tid; i < 4096; i += TB_THREADS) {
+        const uint32_t c = hist[i];
+        if (c) atomicAdd(&g_hist[(int64_t)p * 4096 + i], c);
+    }
+}
+
+// pass B: every workgroup finds the threshold's bin from the row's histogram, splits its slice into sure Top-B
+// tokens and candidates in LDS, reserves room in the row's two lists with one atomic each and copies them there.
+// Does nothing when the lists cannot hold the row's entries (the per-row kernel then makes its own passes).
+__global__ void __launch_bounds__(TB_THREADS)
+topb_split_kernel(Dims d, const float *s_tilde, int budget, const uint32_t *g_hist, int32_t *g_cnt, int32_t *g_hit,
+                  uint32_t *g_cand)
+{
+    __shared__ uint32_t hist[4096];              // the row's histogram, then this slice's sure tokens
+    __shared__ uint32_t lc_key[TB_CAND];
+    __shared__ int32_t lc_idx[TB_CAND];
+    __shared__ int sh_nhit, sh_ncand, sh_base[2];
+    __shared__ uint32_t sh_pair[2];
+    const int p = blockIdx.y, tid = threadIdx.x, T = d.T;
+    const int k = min(budget, T);
+    int a, b;
+    slice_of_row(T, gridDim.x, blockIdx.x, a, b);
+    for (int i = tid; i < 4096; i += TB_THREADS) hist[i] = g_hist[(int64_t)p * 4096 + i];
+    if (tid == 0) { sh_nhit = 0; sh_ncand = 0; }
+    __syncthreads();
+    uint32_t bin, above;
+    find_bin_from_top(hist, 4096, (uint32_t)k, sh_pair, bin, above);
+    const uint32_t n_bin = hist[bin];
+    __syncthreads();                             // hist is reused below
+    if (!(n_bin <= (uint32_t)TB_CAND && k <= TB_HITS)) return;
+    int32_t *lc_hit = reinterpret_cast<int32_t *>(hist);
+    scan_row(s_tilde + (int64_t)p * T + a, b - a, tid, [&](int t, float v) {
+        const uint32_t key = ordered_key(v);
+        const uint32_t kb = key >> 20;
+        if (kb > bin) lc_hit[atomicAdd(&sh_nhit, 1)] = a + t;
+        else if (kb == bin) { const int c = atomicAdd(&sh_ncand, 1); lc_key[c] = key; lc_idx[c] = a + t; }
+    });
+    __syncthreads();
+    if (tid == 0) sh_base[0] = sh_nhit > 0 ? atomicAdd(&g_cnt[2 * p], sh_nhit) : 0;
+    if (tid == 64) sh_base[1] = sh_ncand > 0 ? atomicAdd(&g_cnt[2 * p + 1], sh_ncand) : 0;
+    __syncthreads();
+    for (int i = tid; i < sh_nhit; i += TB_THREADS) g_hit[(int64_t)p * TB_HITS + sh_base[0] + i] = lc_hit[i];
+    for (int i = tid; i < sh_ncand; i += TB_THREADS) {
+        uint32_t *dst = g_cand + ((int64_t)p * TB_CAND + sh_base[1] + i) * 2;
+        dst[0] = lc_key[i];
+        dst[1] = (uint32_t)lc_idx[i];
+    }
+}
 
 template <bool PLAN>
 __global__ void __launch_bounds__(TB_THREADS)
@@ -249,9 +327,14 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         cut = -1;
     } else if (k < T) {
         // ---- pass A: top 12 bits
-        for (int i = tid; i < 4096; i += TB_THREADS) hist[i] = 0;
-        __syncthreads();
-        scan_row(sp, T, tid, [&](int, float v) { atomicAdd(&hist[ordered_key(v) >> 20], 1u); });
+        const bool sliced = PLAN && pa.pre_hist;               // the passes over the row were made by sliced kernels
+        if (sliced) {
+            for (int i = tid; i < 4096; i += TB_THREADS) hist[i] = pa.pre_hist[(int64_t)p * 4096 + i];
+        } else {
+            for (int i = tid; i < 4096; i += TB_THREADS) hist[i] = 0;
+            __syncthreads();
+            scan_row(sp, T, tid, [&](int, float v) { atomicAdd(&hist[ordered_key(v) >> 20], 1u); });
+        }
         __syncthreads();
         uint32_t bin, above;
         find_bin_from_top(hist, 4096, krem, sh_pair, bin, above);
@@ -259,14 +342,25 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         __syncthreads();                       // hist is reused below
         if (n_bin <= (uint32_t)TB_CAND && k <= TB_HITS) {
             // ---- pass B: split the row into sure Top-B tokens and candidates
-            if (tid == 0) { sh_nhit = 0; sh_ncand = 0; }
-            __syncthreads();
-            scan_row(sp, T, tid, [&](int t, float v) {
-                const uint32_t key = ordered_key(v);
-                const uint32_t kb = key >> 20;
-                if (kb > bin) sh_hit[atomicAdd(&sh_nhit, 1)] = t;
-                else if (kb == bin) { const int c = atomicAdd(&sh_ncand, 1); cand_key[c] = key; cand_idx[c] = t; }
-            });
+            if (sliced) {
+                const int nh = pa.pre_cnt[2 * p], nc = pa.pre_cnt[2 * p + 1];
+                for (int i = tid; i < nh; i += TB_THREADS) sh_hit[i] = pa.pre_hit[(int64_t)p * TB_HITS + i];
+                for (int i = tid; i < nc; i += TB_THREADS) {
+                    const uint32_t *src = pa.pre_cand + ((int64_t)p * TB_CAND + i) * 2;
+                    cand_key[i] = src[0];
+                    cand_idx[i] = (int32_t)src[1];
+                }
+                if (tid == 0) { sh_nhit = nh; sh_ncand = nc; }
+            } else {
+                if (tid == 0) { sh_nhit = 0; sh_ncand = 0; }
+                __syncthreads();
+                scan_row(sp, T, tid, [&](int t, float v) {
+                    const uint32_t key = ordered_key(v);
+                    const uint32_t kb = key >> 20;
+                    if (kb > bin) sh_hit[atomicAdd(&sh_nhit, 1)] = t;
+                    else if (kb == bin) { const int c = atomicAdd(&sh_ncand, 1); cand_key[c] = key; cand_idx[c] = t; }
+                });
+            }
             __syncthreads();
             const int ncand = sh_ncand;
             krem -= above;
@@ -729,6 +823,14 @@ __global__ void reset_counters_kernel(int32_t *counters)
     if (threadIdx.x < 3) counters[threadIdx.x] = 0;
 }
 
+// counters of the call's lists, and the rows' histograms and list lengths of the sliced Top-B passes
+__global__ void __launch_bounds__(256)
+reset_sliced_kernel(int32_t *counters, uint32_t *words, int64_t n_words)
+{
+    if (blockIdx.x == 0 && threadIdx.x < 3) counters[threadIdx.x] = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (int64_t)gridDim.x * 256) words[i] = 0u;
+}
+
 // One workgroup per problem: exclusive prefix of b_k over its segments (where each segment's tokens go in the
 // problem's idx_out row), n_sel, the -1 padding of idx_out.  The segments that retain anything are appended to
 // one of the call's three select lists: token-level ones (g_k* = 1) to `light`, the others to `full` or, when
@@ -1013,10 +1115,28 @@ bool search_select_fused(const Dims &d, const SegView &sv, int32_t budget)
     return budget > 0 && budget < d.T && budget <= TB_HITS && sv.max_segments + 1 <= TB_OFFS;
 }
 
+// Workgroups per row for the two Top-B passes of the one-call form: with few problems in a call (a layer at a
+// time) one workgroup per row would leave most of the chip idle.  1: the per-row kernel scans its row itself.
+static int topb_slices(const Dims &d)
+{
+    if (const char *e = getenv("SABLOCK_TOPB_SLICES")) {
+        const int v = atoi(e);
+        if (v >= 1 && v <= 64) return (int64_t)v * 4096 <= d.T ? v : 1;
+    }
+    int s = (int)std::min<int64_t>(16, (int64_t)device_compute_units() / std::max(d.P, 1));
+    s = std::min(s, d.T / 8192);                               // a slice is worth a workgroup from 8 192 tokens on
+    return s >= 2 ? s : 1;
+}
+static size_t sliced_words(const Dims &d) { return (size_t)d.P * (4096 + 2); }          // histograms, then list lengths
+static size_t sliced_bytes(const Dims &d)
+{
+    return align256(sliced_words(d) * 4) + align256((size_t)d.P * TB_HITS * 4) + align256((size_t)d.P * TB_CAND * 8);
+}
+
 size_t search_select_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget)
 {
     const size_t a = search_ws_bytes(d, max_segments, budget), b = select_ws_bytes(d, max_segments, budget);
-    return a > b ? a : b;
+    return (a > b ? a : b) + (topb_slices(d) > 1 ? sliced_bytes(d) : 0);
 }
 
 hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
@@ -1041,8 +1161,31 @@ hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegVi
     SegRec *list = reinterpret_cast<SegRec *>(w);
     w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
     SegRec *list_long = reinterpret_cast<SegRec *>(w);
-    hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, counters);
-    PlanArgs pa{list, list_long, (int)cap, idx_out, n_sel_out};
+    PlanArgs pa{list, list_long, (int)cap, idx_out, n_sel_out, nullptr, nullptr, nullptr, nullptr};
+    const int n_slices = topb_slices(d);
+    if (n_slices > 1) {
+        // behind the larger of the search and select layouts
+        const size_t base = search_select_ws_bytes(d, sv.max_segments, budget) - sliced_bytes(d);
+        char *x = static_cast<char *>(ws) + base;
+        uint32_t *g_hist = reinterpret_cast<uint32_t *>(x);
+        int32_t *g_cnt = reinterpret_cast<int32_t *>(g_hist + (size_t)d.P * 4096);
+        x += align256(sliced_words(d) * 4);
+        int32_t *g_hit = reinterpret_cast<int32_t *>(x);
+        x += align256((size_t)d.P * TB_HITS * 4);
+        uint32_t *g_cand = reinterpret_cast<uint32_t *>(x);
+        const int64_t n_words = (int64_t)sliced_words(d);
+        hipLaunchKernelGGL(reset_sliced_kernel, dim3((unsigned)std::min<int64_t>((n_words + 1023) / 1024, 1024)), dim3(256), 0, st,
+                           counters, g_hist, n_words);
+        hipLaunchKernelGGL(topb_hist_kernel, dim3(n_slices, d.P), dim3(TB_THREADS), 0, st, d, s_tilde, g_hist);
+        hipLaunchKernelGGL(topb_split_kernel, dim3(n_slices, d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, g_hist, g_cnt,
+                           g_hit, g_cand);
+        pa.pre_hist = g_hist;
+        pa.pre_cnt = g_cnt;
+        pa.pre_hit = g_hit;
+        pa.pre_cand = g_cand;
+    } else {
+        hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, counters);
+    }
     hipLaunchKernelGGL(topb_kernel<true>, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, sv, seg_budget,
                        block_size, counters, pa);
     if (cap > 0) {

@@ -409,17 +409,7 @@ window_attention_merge_kernel(const float *o_part, const float *ml_part, int n_c
     if (threadIdx.x == 0) lse[row] = (m + __builtin_amdgcn_logf(z)) * LN2;
 }
 
-int wa_compute_units()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, nn = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&nn, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || nn < 1)
-            nn = 256;
-        cus = nn;
-    }
-    return cus;
-}
+int wa_compute_units() { return device_compute_units(); }
 
 // keys per workgroup: whole rounds of two workgroups per CU (two wavefronts per SIMD: while one waits for its
 // LDS reads or an MFMA result the other computes), as few as keep a chunk within 131 072 keys

@@ -178,6 +178,32 @@ def test_search_select_with_ties_bit_exact(oracle, torch_cuda, seed):
     _assert_search_select(oracle, torch_cuda, st, off, cand, budget, [0.85, 0.5, 1.0][seed % 3])
 
 
+@pytest.mark.parametrize("slices", [2, 3, 5])
+@pytest.mark.parametrize("levels", [0, 1, 300])
+def test_topb_passes_sliced_over_several_workgroups(oracle, torch_cuda, monkeypatch, slices, levels):
+    # With few problems in a call the two Top-B passes over a row are split over several workgroups (slices of the
+    # row, results merged through global lists).  Forced here on a small call: continuous scores, scores on 300
+    # levels (ties at the threshold), and scores that are 0 or 1 with fewer ones than the budget (the threshold's
+    # bin, the zeros, overflows the candidate list, so the per-row kernel falls back to its own passes, and the cut
+    # among the ties is by index).  Same bits as the unsliced call, and as the oracle.
+    rng = np.random.default_rng(4200 + levels)
+    T, P = 20491, 3
+    st = rng.random((P, T)) ** 6
+    if levels:
+        st = np.round(st * levels) / levels
+    lens = rng.integers(1, 90, size=T)
+    off = np.unique(np.minimum(np.concatenate([[0], np.cumsum(lens)]), T)).astype(np.int32)
+    cand, budget, tau = [1, 2, 4, 8, 16, 32], 3000, 0.85
+    if levels == 1:
+        assert (st == 1).sum(axis=1).max() < budget
+    monkeypatch.setenv("SABLOCK_TOPB_SLICES", "1")
+    ref = _search_select_gpu(torch_cuda, st, off, cand, budget, tau)
+    monkeypatch.setenv("SABLOCK_TOPB_SLICES", str(slices))
+    got = _assert_search_select(oracle, torch_cuda, st, off, cand, budget, tau)
+    for a, b in zip(ref, got):
+        np.testing.assert_array_equal(a, b)
+
+
 def test_search_select_degenerate_cases(oracle, torch_cuda):
     torch = torch_cuda
     rng = np.random.default_rng(5)
@@ -758,6 +784,43 @@ def test_whole_path_replays_in_a_hip_graph(torch_cuda):
         torch.cuda.synchronize()
         for name, a, b in zip("s ent s_tilde seg_budget block_size idx n_sel k_out v_out".split(), eager, outs()):
             assert torch.equal(a, b), f"replay {rep}: {name} differs from the eager run"
+
+
+def test_layers_overlapped_on_several_streams(torch_cuda):
+    # A prefill loop calls the path layer by layer and may overlap layers on different streams, each with its own
+    # buffers: nothing in the library is shared between calls, so every layer must come out bit for bit as when
+    # the same per-layer calls run one after the other on one stream.
+    import dataclasses
+
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    w = dataclasses.replace(synth.WORKLOADS["llama8b_8k"], n_layers=6)
+    q, k, v = synth.device_tensors(w, "cuda")
+    off, ptr = synth.workload_segments(w)
+    seg = B.make_segments(off, ptr, "cuda")
+    budget = w.budget()
+    shape_l = B.make_shape(q[:, :1], k[:, :1], v[:, :1])
+    names = "s ent s_tilde seg_budget block_size idx n_sel k_out v_out".split()
+
+    def run(streams):
+        bufs = [B.Buffers(shape_l, seg, budget, "cuda", True) for _ in range(w.n_layers)]
+        for st in streams:
+            st.wait_stream(torch.cuda.current_stream())
+        for rep in range(2):
+            for l in range(w.n_layers):
+                B.compress(shape_l, q[:, l:l + 1], k[:, l:l + 1], v[:, l:l + 1], seg, w.cand, budget, bufs[l], w.eps,
+                           w.alpha, w.eta, w.tau, stream=streams[l % len(streams)])
+        torch.cuda.synchronize()
+        return bufs
+
+    one = run([torch.cuda.current_stream()])
+    many = run([torch.cuda.Stream() for _ in range(3)])
+    assert not torch.equal(one[0].idx, one[1].idx)             # the layers do differ
+    for l in range(w.n_layers):
+        assert int(many[l].n_sel.min()) == budget
+        for name in names:
+            assert torch.equal(getattr(one[l], name), getattr(many[l], name)), f"layer {l}: {name}"
 
 
 def test_maximum_problem_count_per_call(oracle, torch_cuda):
