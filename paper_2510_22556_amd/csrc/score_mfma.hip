@@ -281,6 +281,12 @@ __device__ __forceinline__ floatx16 load_cref(const float *cref, int h, int hf)
     return *reinterpret_cast<const floatx16 *>(cref + h * 32 + hf * 16);
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
 // careful reduction of one 32-row tile of the subtile whose lane key is t; qf(i) = window query of register i
 template <typename QF>
 __device__ __forceinline__ void stats_tile_careful(const floatx16 &acc, float (&z)[16], float *cref_h, float c1, bool first,
@@ -299,9 +305,14 @@ __device__ __forceinline__ void stats_tile_careful(const floatx16 &acc, float (&
         const float inv_c1 = 1.0f / c1;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            float rm = dd[i];                                   // row maximum over the 32 lanes of this half
-#pragma unroll
-            for (int o = 16; o > 0; o >>= 1) rm = fmaxf(rm, __shfl_xor(rm, o));
+            // row maximum over the 32 lanes of this half: four DPP steps inside each row of 16 lanes (lane ^ 1,
+            // lane ^ 2, mirror inside 8, mirror inside 16), then the other row of the half
+            float rm = dd[i];
+            rm = fmaxf(rm, dpp_f<0xB1>(rm));
+            rm = fmaxf(rm, dpp_f<0x4E>(rm));
+            rm = fmaxf(rm, dpp_f<0x141>(rm));
+            rm = fmaxf(rm, dpp_f<0x140>(rm));
+            rm = fmaxf(rm, __shfl_xor(rm, 16));
             const bool move = first ? (rm > -INFINITY) : (rm > RESCALE_AT);
             const float cshift = move ? rm * inv_c1 : 0.f;      // change of the C operand
             const float shift = cshift * c1;                    // and the matching change of the exponent
