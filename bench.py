@@ -109,6 +109,8 @@ def main():
     ap.add_argument("--headline-only", action="store_true",
                     help="only the timed steps and the stage breakdown (profiling runs: keeps the other entries' "
                          "launches of the same kernels out of the per-kernel averages)")
+    ap.add_argument("--layer-by-layer-only", action="store_true",
+                    help="only the per-layer calls on one stream (profiling runs: the kernels of that mode alone)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="first run a plain device copy of this many MiB (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -144,6 +146,31 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     names = ["score", "refine", "search_select", "compact"]
+
+    if args.layer_by_layer_only:
+        shape_l = B.make_shape(q[:, :1], k[:, :1], v[:, :1])
+        buf_l = B.Buffers(shape_l, seg, budget, dev, append_window=True)
+
+        def layer_calls_only():
+            for l in range(w.n_layers):
+                ql, kl, vl = q[:, l:l + 1], k[:, l:l + 1], v[:, l:l + 1]
+                B.sablock_score(shape_l, ql, kl, buf_l.s, buf_l.ent, buf_l.ws, w.eps)
+                B.sablock_refine(shape_l, buf_l.s, buf_l.ent, seg, buf_l.s_tilde, buf_l.ws, w.alpha, w.eta, buf_l.omega)
+                B.sablock_search_select(shape_l, buf_l.s_tilde, seg, w.cand, budget, w.tau, buf_l.seg_budget,
+                                        buf_l.block_size, buf_l.idx, buf_l.n_sel, buf_l.ws, topb_out=buf_l.topb)
+                B.sablock_compact(shape_l, kl, vl, buf_l.idx, buf_l.n_sel, budget, True, buf_l.k_out, buf_l.v_out)
+
+        for _ in range(args.warmup):
+            layer_calls_only()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            layer_calls_only()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        print(json.dumps({"workload": w.name, "layer_by_layer": {"ms_per_step": dt * 1e3, "ms_per_layer": dt * 1e3 / w.n_layers,
+                                                                 "value": w.n_seq * w.seq_len * w.n_layers / dt}}))
+        return
 
     def step(events=None, score_only_events=None):
         def mark(i):
