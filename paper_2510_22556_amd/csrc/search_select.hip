@@ -117,7 +117,8 @@ __device__ inline double add_in_order(double acc, unsigned long long mask, float
 
 // ------------------------------------------------------------------ Top-B
 constexpr int TB_THREADS = 1024;
-constexpr int TB_OFFS = 4096;              // segment offsets and per-segment counts kept in LDS while the implicit budgets are counted
+constexpr int TB_OFFS = 4096;              // segment offsets and per-segment counts kept in LDS while the implicit budgets are counted:
+constexpr int TB_OFFS_MAX = 16384;         // the launch picks 4 096, 8 192 or 16 384 entries (dynamic LDS: two int32 arrays of that size)
 constexpr int TB_HITS = 4096;              // Top-B tokens collected in LDS before they are assigned to segments
 constexpr int TB_CAND = 4096;              // tokens of the threshold's 12-bit bin that the LDS candidate list holds
 
@@ -207,7 +208,7 @@ __device__ inline void find_bin_from_top(const uint32_t *hist, int nbins, uint32
 // Ties at the threshold are cut by ascending index with one ordered pass over the row.
 //
 // PLAN (the search that also selects; the host launches it only when 0 < B < T, B <= TB_HITS and every sequence
-// has fewer than TB_OFFS segments, so the Top-B tokens and the segment counters are in LDS): the same workgroup
+// has fewer than `offs_cap` segments, so the Top-B tokens and the segment counters are in LDS): the same workgroup
 // goes on to the exclusive prefix of b_k (each segment's offset in the problem's idx_out row), writes n_sel, the
 // single token of every segment with b_k == 1 (g_k* = 1) straight to its place, and appends the segments with
 // b_k >= 2 to the call's search lists with their output offset.  `counter` must then be zero on entry.
@@ -295,11 +296,11 @@ topb_split_kernel(Dims d, const float *s_tilde, int budget, const uint32_t *g_hi
 template <bool PLAN>
 __global__ void __launch_bounds__(TB_THREADS)
 topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, int32_t *seg_budget,
-            int32_t *block_size, int32_t *counter, PlanArgs pa)
+            int32_t *block_size, int32_t *counter, PlanArgs pa, int offs_cap)
 {
     __shared__ uint32_t hist[TB_HITS];           // pass-A histogram (4096 bins), later the list of Top-B tokens
     __shared__ uint32_t hist2[2048];             // histograms of the later passes
-    __shared__ int32_t sh_u[2 * TB_OFFS];        // candidates (key, index) during selection, then offsets and counters
+    extern __shared__ int32_t sh_u[];            // [2][offs_cap]: candidates (key, index) during selection, then offsets and counters
     __shared__ int sh_nhit, sh_ncand;
     __shared__ uint32_t sh_pair[2];
     __shared__ int sh_wcnt[TB_THREADS / 64];
@@ -307,8 +308,8 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
     static_assert(TB_HITS == 4096 && TB_CAND <= TB_OFFS, "LDS regions are shared between phases");
     int32_t *sh_hit = reinterpret_cast<int32_t *>(hist);
     uint32_t *cand_key = reinterpret_cast<uint32_t *>(sh_u);
-    int32_t *cand_idx = sh_u + TB_OFFS;
-    int32_t *sh_off = sh_u, *sh_cnt = sh_u + TB_OFFS;
+    int32_t *cand_idx = sh_u + offs_cap;
+    int32_t *sh_off = sh_u, *sh_cnt = sh_u + offs_cap;
     const int p = blockIdx.x, T = d.T;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *sp = s_tilde + (int64_t)p * T;
@@ -456,7 +457,7 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         __syncthreads();
         have_hits = true;
     }
-    if (have_hits && K + 1 <= TB_OFFS) {
+    if (have_hits && K + 1 <= offs_cap) {
         // assign the listed tokens to segments in parallel: binary search on an LDS copy of the offsets, LDS counters
         for (int j = tid; j <= K; j += TB_THREADS) { sh_off[j] = off[j]; sh_cnt[j] = 0; }
         __syncthreads();
@@ -464,13 +465,15 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         __syncthreads();
         for (int j = tid; j < K; j += TB_THREADS) seg_budget[row + j] = sh_cnt[j];
         if (PLAN) {
-            // exclusive prefix of the counters in place (K + 1 entries: b_k = pos[k + 1] - pos[k]); four
+            // exclusive prefix of the counters in place (K + 1 entries: b_k = pos[k + 1] - pos[k]); offs_cap / 1024
             // consecutive entries per thread, wavefront scan, then the sixteen wavefront totals
             __syncthreads();
-            const int j0 = 4 * tid;
-            int c[4], tot = 0;
+            constexpr int PER_MAX = TB_OFFS_MAX / TB_THREADS;
+            const int per = offs_cap / TB_THREADS;
+            const int j0 = per * tid;
+            int c[PER_MAX], tot = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { c[i] = j0 + i < K ? sh_cnt[j0 + i] : 0; tot += c[i]; }
+            for (int i = 0; i < PER_MAX; ++i) { c[i] = (i < per && j0 + i < K) ? sh_cnt[j0 + i] : 0; tot += c[i]; }
             int incl = tot;
             for (int o = 1; o < 64; o <<= 1) { const int x = __shfl_up(incl, o); if (lane >= o) incl += x; }
             if (lane == 63) sh_wcnt[wave] = incl;
@@ -478,7 +481,7 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
             int run = incl - tot;
             for (int w = 0; w < wave; ++w) run += sh_wcnt[w];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { if (j0 + i <= K) sh_cnt[j0 + i] = run; run += c[i]; }
+            for (int i = 0; i < PER_MAX; ++i) { if (i < per && j0 + i <= K) sh_cnt[j0 + i] = run; run += c[i]; }
             __syncthreads();
             int32_t *out = pa.idx_out + (int64_t)p * budget;
             if (tid == 0) pa.n_sel_out[p] = k;                 // k = B < T here, so there is nothing to pad
@@ -1005,12 +1008,14 @@ select_kernel(Dims d, const float *s_tilde, const int32_t *thr, const SegRec *li
 
 }  // namespace
 
+static size_t topb_lds(int offs_cap) { return (size_t)2 * offs_cap * sizeof(int32_t); }
+
 hipError_t launch_topb(const Dims &d, const float *s_tilde, int32_t budget, int32_t *thr, hipStream_t st)
 {
     if (d.P <= 0) return hipSuccess;
     SegView none{};
-    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, none,
-                       (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, PlanArgs{});
+    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), topb_lds(TB_OFFS), st, d, s_tilde, budget, thr, none,
+                       (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, PlanArgs{}, TB_OFFS);
     return hipGetLastError();
 }
 
@@ -1044,8 +1049,8 @@ hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv,
     SegRec *list = reinterpret_cast<SegRec *>(w);
     w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
     SegRec *list_long = reinterpret_cast<SegRec *>(w);
-    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, sv, seg_budget,
-                       block_size, counters, PlanArgs{});
+    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), topb_lds(TB_OFFS), st, d, s_tilde, budget, thr, sv,
+                       seg_budget, block_size, counters, PlanArgs{}, TB_OFFS);
     if (budget > 0 && d.T > 0) {
         hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, thr, seg_budget, block_size,
                            list, list_long, counters, (int)cap);
@@ -1112,7 +1117,7 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
 // ---- search and select in one sequence (same results as launch_search followed by launch_select)
 bool search_select_fused(const Dims &d, const SegView &sv, int32_t budget)
 {
-    return budget > 0 && budget < d.T && budget <= TB_HITS && sv.max_segments + 1 <= TB_OFFS;
+    return budget > 0 && budget < d.T && budget <= TB_HITS && sv.max_segments + 1 <= TB_OFFS_MAX;
 }
 
 // Workgroups per row for the two Top-B passes of the one-call form: with few problems in a call (a layer at a
@@ -1186,8 +1191,19 @@ hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegVi
     } else {
         hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, counters);
     }
-    hipLaunchKernelGGL(topb_kernel<true>, dim3(d.P), dim3(TB_THREADS), 0, st, d, s_tilde, budget, thr, sv, seg_budget,
-                       block_size, counters, pa);
+    // counters and offsets of all segments of a sequence in LDS: the smallest of the three sizes that holds them
+    const int offs_cap = sv.max_segments + 1 <= TB_OFFS ? TB_OFFS : sv.max_segments + 1 <= 2 * TB_OFFS ? 2 * TB_OFFS : TB_OFFS_MAX;
+    if (offs_cap > TB_OFFS) {
+        static bool attr_done = false;
+        if (!attr_done) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(topb_kernel<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)topb_lds(TB_OFFS_MAX));
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+    }
+    hipLaunchKernelGGL(topb_kernel<true>, dim3(d.P), dim3(TB_THREADS), topb_lds(offs_cap), st, d, s_tilde, budget, thr, sv,
+                       seg_budget, block_size, counters, pa, offs_cap);
     if (cap > 0) {
         hipLaunchKernelGGL((search_kernel<CAPT, CAPB, true>), dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64),
                            0, st, d, s_tilde, sv, cand, tau, list, counters, (int)cap, block_size, budget, idx_out);

@@ -204,6 +204,19 @@ def test_topb_passes_sliced_over_several_workgroups(oracle, torch_cuda, monkeypa
         np.testing.assert_array_equal(a, b)
 
 
+@pytest.mark.parametrize("max_len", [2, 5, 12])
+def test_search_select_with_many_segments(oracle, torch_cuda, max_len):
+    # about 13 600, 6 800 and 3 100 segments: the one-call form keeps the counters of all segments of a sequence
+    # in LDS and picks 16 384, 8 192 or 4 096 entries for them (beyond that it runs the two sequences of kernels)
+    rng = np.random.default_rng(77 + max_len)
+    T, P = 20491, 2
+    st = rng.random((P, T)) ** 5
+    lens = rng.integers(1, max_len + 1, size=T)
+    off = np.unique(np.minimum(np.concatenate([[0], np.cumsum(lens)]), T)).astype(np.int32)
+    assert {2: 12000 < len(off) < 16384, 5: 4096 < len(off) < 8192, 12: 2500 < len(off) < 4096}[max_len]
+    _assert_search_select(oracle, torch_cuda, st, off, [1, 2, 4, 8], 2500, 0.85)
+
+
 def test_search_select_degenerate_cases(oracle, torch_cuda):
     torch = torch_cuda
     rng = np.random.default_rng(5)
