@@ -142,6 +142,19 @@ inline int device_compute_units()
     return cus;
 }
 
+// Opt-ins that hold per device (dynamic LDS above 64 KiB for a kernel) are made once per host thread and device:
+//     static thread_local PerDeviceOnce once;  if (once.needed()) { ...; once.done(); }
+// A thread that switches devices simply makes them again.
+struct PerDeviceOnce {
+    int done_dev = -1, cur = -1;
+    bool needed()
+    {
+        if (hipGetDevice(&cur) != hipSuccess) cur = -1;
+        return cur < 0 || cur != done_dev;
+    }
+    void done() { done_dev = cur; }
+};
+
 // row statistics of the scoring step for 256 window-query rows per KV head with one read of K (the attention
 // kernel's first product alone): stats [P][2][row_stats_chunks][128][2] = (reference in the log2 domain, sum)
 bool row_stats_supported(const Dims &d);

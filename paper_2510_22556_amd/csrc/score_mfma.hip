@@ -1319,15 +1319,15 @@ void launch_merge(const ScoreArgs &a, int blocks, int M, hipStream_t st)
 template <int G, int W, bool STORE>
 hipError_t launch_score_g(const ScoreArgs &a, dim3 grid, bool with_stats, hipStream_t st)
 {
-    static bool attr_done = false;
-    if (!attr_done) {
+    static thread_local PerDeviceOnce attr_once;
+    if (attr_once.needed()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats_g<G, W>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, stats_g_lds<G, W>());
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_g<G, W, STORE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, columns_g_lds<G, W>());
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_once.done();
     }
     constexpr int lds1 = stats_g_lds<G, W>(), lds2 = columns_g_lds<G, W>();
     if (with_stats) {
@@ -1459,8 +1459,8 @@ size_t score_mfma_ws_bytes(const Dims &d)
 hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
                              float *s_out, float *ent_out, void *ws, hipStream_t st)
 {
-    static bool attr_done = false;
-    if (!attr_done) {
+    static thread_local PerDeviceOnce attr_once;
+    if (attr_once.needed()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, P1_LDS);
         if (e != hipSuccess) return e;
@@ -1473,7 +1473,7 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns8t<32>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, P2W_LDS);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_once.done();
     }
     const Plan pl = make_plan(d);
     ScoreArgs a;
@@ -1552,15 +1552,15 @@ hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, c
     a.abar = nullptr;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
     if (layer_kernel_shape(d)) {
-        static bool attr_done = false;
-        if (!attr_done) {
+        static thread_local PerDeviceOnce attr_once;
+        if (attr_once.needed()) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, P1_LDS);
             if (e != hipSuccess) return e;
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_layer),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, PL_LDS);
             if (e != hipSuccess) return e;
-            attr_done = true;
+            attr_once.done();
         }
         a.s_out = s_out;
         a.e_out = ent_out;

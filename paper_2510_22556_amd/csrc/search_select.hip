@@ -1194,12 +1194,12 @@ hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegVi
     // counters and offsets of all segments of a sequence in LDS: the smallest of the three sizes that holds them
     const int offs_cap = sv.max_segments + 1 <= TB_OFFS ? TB_OFFS : sv.max_segments + 1 <= 2 * TB_OFFS ? 2 * TB_OFFS : TB_OFFS_MAX;
     if (offs_cap > TB_OFFS) {
-        static bool attr_done = false;
-        if (!attr_done) {
+        static thread_local PerDeviceOnce attr_once;
+        if (attr_once.needed()) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(topb_kernel<true>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)topb_lds(TB_OFFS_MAX));
             if (e != hipSuccess) return e;
-            attr_done = true;
+            attr_once.done();
         }
     }
     hipLaunchKernelGGL(topb_kernel<true>, dim3(d.P), dim3(TB_THREADS), topb_lds(offs_cap), st, d, s_tilde, budget, thr, sv,

@@ -443,12 +443,12 @@ int row_stats_chunks(const Dims &d)
 
 hipError_t launch_row_stats(const Dims &d, const void *q, const void *k, float *stats, hipStream_t st)
 {
-    static bool attr_done = false;
-    if (!attr_done) {
+    static thread_local PerDeviceOnce attr_once;
+    if (attr_once.needed()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<8, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(8, false));
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_once.done();
     }
     WinArgs a;
     a.d = d;
@@ -482,15 +482,15 @@ size_t window_attention_ws_bytes(const Dims &d)
 hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, const void *v, float *out, float *lse,
                                    void *ws, hipStream_t st)
 {
-    static bool attr_done = false;
-    if (!attr_done) {
+    static thread_local PerDeviceOnce attr_once;
+    if (attr_once.needed()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<4, true>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(4));
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<8, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(8));
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_once.done();
     }
     const int nw = d.G * d.W / ROWS;                           // 4 or 8 row blocks = wavefronts per workgroup
     WinArgs a;
