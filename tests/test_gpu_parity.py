@@ -910,6 +910,43 @@ def test_ablation_switches_as_degenerate_configurations(oracle, torch_cuda):
     assert np.array_equal(run.st, run.s[:, :w.T])
 
 
+@pytest.mark.parametrize("G,W", [(4, 32), (4, 64), (8, 32)])
+@pytest.mark.parametrize("extra", [1, 31, 32, 33, 200])
+def test_window_attention_short_contexts(oracle, torch_cuda, G, W, extra):
+    # contexts of W + 1 ... W + 200 tokens: a single ragged subtile, chunks whose keys most rows do not see (their
+    # partial sums are empty), the window starting inside the first subtile
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    ns, nl, Hkv, D = 2, 1, 2, 128
+    L = W + extra
+    q = synth.normal_torch(909, 1, (ns, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(909, 2, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(909, 3, (ns, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    shape = B.make_shape(q, k, v)
+    ws = torch.empty((B.sablock_window_attention_workspace_bytes(shape),), dtype=torch.uint8, device="cuda")
+    out = torch.full((ns, nl, G * Hkv, W, D), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((ns * nl * Hkv, G * W), float("nan"), dtype=torch.float32, device="cuda")
+    B.sablock_window_attention(shape, q, k, v, out, lse, ws)
+    torch.cuda.synchronize()
+    out_g, lse_g = H.to_np(out), H.to_np(lse)
+    vmax = float(v.float().abs().max())
+    for sq in range(ns):
+        for h in range(Hkv):
+            o_ref, l_ref = oracle.window_attention(H.widen(H.to_np(q[sq, 0, h * G:(h + 1) * G])), H.widen(H.to_np(k[sq, 0, h])),
+                                                   H.widen(H.to_np(v[sq, 0, h])))
+            np.testing.assert_allclose(lse_g[sq * Hkv + h].reshape(G, W), l_ref, rtol=0, atol=2e-5)
+            np.testing.assert_allclose(out_g[sq, 0, h * G:(h + 1) * G], o_ref, rtol=0, atol=4e-3 * vmax)
+    seg = B.make_segments(np.tile(np.array([0, L - W], dtype=np.int32), ns), list(range(0, 2 * ns + 1, 2)), "cuda")
+    buf = B.Buffers(shape, seg, 8, "cuda")
+    B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, 1e-6)
+    s0, e0 = H.to_np(buf.s).copy(), H.to_np(buf.ent).copy()
+    B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, 1e-6, row_lse=lse)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(H.to_np(buf.s), s0, rtol=1e-4, atol=1e-9)
+    np.testing.assert_allclose(H.to_np(buf.ent), e0, rtol=1e-4, atol=1e-6)
+
+
 @pytest.mark.parametrize("G,W,chunk", [(4, 32, 0), (4, 32, 512), (4, 64, 0), (4, 64, 512), (8, 32, 0), (8, 32, 1024)])
 def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, monkeypatch, G, W, chunk):
     # Attention of the window queries (the producer of row_lse) against the oracle: outputs and log-sum-exp; keys
