@@ -545,6 +545,25 @@ def test_llama8b_128k_full_size_sampled(oracle, torch_cuda):
     _check_all(oracle, w, run, q, k, v, off, ptr, [3, 130, 255])
 
 
+def test_llama8b_4x64k_full_size_sampled(oracle, torch_cuda):
+    # configuration 5 at full size (4 sequences x 32 layers in one call, 1 024 problems of 256 window-query rows,
+    # whole problems per workgroup as bench.py runs it): one sampled problem per sequence (each sequence has its own
+    # segmentation) against the oracle, properties that hold at any size on all problems
+    torch = torch_cuda
+    w = synth.WORKLOADS["llama8b_4x64k"]
+    q, k, v, off, ptr = _device_workload(torch, w)
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau)
+    B_ = w.budget()
+    P = w.n_seq * w.n_layers * w.n_kv_heads
+    assert run.s.shape == (P, w.seq_len)
+    assert np.allclose(run.s.sum(axis=1), w.window, rtol=1e-4)
+    assert (run.n_sel == B_).all() and (run.b.sum(axis=1) == B_).all()
+    assert (np.diff(run.idx, axis=1) > 0).all() and run.idx.min() >= 0 and run.idx.max() < w.T
+    assert run.k_out.shape[1] == w.cache_budgets[0]
+    per_seq = w.n_layers * w.n_kv_heads
+    _check_all(oracle, w, run, q, k, v, off, ptr, [5, per_seq + 77, 2 * per_seq + 130, 4 * per_seq - 1], end_to_end=False)
+
+
 def test_segmentation_matches_oracle_and_feeds_the_path(oracle, torch_cuda):
     # punctuation-based segmentation on the device (the step in front of the path): offsets bit-exact against the
     # oracle's token walk for ragged lengths, padded rows, no / only delimiters, and as input of the five calls
