@@ -279,6 +279,11 @@ WORKLOADS: Dict[str, Workload] = {
                              (1, 2, 4, 8, 16, 32, 64), (1024,), (64.0,), 2, 512),
     "llama8b_4x64k": Workload("llama8b_4x64k", 5, 4, 32, 32, 8, 128, 65536, 64, "bf16",
                               (1, 2, 4, 8, 16, 32, 64), (2048,), (16.0, 64.0, 256.0, 16.0), 2, None),
+    # the paper's own settings (Implementation Details, Sec. 4.1; block sizes of Sec. 4.4): window of 8 recent
+    # tokens, candidate block sizes up to g_max = 13, on the same head shape; mean segment of 28 tokens, the
+    # length at which a block of 7 crosses a boundary about 21.65 % of the time (Sec. 2.2)
+    "paper_defaults_32k": Workload("paper_defaults_32k", 6, 1, 32, 32, 8, 128, 32768, 8, "bf16",
+                                   (1, 2, 3, 5, 7, 9, 11, 13), (96, 128, 1024), (28.0,), 2, 224, rope=True),
 }
 
 

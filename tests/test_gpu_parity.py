@@ -510,6 +510,24 @@ def test_llama8b_32k_heavy_hitters_three_budgets(oracle, torch_cuda):
     assert mean_g[0] <= mean_g[1] <= mean_g[2]          # larger budgets pick larger blocks (Sec. 3.3 trend)
 
 
+def test_paper_default_settings_three_budgets(oracle, torch_cuda):
+    # the paper's own hyperparameters (Sec. 4.1): window of 8, candidate block sizes {1, 2, 3, 5, 7, 9, 11, 13};
+    # two of the 32 layers at cache budgets 96 / 128 / 1024
+    import dataclasses
+
+    w = dataclasses.replace(synth.WORKLOADS["paper_defaults_32k"], n_layers=2)
+    q, k, v, off, ptr = _device_workload(torch_cuda, w, n_layers=2)
+    mean_g = []
+    for bi in range(3):
+        run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(bi), w.eps, w.alpha, w.eta, w.tau)
+        _check_all(oracle, w, run, q, k, v, off, ptr, [2, 8 + 5], end_to_end=(bi == 1))
+        assert (run.n_sel == w.budget(bi)).all()
+        assert run.k_out.shape[1] == w.cache_budgets[bi]
+        assert np.isin(run.g, (0,) + tuple(w.cand)).all()
+        mean_g.append(float((run.g * run.b).sum() / run.b.sum()))
+    assert mean_g[0] <= mean_g[2]                       # larger budgets pick larger blocks (Sec. 4.4 trend)
+
+
 def test_llama8b_4x64k_window64_batched(oracle, torch_cuda):
     # configuration 5 (one of its 32 layers): batch 4, W = 64, per-sequence segment means 16/64/256/16, B = 1984
     import dataclasses
