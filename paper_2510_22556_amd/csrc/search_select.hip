@@ -341,7 +341,9 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         find_bin_from_top(hist, 4096, krem, sh_pair, bin, above);
         const uint32_t n_bin = hist[bin];
         __syncthreads();                       // hist is reused below
-        if (n_bin <= (uint32_t)TB_CAND && k <= TB_HITS) {
+        // the candidate list is as long as the LDS arrays it sits in (the sliced passes stage theirs in TB_CAND entries)
+        const uint32_t cand_cap = sliced ? (uint32_t)TB_CAND : (uint32_t)offs_cap;
+        if (n_bin <= cand_cap && k <= TB_HITS) {
             // ---- pass B: split the row into sure Top-B tokens and candidates
             if (sliced) {
                 const int nh = pa.pre_cnt[2 * p], nc = pa.pre_cnt[2 * p + 1];
