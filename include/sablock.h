@@ -29,7 +29,11 @@
  *   sablock_workspace_bytes() bytes; its contents are undefined between calls.
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = default stream).
  *   Calls only enqueue work and return; outputs are valid once the stream
- *   reaches that point; calls on one stream are ordered.
+ *   reaches that point; calls on one stream are ordered.  Calls on different
+ *   streams (and from different host threads) may overlap as long as each has
+ *   its own workspace and output buffers: nothing else is shared between calls.
+ *   Only kernels are enqueued (no allocation, copy, memset or synchronisation),
+ *   so a sequence of calls can be captured into a HIP graph.
  * Errors.  Status code only (never exceptions/aborts).  Host scalars are
  *   validated before anything is enqueued: on a non-OK status nothing was
  *   launched.  Device-resident data (segment offsets, NaNs) is not validated.
