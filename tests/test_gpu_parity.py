@@ -217,6 +217,28 @@ def test_search_select_with_many_segments(oracle, torch_cuda, max_len):
     _assert_search_select(oracle, torch_cuda, st, off, [1, 2, 4, 8], 2500, 0.85)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_search_select_random_sweep(oracle, torch_cuda, seed):
+    # random draws of everything the search and the selection depend on: row length, segment lengths, candidate
+    # list (always with 1), budget (also 0, above T, and equal to T), tau (also 0 and above 1), score distribution
+    # (continuous, few levels, mostly zeros)
+    rng = np.random.default_rng(9000 + seed)
+    T, P = int(rng.integers(40, 6000)), int(rng.integers(1, 5))
+    kind = seed % 3
+    st = rng.random((P, T)) ** int(rng.integers(1, 9))
+    if kind == 1:
+        st = np.round(st * 12) / 12
+    elif kind == 2:
+        st = np.where(rng.random((P, T)) < 0.9, 0.0, st)
+    lens = rng.integers(1, int(rng.integers(2, 200)), size=T)
+    off = np.unique(np.minimum(np.concatenate([[0], np.cumsum(lens)]), T)).astype(np.int32)
+    pool = np.arange(2, 65)
+    cand = [1] + sorted(int(c) for c in rng.choice(pool, size=int(rng.integers(0, 7)), replace=False))
+    budget = [int(rng.integers(1, T)), 0, T, T + 17, int(rng.integers(1, min(T, 64)))][seed % 5]
+    tau = [0.85, 0.0, 0.5, 1.0, 1.2][(seed // 2) % 5]
+    _assert_search_select(oracle, torch_cuda, st, off, cand, budget, tau)
+
+
 def test_search_select_degenerate_cases(oracle, torch_cuda):
     torch = torch_cuda
     rng = np.random.default_rng(5)
