@@ -411,6 +411,34 @@ def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, monkeypatch
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
 
+@pytest.mark.parametrize("seed", range(18))
+def test_mfma_score_random_sweep(oracle, torch_cuda, monkeypatch, seed):
+    # every (G, W) the MFMA kernels cover, with random lengths (ragged, from W + 1 on), KV heads, layers, chunk
+    # lengths (one to many chunks per problem, with and without the fold kernel) and a few dominant keys
+    torch = torch_cuda
+    rng = np.random.default_rng(6100 + seed)
+    G, W = [(4, 32), (4, 64), (8, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)][seed % 9]
+    Hkv, nl, D = int(rng.integers(1, 4)), int(rng.integers(1, 3)), 128
+    L = W + int([rng.integers(1, 40), rng.integers(40, 700), rng.integers(700, 5000)][seed % 3])
+    T = L - W
+    chunk = [0, 64, 256, 1024][int(rng.integers(0, 4))]
+    if chunk:
+        monkeypatch.setenv("SABLOCK_SCORE_CHUNK", str(chunk))
+    q = synth.normal_torch(6100 + seed, 1, (1, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k = synth.normal_torch(6100 + seed, 2, (1, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    v = synth.normal_torch(6100 + seed, 3, (1, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    for _ in range(3):
+        l, h, g, i, t = (int(rng.integers(0, n)) for n in (nl, Hkv, G, W, L))
+        k[0, l, h, t, :] = (q[0, l, h * G + g, i, :].float() * float(rng.uniform(3, 8))).to(torch.bfloat16)
+    off = synth.segment_offsets(61 + seed, T, mean=min(28.0, max(T / 2, 1.0)), min_len=1, max_len=200)
+    cand = [1, 2, 4, 8]
+    B_ = max(T // 4, 1)
+    w = synth.Workload("sweep", 0, 1, nl, G * Hkv, Hkv, D, L, W, "bf16", tuple(cand), (B_ + W,), (28.0,))
+    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget())
+    assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
+    _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(nl * Hkv))
+
+
 @pytest.mark.parametrize("G,W,D,dtype", [(4, 32, 128, "bf16"), (4, 64, 128, "bf16"), (4, 8, 128, "bf16"), (3, 5, 40, "f32")])
 def test_score_closed_form_for_zero_queries(torch_cuda, G, W, D, dtype):
     # Q = 0: every visible key gets the same probability, so window query i spreads 1 / (T + i + 1) over keys
