@@ -211,6 +211,8 @@ def main():
         step(evs[i])
     torch.cuda.synchronize()
     stage_ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, n in enumerate(names)}
+    per_step = sorted(e[0].elapsed_time(e[4]) for e in evs)      # whole steps of that second loop, by their events
+    score_per_step = sorted(e[0].elapsed_time(e[1]) for e in sev)
 
     alg = algorithmic_bytes(w, budget)
     score_gbs = alg["score"] / (score_ms * 1e-3) / 1e9
@@ -229,6 +231,9 @@ def main():
                        "GBps": sum(alg.values()) / (dt / args.steps) / 1e9,
                        "frac_hbm_peak": sum(alg.values()) / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
         "stages_ms": stage_ms,
+        "step_events_ms": {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]},
+        "score_events_ms": {"median": score_per_step[len(score_per_step) // 2], "min": score_per_step[0],
+                            "max": score_per_step[-1]},
         "roofline": {"kernel": "sablock_score (all kernels of the scoring step: row statistics + column pass)",
                      "bound": "hbm", "achieved": score_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": score_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),

@@ -314,7 +314,7 @@ sablock_status sablock_window_attention_workspace_bytes(const sablock_shape *sha
     sablock_status st = make_dims(shape, &d);
     if (st != SABLOCK_OK) return st;
     if (!window_attention_supported(d))
-        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_window_attention: needs bf16, head_dim 128 and (query heads per KV head, window) in {(4, 32), (4, 64), (8, 32)}");
+        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_window_attention: needs bf16, head_dim 128, a window of 8, 16, 32 or 64 and 32, 64, 128 or 256 window-query rows per KV head");
     *bytes_out = window_attention_ws_bytes(d);
     return SABLOCK_OK;
 }
@@ -330,7 +330,7 @@ sablock_status sablock_window_attention(const sablock_shape *shape, const void *
         return fail(SABLOCK_ERR_INVALID_ARG, "sablock_window_attention: Q/K/V must be 16-byte aligned");
     if (shape->v_stride[3] < d.D) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_window_attention: V token stride smaller than head_dim");
     if (!window_attention_supported(d))
-        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_window_attention: needs bf16, head_dim 128 and (query heads per KV head, window) in {(4, 32), (4, 64), (8, 32)}");
+        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_window_attention: needs bf16, head_dim 128, a window of 8, 16, 32 or 64 and 32, 64, 128 or 256 window-query rows per KV head");
     const size_t need = window_attention_ws_bytes(d);
     if (!ws || ws_bytes < need)
         return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_window_attention: workspace %zu < %zu bytes", ws_bytes, need);

@@ -2,8 +2,9 @@
 // softmax denominators of its rows as a second output: the part of a prefill attention whose row statistics the
 // scoring step (Sec. 3.2) needs.  With them sablock_score reads K once (its column pass alone).
 //
-// bf16, D = 128; (G, W) = (4, 32) with four wavefronts per workgroup, (4, 64) or (8, 32) with eight: a wavefront
-// is one block of 32 window-query rows (one head, or one half of a head's window of 64).  A workgroup owns a chunk
+// bf16, D = 128; W in {8, 16, 32, 64} with G * W in {32, 64, 128, 256} window-query rows per KV head.  The rows
+// are ordered head * W + query and a wavefront is one block of 32 of them (one head, half of a head's window of
+// 64, or several heads when W < 32), so a workgroup has one to eight wavefronts.  A workgroup owns a chunk
 // of keys of one problem (sequence, layer, KV head).  K and V subtiles of 32 keys
 // go global -> LDS by direct-to-LDS loads into a workgroup-wide ring of NSTAGE stages (each wavefront issues a
 // quarter of a stage); one LDS-only barrier per subtile tells that the stage has landed and that the stage of
@@ -115,8 +116,9 @@ window_attention_kernel(WinArgs a)
     const int p = blockIdx.x / a.n_chunks, chunk = blockIdx.x - p * a.n_chunks;
     const int lo = chunk * a.chunk_len, hi = min(lo + a.chunk_len, d.L);
     const int n_sub = hi > lo ? (hi - lo + SUB - 1) / SUB : 0;                 // the same for all wavefronts
-    const int blocks_per_head = d.W / ROWS;                    // 1 or 2
-    const int head = wave / blocks_per_head, qoff = ROWS * (wave - head * blocks_per_head);
+    // the problem's G * W rows in the order head * W + query; this lane's row of the wavefront's block of 32
+    // (W >= 32: one head per block; W < 32: 32 / W heads per block)
+    const int head = (ROWS * wave + n) / d.W, qoff = (ROWS * wave + n) - head * d.W - n;    // query of this lane = qoff + n
     const uint32_t ring = __builtin_amdgcn_readfirstlane(lds_addr(lds));
     float *fac = reinterpret_cast<float *>(lds + NSTAGE * STAGE_BYTES) + wave * ROWS;        // this wavefront's exchange slice
     const char *kp = reinterpret_cast<const char *>(a.k + k_problem_offset(d, p));
@@ -246,15 +248,11 @@ window_attention_kernel(WinArgs a)
         {
             static_assert(NSTAGE - 2 <= 2, "the wait below knows up to two later stages");
             const int after = min(NSTAGE - 2, n_sub - 1 - u);
-            static_assert(LOADS == 4 || LOADS == 2 || LOADS == 1, "the waits below are written out for these");
+            static_assert(2 * LOADS < 64, "vmcnt is a 6-bit counter");
             if (after >= 2) {
-                if (LOADS == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-                else if (LOADS == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
             } else if (after == 1) {
-                if (LOADS == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-                else if (LOADS == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
@@ -359,7 +357,7 @@ window_attention_kernel(WinArgs a)
         return;
     }
     const int pb = p * NW + wave;                              // (problem, row block)
-    const int64_t out_row0 = ((int64_t)p * d.G + head) * d.W + qoff;           // first output row of this block
+    const int64_t out_row0 = (int64_t)p * d.G * d.W + ROWS * wave;             // first output row of this block
     if (a.n_chunks == 1) {
         if (hf == 0) {
             fac[n] = l_tot > 0.f ? 1.0f / l_tot : 0.f;
@@ -389,8 +387,8 @@ __global__ void __launch_bounds__(128)
 window_attention_merge_kernel(const float *o_part, const float *ml_part, int n_chunks, int G, int W, float *out, float *lse)
 {
     const int row = blockIdx.x;                                // (p * G + h) * W + i
-    const int i = row % W, ph = row / W, h = ph % G, p = ph / G;
-    const int pb = (p * G + h) * (W / ROWS) + i / ROWS, qy = i % ROWS;
+    const int GW = G * W, p = row / GW, r = row - p * GW;      // r = h * W + i: blocks of 32 consecutive r
+    const int pb = p * (GW / ROWS) + r / ROWS, qy = r % ROWS;
     float m = -INFINITY;
     for (int c = 0; c < n_chunks; ++c) {
         const float *ml = ml_part + (((int64_t)pb * n_chunks + c) * ROWS + qy) * 2;
@@ -466,14 +464,16 @@ hipError_t launch_row_stats(const Dims &d, const void *q, const void *k, float *
 
 bool window_attention_supported(const Dims &d)
 {
-    return d.dtype == SABLOCK_BF16 && d.D == 128 &&
-           ((d.G == 4 && d.W == 32) || (d.G == 4 && d.W == 64) || (d.G == 8 && d.W == 32));
+    // whole blocks of 32 rows, each of whole heads or inside one head: the shapes of the MFMA scoring kernels
+    const int rows = d.G * d.W;
+    return d.dtype == SABLOCK_BF16 && d.D == 128 && (rows == 32 || rows == 64 || rows == 128 || rows == 256) &&
+           (d.W == 8 || d.W == 16 || d.W == 32 || d.W == 64);
 }
 
 size_t window_attention_ws_bytes(const Dims &d)
 {
     int len, nc;
-    wa_plan(d, &len, &nc, d.G * d.W / ROWS == 4 ? 2 : 1);
+    wa_plan(d, &len, &nc, d.G * d.W / ROWS <= 4 ? 2 : 1);
     if (nc == 1) return 256;
     const size_t blocks = (size_t)d.P * (d.G * d.W / ROWS);
     return align256(blocks * nc * ROWS * 128 * 4) + align256(blocks * nc * ROWS * 2 * 4);
@@ -484,22 +484,28 @@ hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, 
 {
     static thread_local PerDeviceOnce attr_once;
     if (attr_once.needed()) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<4, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(4));
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<1, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(1));
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<2, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(2));
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<4, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(4));
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<8, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(8));
         if (e != hipSuccess) return e;
         attr_once.done();
     }
-    const int nw = d.G * d.W / ROWS;                           // 4 or 8 row blocks = wavefronts per workgroup
+    const int nw = d.G * d.W / ROWS;                           // 1, 2, 4 or 8 row blocks = wavefronts per workgroup
     WinArgs a;
     a.d = d;
     a.q = static_cast<const uint16_t *>(q);
     a.k = static_cast<const uint16_t *>(k);
     a.v = static_cast<const uint16_t *>(v);
-    // four-wavefront workgroups pair up on a CU; eight-wavefront ones already put two wavefronts on every SIMD
-    wa_plan(d, &a.chunk_len, &a.n_chunks, nw == 4 ? 2 : 1);
+    // workgroups of up to four wavefronts pair up on a CU; eight-wavefront ones already put two wavefronts on every SIMD
+    wa_plan(d, &a.chunk_len, &a.n_chunks, nw <= 4 ? 2 : 1);
     a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
     a.out = out;
     a.lse = lse;
@@ -507,7 +513,9 @@ hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, 
     a.ml_part = reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.P * nw * a.n_chunks * ROWS * 128 * 4));
     const dim3 grid((unsigned)((int64_t)d.P * a.n_chunks));
     a.stats = nullptr;
-    if (nw == 4) hipLaunchKernelGGL((window_attention_kernel<4, true>), grid, dim3(4 * 64), wa_lds(4), st, a);
+    if (nw == 1) hipLaunchKernelGGL((window_attention_kernel<1, true>), grid, dim3(64), wa_lds(1), st, a);
+    else if (nw == 2) hipLaunchKernelGGL((window_attention_kernel<2, true>), grid, dim3(2 * 64), wa_lds(2), st, a);
+    else if (nw == 4) hipLaunchKernelGGL((window_attention_kernel<4, true>), grid, dim3(4 * 64), wa_lds(4), st, a);
     else hipLaunchKernelGGL((window_attention_kernel<8, true>), grid, dim3(8 * 64), wa_lds(8), st, a);
     if (a.n_chunks > 1)
         hipLaunchKernelGGL(window_attention_merge_kernel, dim3((unsigned)((int64_t)d.P * d.G * d.W)), dim3(128), 0, st,

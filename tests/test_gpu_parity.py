@@ -997,11 +997,12 @@ def test_ablation_switches_as_degenerate_configurations(oracle, torch_cuda):
     assert np.array_equal(run.st, run.s[:, :w.T])
 
 
-@pytest.mark.parametrize("G,W", [(4, 32), (4, 64), (8, 32)])
-@pytest.mark.parametrize("extra", [1, 31, 32, 33, 200])
+@pytest.mark.parametrize("G,W", [(4, 32), (4, 64), (8, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)])
+@pytest.mark.parametrize("extra", [1, 31, 32, 33, 200, 3001])
 def test_window_attention_short_contexts(oracle, torch_cuda, G, W, extra):
-    # contexts of W + 1 ... W + 200 tokens: a single ragged subtile, chunks whose keys most rows do not see (their
-    # partial sums are empty), the window starting inside the first subtile
+    # every shape the kernel covers (one to eight blocks of 32 rows; several heads per block when W < 32) on
+    # contexts of W + 1 ... W + 3001 tokens: a single ragged subtile, chunks whose keys most rows do not see (their
+    # partial sums are empty), the window starting inside the first subtile, many chunks
     torch = torch_cuda
     from paper_2510_22556_amd import binding as B
 
