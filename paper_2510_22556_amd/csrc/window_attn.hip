@@ -6,8 +6,8 @@
 // are ordered head * W + query and a wavefront is one block of 32 of them (one head, half of a head's window of
 // 64, or several heads when W < 32), so a workgroup has one to eight wavefronts.  A workgroup owns a chunk
 // of keys of one problem (sequence, layer, KV head).  K and V subtiles of 32 keys
-// go global -> LDS by direct-to-LDS loads into a workgroup-wide ring of NSTAGE stages (each wavefront issues a
-// quarter of a stage); one LDS-only barrier per subtile tells that the stage has landed and that the stage of
+// go global -> LDS by direct-to-LDS loads into a workgroup-wide ring of NSTAGE stages (each wavefront issues its
+// share of a stage); one LDS-only barrier per subtile tells that the stage has landed and that the stage of
 // the previous iteration is free to be refilled.  The score product, the exponentials and the second product of
 // a subtile depend on each other, so a wavefront alone leaves its SIMD idle between them: the ring is kept to
 // 64 KiB so that two workgroups share a CU, and a problem is split over at least two workgroups (partial results
