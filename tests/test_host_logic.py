@@ -4,6 +4,7 @@ and rejects bad host arguments before anything is enqueued (no GPU needed)."""
 import ctypes
 import os
 import re
+import sys
 
 import numpy as np
 import pytest
@@ -216,3 +217,30 @@ def test_paper_defaults_in_workloads():
             vals[k] = v
     w = synth.WORKLOADS["llama8b_128k"]
     assert (w.eps, w.alpha, w.eta, w.tau) == tuple(float(vals[k][0]) for k in ("eps", "alpha", "eta", "tau"))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # this build runs on one GPU: bench.py says so and exits before it touches a device
+    import subprocess
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_algorithmic_bytes_match_the_stated_formulas():
+    # algorithmic bytes of a step as bench.py counts them (K once, Q, the score outputs, refine's three arrays,
+    # one read of the refined scores, the gathered rows twice): config 4 must come to 2 240 B per token and layer
+    # plus the compaction, the figure the roofline fractions are quoted against
+    sys.path.insert(0, ROOT)
+    import bench
+
+    w = synth.WORKLOADS["llama8b_128k"]
+    alg = bench.algorithmic_bytes(w, w.budget())
+    per_layer = sum(alg.values()) / w.n_layers
+    assert alg["score"] > 0.9 * sum(alg.values())
+    k_bytes = w.n_kv_heads * w.seq_len * w.head_dim * 2
+    assert abs(alg["score"] / w.n_layers - (k_bytes + w.n_q_heads * w.window * w.head_dim * 2
+                                            + 2 * 4 * w.n_kv_heads * w.seq_len)) < 1
+    assert 0.29e9 < per_layer < 0.32e9
