@@ -923,6 +923,42 @@ def test_layers_overlapped_on_several_streams(torch_cuda):
             assert torch.equal(getattr(one[l], name), getattr(many[l], name)), f"layer {l}: {name}"
 
 
+@pytest.mark.parametrize("G,W", [(4, 32), (4, 64), (4, 8)])
+def test_token_major_cache_layout(torch_cuda, G, W):
+    # K and V stored [token][KV head][D] (the layout of many serving caches: head stride D, token stride Hkv * D)
+    # and handed over as strided views: every output of the path and of the window attention equals, bit for bit,
+    # the one computed from dense [KV head][token][D] copies
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    ns, nl, Hkv, D, L = 1, 2, 4, 128, 2 * 1024 + 157 + W
+    T = L - W
+    q = synth.normal_torch(4400 + W, 1, (ns, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
+    k_tm = synth.normal_torch(4400 + W, 2, (ns, nl, L, Hkv, D), "cuda", torch.bfloat16)
+    v_tm = synth.normal_torch(4400 + W, 3, (ns, nl, L, Hkv, D), "cuda", torch.bfloat16)
+    views = (k_tm.permute(0, 1, 3, 2, 4), v_tm.permute(0, 1, 3, 2, 4))
+    dense = tuple(t.contiguous() for t in views)
+    assert views[0].stride()[2:] == (D, Hkv * D, 1)
+    off = synth.segment_offsets(44, T, mean=28.0, min_len=1, max_len=200)
+    seg = B.make_segments(off, [0, len(off)], "cuda")
+    cand, budget = [1, 2, 4, 8, 16], 300
+    names = "s ent s_tilde seg_budget block_size idx n_sel k_out v_out".split()
+    res = []
+    for kk, vv in (dense, views):
+        shape = B.make_shape(q, kk, vv)
+        buf = B.Buffers(shape, seg, budget, "cuda", True)
+        B.compress(shape, q, kk, vv, seg, cand, budget, buf)
+        ws = torch.empty((B.sablock_window_attention_workspace_bytes(shape),), dtype=torch.uint8, device="cuda")
+        out = torch.empty((ns, nl, G * Hkv, W, D), dtype=torch.float32, device="cuda")
+        lse = torch.empty((ns * nl * Hkv, G * W), dtype=torch.float32, device="cuda")
+        B.sablock_window_attention(shape, q, kk, vv, out, lse, ws)
+        torch.cuda.synchronize()
+        res.append([getattr(buf, n).clone() for n in names] + [out, lse])
+    assert int(res[0][6].min()) == budget
+    for n, a, b in zip(names + ["attention out", "row_lse"], res[0], res[1]):
+        assert torch.equal(a, b), n
+
+
 def test_maximum_problem_count_per_call(oracle, torch_cuda):
     # 65 535 problems in one call (the documented limit): 13 107 layers x 5 KV heads of a tiny fp32 shape.  Sampled
     # problems at both ends and in the middle against the oracle; invariants on every problem.
