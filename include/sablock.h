@@ -164,9 +164,10 @@ SABLOCK_API sablock_status sablock_select(const sablock_shape *shape, const floa
                               void *ws, size_t ws_bytes, void *stream);
 
 /* Search and selection in one call: the outputs of sablock_search_blocks and of sablock_select for the same
- * arguments, bit for bit (Alg. 2 as a whole).  When 0 < budget < T, budget <= 4096 and every sequence has fewer
- * than 16383 segments, the Top-B kernel also lays out the output rows and the search writes the selected tokens
- * itself, which saves the selection's own passes; otherwise the two sequences simply run one after the other.
+ * arguments, bit for bit (Alg. 2 as a whole).  When 0 < budget < T, budget <= 16384 and every sequence has fewer
+ * than 16383 segments (and not both above 8192), the Top-B kernel also lays out the output rows and the search
+ * writes the selected tokens itself, which saves the selection's own passes; otherwise the two sequences simply
+ * run one after the other.
  * Workspace: sablock_workspace_bytes covers it. */
 SABLOCK_API sablock_status sablock_search_select(const sablock_shape *shape, const float *s_tilde,
                                      const int32_t *seg_off, const int32_t *seg_ptr /* host */,

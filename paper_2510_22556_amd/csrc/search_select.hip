@@ -120,6 +120,7 @@ constexpr int TB_THREADS = 1024;
 constexpr int TB_OFFS = 4096;              // segment offsets and per-segment counts kept in LDS while the implicit budgets are counted:
 constexpr int TB_OFFS_MAX = 16384;         // the launch picks 4 096, 8 192 or 16 384 entries (dynamic LDS: two int32 arrays of that size)
 constexpr int TB_HITS = 4096;              // Top-B tokens collected in LDS before they are assigned to segments
+constexpr int TB_HITS_MAX = 16384;         // ... when the launch gives the list dynamic LDS (8 192 or 16 384 entries)
 constexpr int TB_CAND = 4096;              // tokens of the threshold's 12-bit bin that the LDS candidate list holds
 
 __device__ inline bool in_topb(float v, int t, uint32_t thr_key, int thr_cut)
@@ -207,7 +208,7 @@ __device__ inline void find_bin_from_top(const uint32_t *hist, int nbins, uint32
 // than the list (or k exceeds the token list), three histogram passes over the row (11 + 11 + 10 bits) do it.
 // Ties at the threshold are cut by ascending index with one ordered pass over the row.
 //
-// PLAN (the search that also selects; the host launches it only when 0 < B < T, B <= TB_HITS and every sequence
+// PLAN (the search that also selects; the host launches it only when 0 < B < T, B <= hit_cap and every sequence
 // has fewer than `offs_cap` segments, so the Top-B tokens and the segment counters are in LDS): the same workgroup
 // goes on to the exclusive prefix of b_k (each segment's offset in the problem's idx_out row), writes n_sel, the
 // single token of every segment with b_k == 1 (g_k* = 1) straight to its place, and appends the segments with
@@ -296,17 +297,18 @@ topb_split_kernel(Dims d, const float *s_tilde, int budget, const uint32_t *g_hi
 template <bool PLAN>
 __global__ void __launch_bounds__(TB_THREADS)
 topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, int32_t *seg_budget,
-            int32_t *block_size, int32_t *counter, PlanArgs pa, int offs_cap)
+            int32_t *block_size, int32_t *counter, PlanArgs pa, int offs_cap, int hit_cap)
 {
-    __shared__ uint32_t hist[TB_HITS];           // pass-A histogram (4096 bins), later the list of Top-B tokens
+    __shared__ uint32_t hist[TB_HITS];           // pass-A histogram (4096 bins), later the list of Top-B tokens (hit_cap == TB_HITS)
     __shared__ uint32_t hist2[2048];             // histograms of the later passes
-    extern __shared__ int32_t sh_u[];            // [2][offs_cap]: candidates (key, index) during selection, then offsets and counters
+    extern __shared__ int32_t sh_u[];            // [2][offs_cap]: candidates (key, index) during selection, then offsets and
+                                                 // counters; behind them [hit_cap] Top-B tokens when hit_cap > TB_HITS
     __shared__ int sh_nhit, sh_ncand;
     __shared__ uint32_t sh_pair[2];
     __shared__ int sh_wcnt[TB_THREADS / 64];
     __shared__ int sh_cut;
     static_assert(TB_HITS == 4096 && TB_CAND <= TB_OFFS, "LDS regions are shared between phases");
-    int32_t *sh_hit = reinterpret_cast<int32_t *>(hist);
+    int32_t *sh_hit = hit_cap > TB_HITS ? sh_u + 2 * offs_cap : reinterpret_cast<int32_t *>(hist);
     uint32_t *cand_key = reinterpret_cast<uint32_t *>(sh_u);
     int32_t *cand_idx = sh_u + offs_cap;
     int32_t *sh_off = sh_u, *sh_cnt = sh_u + offs_cap;
@@ -343,7 +345,7 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         __syncthreads();                       // hist is reused below
         // the candidate list is as long as the LDS arrays it sits in (the sliced passes stage theirs in TB_CAND entries)
         const uint32_t cand_cap = sliced ? (uint32_t)TB_CAND : (uint32_t)offs_cap;
-        if (n_bin <= cand_cap && k <= TB_HITS) {
+        if (n_bin <= cand_cap && k <= hit_cap) {
             // ---- pass B: split the row into sure Top-B tokens and candidates
             if (sliced) {
                 const int nh = pa.pre_cnt[2 * p], nc = pa.pre_cnt[2 * p + 1];
@@ -449,7 +451,7 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         for (int j = tid; j < K; j += TB_THREADS) seg_budget[row + j] = off[j + 1] - off[j];
         return;
     }
-    if (!have_hits && k <= TB_HITS) {
+    if (!have_hits && k <= hit_cap) {
         // collect T_topB with one more pass over the row
         if (tid == 0) sh_nhit = 0;
         __syncthreads();
@@ -1010,14 +1012,24 @@ select_kernel(Dims d, const float *s_tilde, const int32_t *thr, const SegRec *li
 
 }  // namespace
 
-static size_t topb_lds(int offs_cap) { return (size_t)2 * offs_cap * sizeof(int32_t); }
+// dynamic LDS of topb_kernel, and what a launch may take next to the kernel's 25 KiB of static LDS
+static size_t topb_lds(int offs_cap, int hit_cap)
+{
+    return ((size_t)2 * offs_cap + (hit_cap > TB_HITS ? hit_cap : 0)) * sizeof(int32_t);
+}
+constexpr size_t TOPB_LDS_MAX = 128 * 1024;
+static int topb_offs_cap(const SegView &sv)
+{
+    return sv.max_segments + 1 <= TB_OFFS ? TB_OFFS : sv.max_segments + 1 <= 2 * TB_OFFS ? 2 * TB_OFFS : TB_OFFS_MAX;
+}
+static int topb_hit_cap(int32_t budget) { return budget <= TB_HITS ? TB_HITS : budget <= 2 * TB_HITS ? 2 * TB_HITS : TB_HITS_MAX; }
 
 hipError_t launch_topb(const Dims &d, const float *s_tilde, int32_t budget, int32_t *thr, hipStream_t st)
 {
     if (d.P <= 0) return hipSuccess;
     SegView none{};
-    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), topb_lds(TB_OFFS), st, d, s_tilde, budget, thr, none,
-                       (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, PlanArgs{}, TB_OFFS);
+    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), topb_lds(TB_OFFS, TB_HITS), st, d, s_tilde, budget, thr, none,
+                       (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, PlanArgs{}, TB_OFFS, TB_HITS);
     return hipGetLastError();
 }
 
@@ -1051,8 +1063,8 @@ hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv,
     SegRec *list = reinterpret_cast<SegRec *>(w);
     w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
     SegRec *list_long = reinterpret_cast<SegRec *>(w);
-    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), topb_lds(TB_OFFS), st, d, s_tilde, budget, thr, sv,
-                       seg_budget, block_size, counters, PlanArgs{}, TB_OFFS);
+    hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), topb_lds(TB_OFFS, TB_HITS), st, d, s_tilde, budget, thr, sv,
+                       seg_budget, block_size, counters, PlanArgs{}, TB_OFFS, TB_HITS);
     if (budget > 0 && d.T > 0) {
         hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, thr, seg_budget, block_size,
                            list, list_long, counters, (int)cap);
@@ -1119,13 +1131,15 @@ hipError_t launch_select(const Dims &d, const float *s_tilde, const SegView &sv,
 // ---- search and select in one sequence (same results as launch_search followed by launch_select)
 bool search_select_fused(const Dims &d, const SegView &sv, int32_t budget)
 {
-    return budget > 0 && budget < d.T && budget <= TB_HITS && sv.max_segments + 1 <= TB_OFFS_MAX;
+    if (!(budget > 0 && budget < d.T && budget <= TB_HITS_MAX && sv.max_segments + 1 <= TB_OFFS_MAX)) return false;
+    return topb_lds(topb_offs_cap(sv), topb_hit_cap(budget)) <= TOPB_LDS_MAX;
 }
 
 // Workgroups per row for the two Top-B passes of the one-call form: with few problems in a call (a layer at a
 // time) one workgroup per row would leave most of the chip idle.  1: the per-row kernel scans its row itself.
-static int topb_slices(const Dims &d)
+static int topb_slices(const Dims &d, int32_t budget)
 {
+    if (budget > TB_HITS) return 1;                            // the sliced passes stage at most TB_HITS tokens per row
     if (const char *e = getenv("SABLOCK_TOPB_SLICES")) {
         const int v = atoi(e);
         if (v >= 1 && v <= 64) return (int64_t)v * 4096 <= d.T ? v : 1;
@@ -1143,7 +1157,7 @@ static size_t sliced_bytes(const Dims &d)
 size_t search_select_ws_bytes(const Dims &d, int32_t max_segments, int32_t budget)
 {
     const size_t a = search_ws_bytes(d, max_segments, budget), b = select_ws_bytes(d, max_segments, budget);
-    return (a > b ? a : b) + (topb_slices(d) > 1 ? sliced_bytes(d) : 0);
+    return (a > b ? a : b) + (topb_slices(d, budget) > 1 ? sliced_bytes(d) : 0);
 }
 
 hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegView &sv, const CandList &cand,
@@ -1169,7 +1183,7 @@ hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegVi
     w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
     SegRec *list_long = reinterpret_cast<SegRec *>(w);
     PlanArgs pa{list, list_long, (int)cap, idx_out, n_sel_out, nullptr, nullptr, nullptr, nullptr};
-    const int n_slices = topb_slices(d);
+    const int n_slices = topb_slices(d, budget);
     if (n_slices > 1) {
         // behind the larger of the search and select layouts
         const size_t base = search_select_ws_bytes(d, sv.max_segments, budget) - sliced_bytes(d);
@@ -1193,19 +1207,19 @@ hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegVi
     } else {
         hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, counters);
     }
-    // counters and offsets of all segments of a sequence in LDS: the smallest of the three sizes that holds them
-    const int offs_cap = sv.max_segments + 1 <= TB_OFFS ? TB_OFFS : sv.max_segments + 1 <= 2 * TB_OFFS ? 2 * TB_OFFS : TB_OFFS_MAX;
-    if (offs_cap > TB_OFFS) {
+    // counters and offsets of all segments of a sequence, and the Top-B tokens of a row, in LDS
+    const int offs_cap = topb_offs_cap(sv), hit_cap = topb_hit_cap(budget);
+    if (topb_lds(offs_cap, hit_cap) > topb_lds(TB_OFFS, TB_HITS)) {
         static thread_local PerDeviceOnce attr_once;
         if (attr_once.needed()) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(topb_kernel<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)topb_lds(TB_OFFS_MAX));
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)TOPB_LDS_MAX);
             if (e != hipSuccess) return e;
             attr_once.done();
         }
     }
-    hipLaunchKernelGGL(topb_kernel<true>, dim3(d.P), dim3(TB_THREADS), topb_lds(offs_cap), st, d, s_tilde, budget, thr, sv,
-                       seg_budget, block_size, counters, pa, offs_cap);
+    hipLaunchKernelGGL(topb_kernel<true>, dim3(d.P), dim3(TB_THREADS), topb_lds(offs_cap, hit_cap), st, d, s_tilde, budget, thr,
+                       sv, seg_budget, block_size, counters, pa, offs_cap, hit_cap);
     if (cap > 0) {
         hipLaunchKernelGGL((search_kernel<CAPT, CAPB, true>), dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64),
                            0, st, d, s_tilde, sv, cand, tau, list, counters, (int)cap, block_size, budget, idx_out);

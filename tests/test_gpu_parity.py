@@ -239,6 +239,20 @@ def test_search_select_random_sweep(oracle, torch_cuda, seed):
     _assert_search_select(oracle, torch_cuda, st, off, cand, budget, tau)
 
 
+@pytest.mark.parametrize("budget,max_len", [(4096, 60), (4097, 60), (6000, 60), (8192, 4), (8193, 60), (16384, 60), (16385, 60),
+                                            (12000, 2)])
+def test_search_select_large_budgets(oracle, torch_cuda, budget, max_len):
+    # budgets around the sizes of the Top-B kernel's LDS token list (4 096 static, 8 192 or 16 384 dynamic), with
+    # few and with many segments (the segment counters share the LDS): the one-call form up to 16 384 where both
+    # fit, the two kernel sequences beyond; all against the oracle
+    rng = np.random.default_rng(budget + max_len)
+    T, P = 30011, 2
+    st = rng.random((P, T)) ** 4
+    lens = rng.integers(1, max_len + 1, size=T)
+    off = np.unique(np.minimum(np.concatenate([[0], np.cumsum(lens)]), T)).astype(np.int32)
+    _assert_search_select(oracle, torch_cuda, st, off, [1, 2, 4, 8, 16, 32], budget, 0.85)
+
+
 def test_search_select_degenerate_cases(oracle, torch_cuda):
     torch = torch_cuda
     rng = np.random.default_rng(5)
