@@ -431,6 +431,15 @@ def main():
     if args.cpu_layers > 0:
         result["cpu_baseline"] = cpu_baseline(w, q, k, v, off, ptr, budget, min(args.cpu_layers, w.n_layers),
                                               args.cpu_threads)
+        # the oracle on ONE thread on the two small configurations (whole workload each), for scale
+        single = {}
+        for name in ("tiny", "llama8b_8k"):
+            ws_ = synth.WORKLOADS[name]
+            qs, ks_, vs = synth.device_tensors(ws_, dev)
+            offs, ptrs = synth.workload_segments(ws_)
+            r = cpu_baseline(ws_, qs, ks_, vs, offs, ptrs, ws_.budget(), ws_.n_layers, 1)
+            single[name] = {"value": r["value"], "unit": r["unit"], "sample": r["sample"]}
+        result["cpu_baseline"]["single_thread"] = single
     print(json.dumps(result))
 
 
