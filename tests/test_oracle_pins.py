@@ -180,6 +180,22 @@ def test_search_partial_block_and_short_tail_by_hand(oracle):
     assert sc == 10.0 and take.tolist() == [True, False, False, False, True]
 
 
+def test_search_accepts_at_equality_with_the_threshold(oracle):
+    # Eq. gk_star and Alg. 2 accept a block size when R_k(g) >= tau, equality included.  One segment, B = 2: the
+    # Top-2 tokens are the first block of size 2, so T_k(2) is the Top-B set itself and R_k(2) = 1 exactly; with
+    # tau = 1 the answer is g = 2 (a strict comparison would fall back to g = 1).  Second case by hand at
+    # tau = 0.75 exactly: Top-2 = {0, 3}, base 16; g = 2 takes block {0, 1} = 12, R = 12/16 = 0.75.
+    st = [9, 9, 1, 1, 1, 1, 1, 1]
+    b, g = oracle.search_blocks(st, [0, 8], [1, 2, 4], 2, 1.0)
+    assert (b.tolist(), g.tolist()) == ([2], [2])
+    st = [8, 4, 3, 8, 0, 0]
+    b, g = oracle.search_blocks(st, [0, 6], [1, 2], 2, 0.75)
+    assert (b.tolist(), g.tolist()) == ([2], [2])
+    assert oracle.select(st, [0, 6], b, g, 2)[0].tolist() == [0, 1]
+    b, g = oracle.search_blocks(st, [0, 6], [1, 2], 2, 0.7500001)
+    assert g.tolist() == [1]
+
+
 def _random_case(rng, T, mean_len, levels=None):
     lens = []
     while sum(lens) < T:
