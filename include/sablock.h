@@ -24,9 +24,11 @@
  *   paper's n_rcnt), T = L - W (compressible region), G = n_q_heads/n_kv_heads.
  * Pointers.  Every pointer is a DEVICE pointer unless its comment says "host".
  *   The caller owns all buffers; the library allocates no device memory, keeps
- *   no state between calls and frees nothing.  Scratch comes from the
- *   caller's workspace `ws` (device, 256-byte aligned) of at least
- *   sablock_workspace_bytes() bytes; its contents are undefined between calls.
+ *   no state between calls, reads no environment variable and frees nothing.
+ *   Scratch comes from the caller's workspace `ws` (device, 256-byte aligned)
+ *   of at least sablock_workspace_bytes() bytes; its contents are undefined
+ *   between calls.  (The only thing remembered is each device's compute-unit
+ *   count, asked once per device.)
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = default stream).
  *   Calls only enqueue work and return; outputs are valid once the stream
  *   reaches that point; calls on one stream are ordered.  Calls on different
@@ -45,7 +47,7 @@
  *   sequence.  Per-segment outputs use the row stride max_segments >= max_s K_s
  *   passed by the caller; entries k >= K_s are written as 0.
  * Ranking.  Wherever tokens or blocks are ranked: value descending, index
- *   ascending.
+ *   ascending; -0.0 and +0.0 rank as equal values.
  */
 #ifndef SABLOCK_H
 #define SABLOCK_H
@@ -69,6 +71,24 @@ typedef enum {
 
 typedef enum { SABLOCK_F32 = 0, SABLOCK_BF16 = 1 } sablock_dtype;
 
+/* Launch parameters of this implementation (no passage of the paper: they change how the work is cut into
+ * workgroups, never a result).  Part of the shape, so the workspace size and the calls always see the same
+ * values; all zero = the library's own plan, which is what every figure quoted for the library was taken with.
+ * Out-of-range values are INVALID_ARG. */
+typedef struct {
+    int32_t compute_units;    /* compute units the launch plans assume; 0 = ask the current device (DEVICE error
+                                 if there is none: set it to size a workspace on a host without a GPU) */
+    int32_t score_chunk;      /* keys per workgroup of the MFMA scoring kernels, >= 128, rounded down to a multiple
+                                 of 128; 0 = whole rounds of one workgroup per compute unit */
+    int32_t window_chunk;     /* keys per workgroup of sablock_window_attention and of the one-read row statistics,
+                                 >= 32, rounded down to a multiple of 32; 0 = whole rounds of workgroups */
+    int32_t topb_slices;      /* workgroups per row of the two Top-B passes of sablock_search_select, 1 .. 64
+                                 (1 = the per-row kernel alone); 0 = by problems per compute unit */
+    int32_t stats_per_key;    /* shapes with 256 window-query rows per KV head: 1 = row statistics by the 128-row
+                                 kernel on two row blocks (K read twice by that pass) instead of the one-read kernel */
+    int32_t reserved[3];      /* must be 0 */
+} sablock_tuning;
+
 /* Host scalars describing one call.  Strides are in ELEMENTS for the four outer
  * axes (sequence, layer, head, token); the head_dim axis is contiguous. */
 typedef struct {
@@ -83,6 +103,7 @@ typedef struct {
     int64_t q_stride[4];      /* Q window [n_seq][n_layers][n_q_heads][W][D]; token axis = window query */
     int64_t k_stride[4];      /* K [n_seq][n_layers][n_kv_heads][L][D] */
     int64_t v_stride[4];      /* V, same axes as K */
+    sablock_tuning tuning;    /* all zero = defaults */
 } sablock_shape;
 
 /* Hyperparameters; the paper's defaults are eps 1e-6, alpha 0.9, eta 1.0, tau 0.85 (Sec. 4.1). */
@@ -91,8 +112,9 @@ typedef struct { float eps, alpha, eta, tau; } sablock_hparams;
 SABLOCK_API const char *sablock_version(void);
 SABLOCK_API const char *sablock_last_error(void);
 
-/* Bytes of workspace that any of the calls below may need for this shape
- * (host computation only).  max_segments and budget as passed to the calls. */
+/* Bytes of workspace that any of the calls below may need for this shape, max_segments and budget as passed to
+ * the calls.  Host computation only; the launch plans behind it depend on the compute-unit count, which is
+ * shape->tuning.compute_units or, when that is 0, the current device's. */
 SABLOCK_API sablock_status sablock_workspace_bytes(const sablock_shape *shape, int32_t max_segments,
                                        int32_t budget, size_t *bytes_out /* host */);
 
@@ -107,6 +129,7 @@ SABLOCK_API sablock_status sablock_workspace_bytes(const sablock_shape *shape, i
  *   sum-exp of each window query's scaled logits over its visible keys (what a
  *   prefill attention kernel already has); when NULL it is computed here with an
  *   extra pass over K.
+ * eps: > 0 (it keeps the logarithm of a masked or underflowed entry finite; INVALID_ARG otherwise).
  * s_out, ent_out: [P][L] float.  Arithmetic: fp32 accumulate and outputs. */
 SABLOCK_API sablock_status sablock_score(const sablock_shape *shape, const void *q_win, const void *k,
                              const float *row_lse /* nullable */, float eps,
@@ -137,7 +160,7 @@ SABLOCK_API sablock_status sablock_refine(const sablock_shape *shape, const floa
  * seg_budget_out (b_k), block_size_out (g_k*, 0 where b_k == 0): [P][max_segments] int32.
  * topb_out: optional [P][2] int32, the Top-B set in closed form: (order-preserving key v of the
  *   min(budget,T)-th best score, index cut c); token t is in T_topB iff key(t) > v or (key(t) == v and
- *   t <= c), key(x) = bits(x) ^ (x < 0 ? 0xFFFFFFFF : 0x80000000).  sablock_select accepts it back and then
+ *   t <= c), key(x) = bits(x) ^ (sign bit of x set ? 0xFFFFFFFF : 0x80000000), -0.0 taken as +0.0.  sablock_select accepts it back and then
  *   skips recomputing it.
  * Block sums, scores and the accept test are evaluated in fp64 on the fp32 inputs. */
 SABLOCK_API sablock_status sablock_search_blocks(const sablock_shape *shape, const float *s_tilde,

@@ -258,7 +258,7 @@ static double greedy_fill(const double *st, int32_t a, int32_t b, int32_t g, int
  * g_max = cand[n_cand-1]).  Outputs b_k (Eq. implicit_budget) and g_k*
  * (0 where b_k = 0: nothing is kept from that segment).  The accept test
  * R_k(g) >= tau is evaluated as Score_k(g) >= tau * Score_k^base; g = 1 is the
- * unconditional last resort ("fall back ... until reaching token-level").
+ * unconditional last resort (Sec. 3.3, the text after Eq. gk_star).
  * ---------------------------------------------------------------------- */
 int sablock_ref_search_blocks(const double *st, int32_t T, const int32_t *seg_off, int32_t K,
                               const int32_t *cand, int32_t n_cand, int32_t B, double tau,

@@ -35,11 +35,19 @@ class SablockError(RuntimeError):
         self.status = status
 
 
+class CTuning(ctypes.Structure):
+    """Launch parameters (``sablock_tuning``); all zero = the library's own plan."""
+
+    _fields_ = [("compute_units", ctypes.c_int32), ("score_chunk", ctypes.c_int32), ("window_chunk", ctypes.c_int32),
+                ("topb_slices", ctypes.c_int32), ("stats_per_key", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+
+
 class CShape(ctypes.Structure):
     _fields_ = [("n_seq", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
                 ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("seq_len", ctypes.c_int32),
                 ("window", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("q_stride", ctypes.c_int64 * 4), ("k_stride", ctypes.c_int64 * 4), ("v_stride", ctypes.c_int64 * 4)]
+                ("q_stride", ctypes.c_int64 * 4), ("k_stride", ctypes.c_int64 * 4), ("v_stride", ctypes.c_int64 * 4),
+                ("tuning", CTuning)]
 
 
 class CHparams(ctypes.Structure):
@@ -103,8 +111,9 @@ def _stream(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
-def make_shape(q, k, v=None) -> CShape:
-    """Shape descriptor from ``q [n_seq, n_layers, Hq, W, D]`` and ``k, v [n_seq, n_layers, Hkv, L, D]``."""
+def make_shape(q, k, v=None, **tuning) -> CShape:
+    """Shape descriptor from ``q [n_seq, n_layers, Hq, W, D]`` and ``k, v [n_seq, n_layers, Hkv, L, D]``;
+    keyword arguments set fields of ``shape.tuning`` (e.g. ``score_chunk=2048``)."""
     import torch
 
     assert q.dim() == 5 and k.dim() == 5 and q.stride(-1) == 1 and k.stride(-1) == 1
@@ -118,6 +127,8 @@ def make_shape(q, k, v=None) -> CShape:
         s.q_stride[a] = q.stride(a)
         s.k_stride[a] = k.stride(a)
         s.v_stride[a] = vv.stride(a)
+    for name, val in tuning.items():
+        setattr(s.tuning, name, int(val))
     return s
 
 

@@ -2,6 +2,7 @@
 // Nothing here touches the device except kernel launches on the caller's stream.
 #include "sablock_internal.h"
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -22,6 +23,32 @@ sablock_status fail(sablock_status st, const char *fmt, ...)
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Compute units of the current device.  Asked once per device and remembered (the only thing the library
+// remembers between calls); concurrent first calls store the same value.
+constexpr int MAX_DEVICES = 64;
+std::atomic<int> g_cus[MAX_DEVICES];
+
+sablock_status current_device_cus(int32_t *out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
+        (void)hipGetLastError();
+        return fail(SABLOCK_ERR_DEVICE, "no current HIP device (set shape.tuning.compute_units to plan without one)");
+    }
+    if (dev < MAX_DEVICES) {
+        const int c = g_cus[dev].load(std::memory_order_relaxed);
+        if (c > 0) { *out = c; return SABLOCK_OK; }
+    }
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+        (void)hipGetLastError();
+        return fail(SABLOCK_ERR_DEVICE, "cannot read the compute-unit count of device %d", dev);
+    }
+    if (dev < MAX_DEVICES) g_cus[dev].store(n, std::memory_order_relaxed);
+    *out = n;
+    return SABLOCK_OK;
+}
 
 sablock_status make_dims(const sablock_shape *s, Dims *d)
 {
@@ -50,6 +77,25 @@ sablock_status make_dims(const sablock_shape *s, Dims *d)
     }
     if (s->q_stride[3] < s->head_dim || s->k_stride[3] < s->head_dim)
         return fail(SABLOCK_ERR_INVALID_ARG, "token stride smaller than head_dim");
+    const sablock_tuning &tu = s->tuning;
+    if (tu.compute_units < 0 || tu.compute_units > 65536)
+        return fail(SABLOCK_ERR_INVALID_ARG, "tuning.compute_units %d: need 0 (ask the device) .. 65536", tu.compute_units);
+    if (tu.score_chunk != 0 && (tu.score_chunk < 128 || tu.score_chunk > 131072))
+        return fail(SABLOCK_ERR_INVALID_ARG, "tuning.score_chunk %d: need 0 or 128 .. 131072", tu.score_chunk);
+    if (tu.window_chunk != 0 && (tu.window_chunk < 32 || tu.window_chunk > 131072))
+        return fail(SABLOCK_ERR_INVALID_ARG, "tuning.window_chunk %d: need 0 or 32 .. 131072", tu.window_chunk);
+    if (tu.topb_slices < 0 || tu.topb_slices > 64)
+        return fail(SABLOCK_ERR_INVALID_ARG, "tuning.topb_slices %d: need 0 .. 64", tu.topb_slices);
+    if (tu.stats_per_key != 0 && tu.stats_per_key != 1)
+        return fail(SABLOCK_ERR_INVALID_ARG, "tuning.stats_per_key %d: need 0 or 1", tu.stats_per_key);
+    if (tu.reserved[0] || tu.reserved[1] || tu.reserved[2])
+        return fail(SABLOCK_ERR_INVALID_ARG, "tuning.reserved must be 0");
+    d->tune = tu;
+    d->cus = tu.compute_units;
+    if (d->cus == 0) {
+        const sablock_status st = current_device_cus(&d->cus);
+        if (st != SABLOCK_OK) return st;
+    }
     d->n_seq = s->n_seq; d->n_layers = s->n_layers; d->Hq = s->n_q_heads; d->Hkv = s->n_kv_heads;
     d->G = s->n_q_heads / s->n_kv_heads; d->D = s->head_dim; d->L = s->seq_len; d->W = s->window;
     d->T = s->seq_len - s->window; d->M = d->G * d->W; d->P = (int32_t)P; d->dtype = s->dtype;
@@ -112,24 +158,40 @@ sablock_status sablock_workspace_bytes(const sablock_shape *shape, int32_t max_s
     return SABLOCK_OK;
 }
 
+// argument checks of the scoring call and the bytes of workspace it needs
+static sablock_status score_checked(const char *who, const sablock_shape *shape, const void *q_win, const void *k,
+                                    const float *row_lse, float eps, float *s_out, float *ent_out,
+                                    Dims *d, size_t *need)
+{
+    sablock_status st = make_dims(shape, d);
+    if (st != SABLOCK_OK) return st;
+    if (!q_win || !k || !s_out || !ent_out) return fail(SABLOCK_ERR_INVALID_ARG, "%s: NULL tensor", who);
+    if (!aligned16(q_win) || !aligned16(k)) return fail(SABLOCK_ERR_INVALID_ARG, "%s: Q/K must be 16-byte aligned", who);
+    if (!(eps > 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "%s: eps must be > 0", who);
+    *need = row_lse ? 0 : (score_mfma_supported(*d) ? score_mfma_ws_bytes(*d) : score_generic_ws_bytes(*d));
+    return SABLOCK_OK;
+}
+
+static sablock_status score_launch(const char *who, const Dims &d, const void *q_win, const void *k, const float *row_lse,
+                                   float eps, float *s_out, float *ent_out, void *ws, void *stream)
+{
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    hipError_t e = score_mfma_supported(d) ? launch_score_mfma(d, q_win, k, row_lse, eps, s_out, ent_out, ws, hs)
+                                           : launch_score_generic(d, q_win, k, row_lse, eps, s_out, ent_out, ws, hs);
+    return dev(e, who);
+}
+
 sablock_status sablock_score(const sablock_shape *shape, const void *q_win, const void *k,
                              const float *row_lse, float eps, float *s_out, float *ent_out,
                              void *ws, size_t ws_bytes, void *stream)
 {
     Dims d;
-    sablock_status st = make_dims(shape, &d);
+    size_t need = 0;
+    sablock_status st = score_checked("sablock_score", shape, q_win, k, row_lse, eps, s_out, ent_out, &d, &need);
     if (st != SABLOCK_OK) return st;
-    if (!q_win || !k || !s_out || !ent_out) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score: NULL tensor");
-    if (!aligned16(q_win) || !aligned16(k)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score: Q/K must be 16-byte aligned");
-    if (!(eps >= 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score: eps must be >= 0");
-    const bool mfma = score_mfma_supported(d);
-    const size_t need = row_lse ? 0 : (mfma ? score_mfma_ws_bytes(d) : score_generic_ws_bytes(d));
     if (need && (!ws || ws_bytes < need))
         return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_score: workspace %zu < %zu bytes", ws_bytes, need);
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    hipError_t e = mfma ? launch_score_mfma(d, q_win, k, row_lse, eps, s_out, ent_out, ws, hs)
-                        : launch_score_generic(d, q_win, k, row_lse, eps, s_out, ent_out, ws, hs);
-    return dev(e, "sablock_score");
+    return score_launch("sablock_score", d, q_win, k, row_lse, eps, s_out, ent_out, ws, stream);
 }
 
 sablock_status sablock_refine(const sablock_shape *shape, const float *s, const float *ent,
@@ -297,7 +359,7 @@ sablock_status sablock_score_all_heads(const sablock_shape *shape, const void *q
     if (st != SABLOCK_OK) return st;
     if (!q_win || !k || !s_out || !ent_out) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score_all_heads: NULL argument");
     if (!aligned16(q_win) || !aligned16(k)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score_all_heads: Q/K must be 16-byte aligned");
-    if (!(eps >= 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score_all_heads: eps must be >= 0");
+    if (!(eps > 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score_all_heads: eps must be > 0");
     if (!score_all_heads_supported(d))
         return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_score_all_heads: needs bf16, head_dim 128 and at most 128 window-query rows per KV head in a shape the MFMA kernels cover");
     const size_t need = score_all_heads_ws_bytes(d);

@@ -14,6 +14,8 @@ struct Dims {
     int32_t n_seq, n_layers, Hq, Hkv, G, D, L, W, T, M;   // M = G * W rows of the window-query matrix
     int32_t P;                                            // problems = n_seq * n_layers * Hkv
     int32_t dtype;
+    int32_t cus;                                          // compute units the launch plans assume (never 0)
+    sablock_tuning tune;                                  // the caller's launch parameters, validated (0 = plan)
     int64_t qs[4], ks[4], vs[4];
 };
 
@@ -61,7 +63,7 @@ __host__ __device__ inline int64_t q_row_offset(const Dims &d, int32_t p, int32_
            (int64_t)(head_of_problem(d, p) * d.G + h_local) * d.qs[2] + (int64_t)i * d.qs[3];
 }
 
-// order-preserving map float -> uint32 (larger float <=> larger key)
+// order-preserving map float -> uint32 (larger float <=> larger key; -0.0 and +0.0 share a key, as they compare equal)
 __host__ __device__ inline uint32_t ordered_key(float f)
 {
     uint32_t u;
@@ -70,6 +72,7 @@ __host__ __device__ inline uint32_t ordered_key(float f)
 #else
     __builtin_memcpy(&u, &f, 4);
 #endif
+    if (u == 0x80000000u) u = 0u;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
@@ -128,19 +131,6 @@ hipError_t launch_segment_count(const int32_t *tok, int64_t stride, int32_t n_se
                                 int32_t *seg_count, hipStream_t st);
 hipError_t launch_segment_offsets(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,
                                   const SeqPtr &sp, int32_t *seg_off, hipStream_t st);
-
-// compute units of the current device (256 when no device can be asked, e.g. for sizes computed without a GPU)
-inline int device_compute_units()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-            n = 256;
-        cus = n;
-    }
-    return cus;
-}
 
 // Opt-ins that hold per device (dynamic LDS above 64 KiB for a kernel) are made once per host thread and device:
 //     static thread_local PerDeviceOnce once;  if (once.needed()) { ...; once.done(); }

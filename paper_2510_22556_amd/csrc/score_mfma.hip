@@ -35,7 +35,6 @@
 #include "sablock_internal.h"
 
 #include <algorithm>
-#include <cstdlib>
 
 namespace sablock {
 namespace {
@@ -1392,8 +1391,6 @@ struct Plan {
 
 constexpr int MERGE_FROM = 8;       // chunks per problem from which the separate fold pays
 
-int compute_units() { return device_compute_units(); }
-
 Plan make_plan(const Dims &d)
 {
     // One launch per pass covers every problem.  A workgroup owns chunk_len consecutive keys of one problem, and
@@ -1403,9 +1400,9 @@ Plan make_plan(const Dims &d)
     constexpr int MAX_CHUNK = 131072;
     Plan pl;
     int len;
-    if (const char *e = getenv("SABLOCK_SCORE_CHUNK"); e && atoi(e) >= STRIDE) len = (atoi(e) / STRIDE) * STRIDE;
+    if (d.tune.score_chunk >= STRIDE) len = (d.tune.score_chunk / STRIDE) * STRIDE;
     else {
-        const int64_t cus = compute_units();
+        const int64_t cus = d.cus;
         const int64_t rounds = ((int64_t)d.P * d.L + cus * MAX_CHUNK - 1) / (cus * MAX_CHUNK);
         const int64_t per_problem = std::max<int64_t>(1, (cus * rounds + d.P / 2) / d.P);     // chunks per problem
         len = (int)(((d.L + per_problem - 1) / per_problem + STRIDE - 1) / STRIDE) * STRIDE;
@@ -1445,7 +1442,7 @@ bool score_mfma_supported(const Dims &d)
 
 // pass 1 for 256 rows by the transposed-score kernel (csrc/window_attn.hip): K is read once instead of once per
 // block of 128 rows
-static bool stats_by_rows(const Dims &d) { return row_stats_supported(d) && !getenv("SABLOCK_STATS_PER_KEY"); }
+static bool stats_by_rows(const Dims &d) { return row_stats_supported(d) && !d.tune.stats_per_key; }
 static size_t row_stats_bytes(const Dims &d) { return align256((size_t)d.P * 2 * row_stats_chunks(d) * M_ROWS * 2 * 4); }
 
 size_t score_mfma_ws_bytes(const Dims &d)
@@ -1571,7 +1568,7 @@ hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, c
         // pass 2 has its own decomposition: a workgroup walks a chunk of keys through all 8 KV heads of a layer,
         // again in whole rounds of one workgroup per CU
         constexpr int MAX_LAYER_CHUNK = 32768;
-        const int64_t n_sl = (int64_t)d.n_seq * d.n_layers, cus = compute_units();
+        const int64_t n_sl = (int64_t)d.n_seq * d.n_layers, cus = d.cus;
         const int64_t rounds = (n_sl * d.L + cus * MAX_LAYER_CHUNK - 1) / (cus * MAX_LAYER_CHUNK);
         const int64_t per_layer = std::max<int64_t>(1, (cus * rounds + n_sl / 2) / n_sl);
         int len = (int)(((d.L + per_layer - 1) / per_layer + SUB - 1) / SUB) * SUB;

@@ -1140,11 +1140,8 @@ bool search_select_fused(const Dims &d, const SegView &sv, int32_t budget)
 static int topb_slices(const Dims &d, int32_t budget)
 {
     if (budget > TB_HITS) return 1;                            // the sliced passes stage at most TB_HITS tokens per row
-    if (const char *e = getenv("SABLOCK_TOPB_SLICES")) {
-        const int v = atoi(e);
-        if (v >= 1 && v <= 64) return (int64_t)v * 4096 <= d.T ? v : 1;
-    }
-    int s = (int)std::min<int64_t>(16, (int64_t)device_compute_units() / std::max(d.P, 1));
+    if (const int v = d.tune.topb_slices; v >= 1) return (int64_t)v * 4096 <= d.T ? v : 1;
+    int s = (int)std::min<int64_t>(16, (int64_t)d.cus / std::max(d.P, 1));
     s = std::min(s, d.T / 8192);                               // a slice is worth a workgroup from 8 192 tokens on
     return s >= 2 ? s : 1;
 }

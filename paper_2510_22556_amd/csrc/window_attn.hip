@@ -407,18 +407,16 @@ window_attention_merge_kernel(const float *o_part, const float *ml_part, int n_c
     if (threadIdx.x == 0) lse[row] = (m + __builtin_amdgcn_logf(z)) * LN2;
 }
 
-int wa_compute_units() { return device_compute_units(); }
-
 // keys per workgroup: whole rounds of two workgroups per CU (two wavefronts per SIMD: while one waits for its
 // LDS reads or an MFMA result the other computes), as few as keep a chunk within 131 072 keys
 void wa_plan(const Dims &d, int *chunk_len, int *n_chunks, int wgs_per_cu)
 {
     constexpr int MAX_CHUNK = 131072;
-    const int64_t cus = wgs_per_cu * (int64_t)wa_compute_units();
+    const int64_t cus = wgs_per_cu * (int64_t)d.cus;
     const int64_t rounds = ((int64_t)d.P * d.L + cus * MAX_CHUNK - 1) / (cus * MAX_CHUNK);
     const int64_t per_problem = std::max<int64_t>(1, (cus * rounds + d.P / 2) / d.P);
     int len = (int)(((d.L + per_problem - 1) / per_problem + SUB - 1) / SUB) * SUB;
-    if (const char *e = getenv("SABLOCK_WINDOW_CHUNK"); e && atoi(e) >= SUB) len = (atoi(e) / SUB) * SUB;
+    if (d.tune.window_chunk >= SUB) len = (d.tune.window_chunk / SUB) * SUB;
     len = std::min(std::max(len, SUB), MAX_CHUNK);
     *chunk_len = len;
     *n_chunks = (d.L + len - 1) / len;

@@ -45,13 +45,13 @@ class GpuRun:
     """All five ABI calls on device tensors; results as numpy arrays indexed by problem."""
 
     def __init__(self, q, k, v, seg_off, seg_ptr, cand, budget, eps=1e-6, alpha=0.9, eta=1.0, tau=0.85,
-                 append_window=True, row_lse=None):
+                 append_window=True, row_lse=None, tuning=None):
         import torch
         from paper_2510_22556_amd import binding as B
 
         self.B = B
         dev = q.device
-        self.shape = B.make_shape(q, k, v)
+        self.shape = B.make_shape(q, k, v, **(tuning or {}))
         self.seg = B.make_segments(seg_off, seg_ptr, dev)
         self.buf = B.Buffers(self.shape, self.seg, budget, dev, append_window)
         self.cand, self.budget = list(cand), budget

@@ -126,12 +126,12 @@ def _stage_inputs(torch, st_rows, L_extra=4):
     return q, k
 
 
-def _search_select_gpu(torch, st_rows, off, cand, budget, tau):
+def _search_select_gpu(torch, st_rows, off, cand, budget, tau, **tuning):
     from paper_2510_22556_amd import binding as B
 
     P, T = st_rows.shape
     q, k = _stage_inputs(torch, st_rows)
-    shape = B.make_shape(q, k)
+    shape = B.make_shape(q, k, **tuning)
     seg = B.make_segments(off, [0, len(off)], "cuda")
     buf = B.Buffers(shape, seg, budget, "cuda")
     st = torch.as_tensor(st_rows.astype(np.float32)).cuda().contiguous()
@@ -151,8 +151,8 @@ def _search_select_gpu(torch, st_rows, off, cand, budget, tau):
     return H.to_np(buf.seg_budget), H.to_np(buf.block_size), H.to_np(buf.idx), H.to_np(buf.n_sel)
 
 
-def _assert_search_select(oracle, torch, st_rows, off, cand, budget, tau):
-    b, g, idx, n = _search_select_gpu(torch, st_rows, off, cand, budget, tau)
+def _assert_search_select(oracle, torch, st_rows, off, cand, budget, tau, **tuning):
+    b, g, idx, n = _search_select_gpu(torch, st_rows, off, cand, budget, tau, **tuning)
     K = len(off) - 1
     st32 = st_rows.astype(np.float32)
     for p in range(st_rows.shape[0]):
@@ -180,7 +180,7 @@ def test_search_select_with_ties_bit_exact(oracle, torch_cuda, seed):
 
 @pytest.mark.parametrize("slices", [2, 3, 5])
 @pytest.mark.parametrize("levels", [0, 1, 300])
-def test_topb_passes_sliced_over_several_workgroups(oracle, torch_cuda, monkeypatch, slices, levels):
+def test_topb_passes_sliced_over_several_workgroups(oracle, torch_cuda, slices, levels):
     # With few problems in a call the two Top-B passes over a row are split over several workgroups (slices of the
     # row, results merged through global lists).  Forced here on a small call: continuous scores, scores on 300
     # levels (ties at the threshold), and scores that are 0 or 1 with fewer ones than the budget (the threshold's
@@ -196,10 +196,8 @@ def test_topb_passes_sliced_over_several_workgroups(oracle, torch_cuda, monkeypa
     cand, budget, tau = [1, 2, 4, 8, 16, 32], 3000, 0.85
     if levels == 1:
         assert (st == 1).sum(axis=1).max() < budget
-    monkeypatch.setenv("SABLOCK_TOPB_SLICES", "1")
-    ref = _search_select_gpu(torch_cuda, st, off, cand, budget, tau)
-    monkeypatch.setenv("SABLOCK_TOPB_SLICES", str(slices))
-    got = _assert_search_select(oracle, torch_cuda, st, off, cand, budget, tau)
+    ref = _search_select_gpu(torch_cuda, st, off, cand, budget, tau, topb_slices=1)
+    got = _assert_search_select(oracle, torch_cuda, st, off, cand, budget, tau, topb_slices=slices)
     for a, b in zip(ref, got):
         np.testing.assert_array_equal(a, b)
 
@@ -381,11 +379,10 @@ def test_mfma_row_lse_input_equals_internal_pass(oracle, torch_cuda, W):
     assert np.allclose(s0.sum(axis=1), W, rtol=1e-4)
 
 
-def test_mfma_score_eight_heads_per_group(oracle, torch_cuda, monkeypatch):
+def test_mfma_score_eight_heads_per_group(oracle, torch_cuda):
     # G = 8 (64 query / 8 KV heads), W = 32: 256 window-query rows per KV head on the eight-tile column kernel;
     # ragged length, 16 subtiles per wavefront, planted keys that move row references in both head blocks
     torch = torch_cuda
-    monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "2048")
     L, W, D, G, Hkv = 3 * 2048 + 333 + 32, 32, 128, 8, 2
     T = L - W
     q = synth.normal_torch(717, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
@@ -395,18 +392,17 @@ def test_mfma_score_eight_heads_per_group(oracle, torch_cuda, monkeypatch):
         k[0, 0, g, t, :] = (q[0, 0, g * G + h, i, :].float() * 5.0).to(torch.bfloat16)
     off = synth.segment_offsets(717, T, mean=40.0, min_len=1, max_len=300)
     w = synth.Workload("g8", 0, 1, 1, G * Hkv, Hkv, D, L, W, "bf16", (1, 2, 4, 8, 16, 32), (512,), (40.0,))
-    run = H.GpuRun(q, k, v, off, [0, len(off)], w.cand, w.budget())
+    run = H.GpuRun(q, k, v, off, [0, len(off)], w.cand, w.budget(), tuning=dict(score_chunk=2048))
     assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
     assert run.s[0, 900] > 0.99 / G and run.s[1, 4000] > 0.99 / G
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
 
 @pytest.mark.parametrize("G,W", [(4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)])
-def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, monkeypatch, G, W):
+def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, G, W):
     # 32, 64 or 128 window-query rows per KV head in one to four MFMA tiles (several heads per tile when W < 32):
     # ragged length, 16 subtiles per wavefront, planted keys that move row references, all five steps
     torch = torch_cuda
-    monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "2048")
     L, D, Hkv = 2 * 2048 + 411 + W, 128, 2
     T = L - W
     q = synth.normal_torch(3000 + G * W, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
@@ -418,7 +414,7 @@ def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, monkeypatch
     off = synth.segment_offsets(55, T, mean=28.0, min_len=1, max_len=200)
     cand = [1, 2, 3, 5, 7, 9, 11, 13]
     w = synth.Workload("shape", 0, 1, 1, G * Hkv, Hkv, D, L, W, "bf16", tuple(cand), (512 + W,), (28.0,))
-    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget())
+    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget(), tuning=dict(score_chunk=2048))
     assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
     for g, h, i, t in plants[:3]:
         assert run.s[g, t] > 0.99 / G
@@ -426,7 +422,7 @@ def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, monkeypatch
 
 
 @pytest.mark.parametrize("seed", range(18))
-def test_mfma_score_random_sweep(oracle, torch_cuda, monkeypatch, seed):
+def test_mfma_score_random_sweep(oracle, torch_cuda, seed):
     # every (G, W) the MFMA kernels cover, with random lengths (ragged, from W + 1 on), KV heads, layers, chunk
     # lengths (one to many chunks per problem, with and without the fold kernel) and a few dominant keys
     torch = torch_cuda
@@ -435,9 +431,7 @@ def test_mfma_score_random_sweep(oracle, torch_cuda, monkeypatch, seed):
     Hkv, nl, D = int(rng.integers(1, 4)), int(rng.integers(1, 3)), 128
     L = W + int([rng.integers(1, 40), rng.integers(40, 700), rng.integers(700, 5000)][seed % 3])
     T = L - W
-    chunk = [0, 64, 256, 1024][int(rng.integers(0, 4))]
-    if chunk:
-        monkeypatch.setenv("SABLOCK_SCORE_CHUNK", str(chunk))
+    chunk = [0, 128, 256, 1024][int(rng.integers(0, 4))]
     q = synth.normal_torch(6100 + seed, 1, (1, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
     k = synth.normal_torch(6100 + seed, 2, (1, nl, Hkv, L, D), "cuda", torch.bfloat16)
     v = synth.normal_torch(6100 + seed, 3, (1, nl, Hkv, L, D), "cuda", torch.bfloat16)
@@ -448,7 +442,7 @@ def test_mfma_score_random_sweep(oracle, torch_cuda, monkeypatch, seed):
     cand = [1, 2, 4, 8]
     B_ = max(T // 4, 1)
     w = synth.Workload("sweep", 0, 1, nl, G * Hkv, Hkv, D, L, W, "bf16", tuple(cand), (B_ + W,), (28.0,))
-    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget())
+    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget(), tuning=dict(score_chunk=chunk))
     assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(nl * Hkv))
 
@@ -505,14 +499,13 @@ def test_mfma_score_long_ragged_with_heavy_rows(oracle, torch_cuda):
 
 
 @pytest.mark.parametrize("W", [32, 64])
-def test_mfma_score_reference_moves_for_every_head(oracle, torch_cuda, monkeypatch, W):
+def test_mfma_score_reference_moves_for_every_head(oracle, torch_cuda, W):
     # Keys planted along chosen query rows give those rows logits far above (> 50 nats) everything seen before,
     # so the row's running reference has to move in the middle of a wavefront's stream: for each of the four
     # heads of a group, for two heads in one subtile, twice for one row, in the last subtile of a workgroup's
     # chunk, in a chunk's first subtile and inside the observation window.  Chunks of 4096 keys make every
     # wavefront loop over 32 subtiles although there are only two problems.
     torch = torch_cuda
-    monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "4096")
     L, D, G, Hkv = 3 * 4096 + 77 + W, 128, 4, 2
     T = L - W
     q = synth.normal_torch(515, 1, (1, 1, G * Hkv, W, D), "cuda", torch.bfloat16)
@@ -533,7 +526,7 @@ def test_mfma_score_reference_moves_for_every_head(oracle, torch_cuda, monkeypat
         k[0, 0, g, t, :] = (q[0, 0, g * G + h, i, :].float() * scale).to(torch.bfloat16)
     off = synth.segment_offsets(7, T, mean=48.0, min_len=1, max_len=300)
     w = synth.Workload("moves", 0, 1, 1, G * Hkv, Hkv, D, L, W, "bf16", (1, 2, 4, 8, 16, 32), (512,), (48.0,))
-    run = H.GpuRun(q, k, v, off, [0, len(off)], w.cand, w.budget())
+    run = H.GpuRun(q, k, v, off, [0, len(off)], w.cand, w.budget(), tuning=dict(score_chunk=4096))
     assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
     for g, h, i, t, scale in plants:                 # a planted key takes (almost) all of its row: Abar = 1/G
         if t < T and t not in (700, 6000):           # (the plants at 700 / 6000 lose their rows to those at 2000 / 8000)
@@ -785,7 +778,7 @@ def test_decode_attention_128k_full_and_compacted(oracle, torch_cuda):
 
 
 @pytest.mark.parametrize("G,W,Hkv", [(4, 32, 8), (4, 32, 3), (4, 8, 3), (2, 32, 3)])
-def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, monkeypatch, G, W, Hkv):
+def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, G, W, Hkv):
     # Eq. barA taken literally: one score row and one retained set per (sequence, layer).  Scores against the
     # oracle's all-head mean; refine / search / select stage-wise on the per-layer rows; shared compaction.
     # 8 KV heads with G = 4, W = 32 run the kernel that sums a layer's heads on chip (many short chunks here,
@@ -794,7 +787,6 @@ def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, monkeypatch, G,
     from paper_2510_22556_amd import binding as B
     from scipy.special import logsumexp
 
-    monkeypatch.setenv("SABLOCK_SCORE_CHUNK", "2048")
     D, nl, ns = 128, 2, 1
     L = 2 * 2048 + 300 + W
     T = L - W
@@ -805,7 +797,7 @@ def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, monkeypatch, G,
     off = synth.segment_offsets(606, T, mean=32.0, min_len=1, max_len=256)
     seg = B.make_segments(off, [0, len(off)], "cuda")
     cand, budget, eps, alpha, eta, tau = [1, 2, 4, 8, 16, 32], 400, 1e-6, 0.9, 1.0, 0.85
-    shape = B.make_shape(q, k, v)
+    shape = B.make_shape(q, k, v, score_chunk=2048)
     ls = B.layer_shape(shape)
     buf = B.Buffers(ls, seg, budget, "cuda", dtype=torch.bfloat16)       # per-layer rows (P' = n_seq * n_layers)
     ws = torch.empty((B.sablock_score_all_heads_workspace_bytes(shape),), dtype=torch.uint8, device="cuda")
@@ -1086,7 +1078,7 @@ def test_window_attention_short_contexts(oracle, torch_cuda, G, W, extra):
 
 
 @pytest.mark.parametrize("G,W,chunk", [(4, 32, 0), (4, 32, 512), (4, 64, 0), (4, 64, 512), (8, 32, 0), (8, 32, 1024)])
-def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, monkeypatch, G, W, chunk):
+def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, G, W, chunk):
     # Attention of the window queries (the producer of row_lse) against the oracle: outputs and log-sum-exp; keys
     # planted along query rows so that the running reference moves late in the stream, inside the window and in a
     # chunk's first subtile; one chunk per problem and many (merge kernel); ragged length.  Its row_lse then drives
@@ -1094,8 +1086,6 @@ def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, m
     torch = torch_cuda
     from paper_2510_22556_amd import binding as B
 
-    if chunk:
-        monkeypatch.setenv("SABLOCK_WINDOW_CHUNK", str(chunk))
     ns, nl, Hkv, D = 1, 2, 2, 128
     L = 3 * 1024 + 77 + W
     T = L - W
@@ -1105,7 +1095,7 @@ def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, m
     for (l, h, g, i, t, scale) in [(0, 0, 1, 5, 2000, 5.0), (0, 0, 1, 5, 2600, 9.0), (0, 1, 3, W - 1, T + 20, 6.0),
                                    (1, 0, 0, 0, 512, 7.0), (1, 1, G - 1, W - 15, 40, 8.0)]:
         k[0, l, h, t, :] = (q[0, l, h * G + g, i, :].float() * scale).to(torch.bfloat16)
-    shape = B.make_shape(q, k, v)
+    shape = B.make_shape(q, k, v, window_chunk=chunk)
     ws = torch.empty((B.sablock_window_attention_workspace_bytes(shape),), dtype=torch.uint8, device="cuda")
     out = torch.full((ns, nl, G * Hkv, W, D), float("nan"), dtype=torch.float32, device="cuda")
     lse = torch.full((ns * nl * Hkv, G * W), float("nan"), dtype=torch.float32, device="cuda")

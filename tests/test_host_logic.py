@@ -27,10 +27,11 @@ def _shape(**kw):
     s = B.CShape()
     s.n_seq, s.n_layers, s.n_q_heads, s.n_kv_heads = 1, 1, 4, 2
     s.head_dim, s.seq_len, s.window, s.dtype = 64, 2048, 16, B.SABLOCK_F32
+    s.tuning.compute_units = 256            # plans are made for this count: no device is asked
     for a, (qv, kv) in enumerate([(4 * 16 * 64, 2 * 2048 * 64), (4 * 16 * 64, 2 * 2048 * 64), (16 * 64, 2048 * 64), (64, 64)]):
         s.q_stride[a], s.k_stride[a], s.v_stride[a] = qv, kv, kv
     for k, v in kw.items():
-        setattr(s, k, v)
+        setattr(s.tuning if hasattr(B.CTuning, k) else s, k, v)
     return s
 
 
@@ -44,10 +45,15 @@ def test_exports_match_header(lib):
 
 
 def test_struct_layout_matches_header():
-    # 8 int32 then 3 x 4 int64, no padding surprises
-    assert ctypes.sizeof(B.CShape) == 8 * 4 + 12 * 8
-    assert B.CShape.q_stride.offset == 32 and B.CShape.v_stride.offset == 96
+    # 8 int32, 3 x 4 int64, then the 8 int32 of the launch parameters: no padding surprises
+    assert ctypes.sizeof(B.CShape) == 8 * 4 + 12 * 8 + 8 * 4
+    assert B.CShape.q_stride.offset == 32 and B.CShape.v_stride.offset == 96 and B.CShape.tuning.offset == 128
+    assert ctypes.sizeof(B.CTuning) == 32 and B.CTuning.stats_per_key.offset == 16
     assert ctypes.sizeof(B.CHparams) == 16
+    hdr = open(os.path.join(ROOT, "include", "sablock.h")).read()
+    body = re.search(r"typedef struct \{([^}]*)\} sablock_tuning;", hdr).group(1)
+    fields = re.findall(r"int32_t\s+(\w+)", body)
+    assert fields == [f[0] for f in B.CTuning._fields_]
 
 
 def test_workspace_bytes_and_shape_validation(lib):
@@ -60,6 +66,42 @@ def test_workspace_bytes_and_shape_validation(lib):
         assert ei.value.status == status, bad
     with pytest.raises(B.SablockError):
         B.sablock_workspace_bytes(_shape(), -1, 10)
+
+
+def test_launch_parameters_are_validated_and_change_only_the_plan(lib):
+    # out-of-range launch parameters are refused; valid ones change workspace sizes, never the status
+    llama = dict(dtype=B.SABLOCK_BF16, head_dim=128, n_q_heads=32, n_kv_heads=8, seq_len=131072, window=32)
+    def shape(**kw):                        # dense strides for the Llama geometry
+        s = _shape(**kw)
+        for a, (qv, kv) in enumerate([(32 * 32 * 128, 8 * 131072 * 128), (32 * 32 * 128, 8 * 131072 * 128),
+                                      (32 * 128, 131072 * 128), (128, 128)]):
+            s.q_stride[a], s.k_stride[a], s.v_stride[a] = qv, kv, kv
+        return s
+
+    for bad in (dict(compute_units=-1), dict(score_chunk=64), dict(score_chunk=1 << 20), dict(window_chunk=8),
+                dict(topb_slices=65), dict(topb_slices=-2), dict(stats_per_key=2)):
+        with pytest.raises(B.SablockError) as ei:
+            B.sablock_workspace_bytes(shape(**llama, **bad), 100, 112)
+        assert ei.value.status == 1, bad
+    s = shape(**llama)
+    s.tuning.reserved[1] = 3
+    with pytest.raises(B.SablockError):
+        B.sablock_workspace_bytes(s, 100, 112)
+    base = B.sablock_workspace_bytes(shape(**llama), 2100, 992)
+    # shorter chunks = more chunk partials of the row statistics; more compute units = more chunks per problem
+    few = B.sablock_workspace_bytes(shape(**llama), 0, 0)
+    assert B.sablock_workspace_bytes(shape(**llama, score_chunk=1024), 0, 0) > few
+    assert B.sablock_workspace_bytes(shape(**llama, compute_units=4096), 0, 0) > few
+    assert B.sablock_workspace_bytes(shape(**llama, topb_slices=1), 2100, 992) < base      # no sliced Top-B lists
+    # the library reads no environment variable
+    os.environ["SABLOCK_SCORE_CHUNK"] = "1024"
+    try:
+        assert B.sablock_workspace_bytes(shape(**llama), 0, 0) == few
+    finally:
+        del os.environ["SABLOCK_SCORE_CHUNK"]
+    src = os.path.join(ROOT, "paper_2510_22556_amd", "csrc")
+    for f in os.listdir(src):
+        assert "getenv" not in open(os.path.join(src, f)).read(), f
 
 
 def test_calls_reject_bad_host_arguments_before_launch(lib):
