@@ -71,9 +71,10 @@ def problem_views(q, k, v, p, n_layers, Hkv, G):
 
 
 def check_problem(oracle, run: GpuRun, p, q_raw, k_raw, v_raw, seg_off, eps, alpha, eta, tau, append_window=True,
-                  end_to_end=True):
+                  end_to_end=True, score_ref=None):
     """Stage-wise parity of problem p (each oracle stage fed with the GPU's previous output),
-    then end-to-end parity with every disagreement explained by a near-tie."""
+    then end-to-end parity with every disagreement explained by a near-tie.  ``score_ref``: the oracle's
+    (s, ent) of this problem when the caller already has them (several runs over the same tensors)."""
     W = q_raw.shape[1]
     L = k_raw.shape[0]
     T = L - W
@@ -81,7 +82,7 @@ def check_problem(oracle, run: GpuRun, p, q_raw, k_raw, v_raw, seg_off, eps, alp
     B_ = run.budget
     cand = run.cand
     # --- stage 1: scores
-    s_ref, e_ref = oracle.score(widen(q_raw), widen(k_raw), eps)
+    s_ref, e_ref = score_ref if score_ref is not None else oracle.score(widen(q_raw), widen(k_raw), eps)
     close(run.s[p], s_ref, f"s[p={p}]")
     close(run.e[p], e_ref, f"ent[p={p}]")
     # --- stage 2: refinement of the GPU's own s, e
@@ -112,12 +113,19 @@ def check_problem(oracle, run: GpuRun, p, q_raw, k_raw, v_raw, seg_off, eps, alp
     idx_o, n_o = oracle.select(st_o, seg_off, b_o, g_o, B_)
     assert n_o == run.n_sel[p]
     return explain_mismatches(st_o, seg_off, cand, B_, f32(tau), b_o, g_o, idx_o[:n_o], run.b[p][:K], run.g[p][:K],
-                              run.idx[p][:n_o])
+                              run.idx[p][:n_o], st_g=run.st[p])
 
 
-def explain_mismatches(st_o, seg_off, cand, B_, tau, b_o, g_o, idx_o, b_g, g_g, idx_g):
+def explain_mismatches(st_o, seg_off, cand, B_, tau, b_o, g_o, idx_o, b_g, g_g, idx_g, st_g=None):
     """Every segment where the two chains disagree must contain a decision whose two
-    competing fp64 values differ by less than the score tolerance.  Returns the count."""
+    competing fp64 values differ by less than the score tolerance.  Returns the count.
+
+    A differing implicit budget must come from tokens whose Top-B membership flipped, and every flipped token
+    of the segment must itself sit within the tolerance of the oracle's Top-B threshold (``st_g``, the refined
+    scores the other chain ranked, names the flipped tokens; without it, some token of the segment must).  Any
+    other difference is handed to the enumerator, which reports the tightest comparison among all the
+    segment's decisions (block ranking, cut block, accept test); only segments of 65 536 tokens or more are
+    skipped (the pure-Python enumeration would take minutes)."""
     T = int(seg_off[-1])
     sel_o = np.zeros(T, bool)
     sel_o[idx_o] = True
@@ -127,6 +135,13 @@ def explain_mismatches(st_o, seg_off, cand, B_, tau, b_o, g_o, idx_o, b_g, g_g, 
     nB = min(B_, T)
     v_star = st_o[order[nB - 1]] if nB > 0 else 0.0
     top_set = set(order[:nB].tolist())
+    in_top_o = np.zeros(T, bool)
+    in_top_o[order[:nB]] = True
+    in_top_g = None
+    if st_g is not None:
+        st_g = np.asarray(st_g, dtype=np.float64)[:T]
+        in_top_g = np.zeros(T, bool)
+        in_top_g[np.lexsort((np.arange(T), -st_g))[:nB]] = True
     st_list = None
     n_bad = 0
     for k in range(len(seg_off) - 1):
@@ -136,10 +151,15 @@ def explain_mismatches(st_o, seg_off, cand, B_, tau, b_o, g_o, idx_o, b_g, g_g, 
         n_bad += 1
         if b_o[k] != b_g[k]:
             # a Top-B membership flipped: some token of the segment sits at the threshold
-            gap = np.abs(st_o[a:b] - v_star).min() / max(v_star, 1e-300)
+            if in_top_g is not None:
+                flipped = np.nonzero(in_top_o[a:b] != in_top_g[a:b])[0]
+                assert flipped.size, f"segment {k}: b_k {b_o[k]} vs {b_g[k]} although no Top-B membership differs"
+                gap = np.abs(st_o[a:b][flipped] - v_star).max() / max(v_star, 1e-300)
+            else:
+                gap = np.abs(st_o[a:b] - v_star).min() / max(v_star, 1e-300)
             assert gap <= RTOL, f"segment {k}: b_k {b_o[k]} vs {b_g[k]} without a score within tolerance of the Top-B threshold"
             continue
-        if b - a >= 4096:
+        if b - a >= 65536:
             continue
         if st_list is None:
             st_list = st_o.tolist()

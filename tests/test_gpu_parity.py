@@ -32,15 +32,39 @@ def _device_workload(torch, w, n_layers=None):
     return q, k, v, off, ptr
 
 
-def _check_all(oracle, w, run, q, k, v, off, ptr, problems, tau=None, end_to_end=True):
+def _check_all(oracle, w, run, q, k, v, off, ptr, problems, tau=None, end_to_end=True, score_cache=None):
+    """Problems `problems` of `run` against the oracle; returns the number of segments whose end-to-end
+    difference was explained by a near-tie.  `score_cache` (a dict) keeps the oracle's scores of a problem for
+    further runs over the same tensors (other budgets, the row_lse route)."""
     n_layers = q.shape[1]
     total = 0
     for p in problems:
         qr, kr, vr, seq = H.problem_views(q, k, v, p, n_layers, w.n_kv_heads, w.G)
         so = off[ptr[seq]:ptr[seq + 1]]
+        ref = None
+        if score_cache is not None:
+            if p not in score_cache:
+                score_cache[p] = oracle.score(H.widen(qr), H.widen(kr), w.eps)
+            ref = score_cache[p]
         total += H.check_problem(oracle, run, p, qr, kr, vr, so, w.eps, w.alpha, w.eta, tau or w.tau,
-                                 end_to_end=end_to_end)
+                                 end_to_end=end_to_end, score_ref=ref)
     return total
+
+
+def _row_lse_from_window_attention(torch, q, k, v):
+    """The rows' log-sum-exp as a prefill would hand it over: from sablock_window_attention, [P][G * W]."""
+    from paper_2510_22556_amd import binding as B
+
+    shape = B.make_shape(q, k, v)
+    ns, nl, Hq, W, D = q.shape
+    ws = torch.empty((B.sablock_window_attention_workspace_bytes(shape),), dtype=torch.uint8, device="cuda")
+    out = torch.empty((ns, nl, Hq, W, D), dtype=torch.float32, device="cuda")
+    lse = torch.full((ns, nl, Hq, W), float("nan"), dtype=torch.float32, device="cuda")
+    B.sablock_window_attention(shape, q, k, v, out, lse, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(lse).all())
+    del out, ws
+    return lse
 
 
 def test_tiny_fp32_all_stages(oracle, torch_cuda):
@@ -567,6 +591,35 @@ def test_llama8b_32k_heavy_hitters_three_budgets(oracle, torch_cuda):
     assert mean_g[0] <= mean_g[1] <= mean_g[2]          # larger budgets pick larger blocks (Sec. 3.3 trend)
 
 
+def test_llama8b_32k_full_size_three_budgets_both_routes(oracle, torch_cuda):
+    # configuration 3 at its stated size, in the launch configuration bench.py times: all 32 layers x 8 KV heads
+    # of 32 768 tokens in ONE call (256 problems), cache budgets 96 / 256 / 1 024; three sampled problems per
+    # budget end to end against the oracle's own fp64 chain, properties that hold at any size on all problems.
+    # Then the same through the row_lse route (log-sum-exp from sablock_window_attention, K read once).
+    torch = torch_cuda
+    w = synth.WORKLOADS["llama8b_32k_heavy"]
+    q, k, v, off, ptr = _device_workload(torch, w)
+    assert q.shape[1] == 32 and k.shape[3] == 32768
+    lse = _row_lse_from_window_attention(torch, q, k, v)
+    cache = {}
+    sample = [5, 8 * 13 + 2, 255]
+    for route in ("two_pass", "row_lse"):
+        mean_g = []
+        for bi in range(3):
+            run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(bi), w.eps, w.alpha, w.eta, w.tau,
+                           row_lse=lse if route == "row_lse" else None)
+            B_ = w.budget(bi)
+            assert np.allclose(run.s.sum(axis=1), w.window, rtol=1e-4)
+            assert (run.n_sel == B_).all() and (run.b.sum(axis=1) == B_).all()
+            assert (np.diff(run.idx, axis=1) > 0).all() and run.idx.min() >= 0 and run.idx.max() < w.T
+            assert run.k_out.shape[1] == w.cache_budgets[bi]
+            n_mis = _check_all(oracle, w, run, q, k, v, off, ptr, sample, score_cache=cache)
+            assert n_mis <= 6, (route, bi, n_mis)
+            mean_g.append(float((run.g * run.b).sum() / run.b.sum()))
+            del run
+        assert mean_g[0] <= mean_g[1] <= mean_g[2]      # larger budgets pick larger blocks (Sec. 3.3 trend)
+
+
 def test_paper_default_settings_three_budgets(oracle, torch_cuda):
     # the paper's own hyperparameters (Sec. 4.1): window of 8, candidate block sizes {1, 2, 3, 5, 7, 9, 11, 13};
     # two of the 32 layers at cache budgets 96 / 128 / 1024
@@ -594,7 +647,7 @@ def test_llama8b_4x64k_window64_batched(oracle, torch_cuda):
     run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau)
     assert (run.n_sel == w.budget()).all()
     assert np.allclose(run.s.sum(axis=1), w.window, rtol=1e-4)
-    _check_all(oracle, w, run, q, k, v, off, ptr, [0, 8 + 3, 16 + 5, 24 + 7], end_to_end=False)
+    assert _check_all(oracle, w, run, q, k, v, off, ptr, [0, 8 + 3, 16 + 5, 24 + 7]) <= 12
 
 
 def test_llama8b_128k_full_size_sampled(oracle, torch_cuda):
@@ -617,7 +670,19 @@ def test_llama8b_128k_full_size_sampled(oracle, torch_cuda):
     seg_of = np.searchsorted(off, run.idx, side="right") - 1                       # blocks never leave their segment:
     for p in (0, 100, 255):                                                        # per segment, exactly b_k tokens selected
         assert (np.bincount(seg_of[p], minlength=len(off) - 1) == run.b[p][:len(off) - 1]).all()
-    _check_all(oracle, w, run, q, k, v, off, ptr, [3, 130, 255])
+    cache = {}
+    assert _check_all(oracle, w, run, q, k, v, off, ptr, [3, 130, 255], score_cache=cache) <= 6
+    # the row_lse route at the same size (the rows' log-sum-exp from sablock_window_attention, K read once by the
+    # scoring step): the same sampled problems against the ORACLE's chain, not against the two-pass result
+    s_two_pass = run.s
+    del run
+    lse = _row_lse_from_window_attention(torch, q, k, v)
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau, row_lse=lse)
+    assert np.allclose(run.s.sum(axis=1), w.window, rtol=1e-4)
+    assert (run.n_sel == B_).all() and (run.b.sum(axis=1) == B_).all()
+    assert (np.diff(run.idx, axis=1) > 0).all() and run.idx.min() >= 0 and run.idx.max() < w.T
+    assert _check_all(oracle, w, run, q, k, v, off, ptr, [3, 130, 255], score_cache=cache) <= 6
+    np.testing.assert_allclose(run.s, s_two_pass, rtol=2e-4, atol=1e-9)           # all 256 problems, both routes
 
 
 def test_llama8b_4x64k_full_size_sampled(oracle, torch_cuda):
@@ -636,7 +701,18 @@ def test_llama8b_4x64k_full_size_sampled(oracle, torch_cuda):
     assert (np.diff(run.idx, axis=1) > 0).all() and run.idx.min() >= 0 and run.idx.max() < w.T
     assert run.k_out.shape[1] == w.cache_budgets[0]
     per_seq = w.n_layers * w.n_kv_heads
-    _check_all(oracle, w, run, q, k, v, off, ptr, [5, per_seq + 77, 2 * per_seq + 130, 4 * per_seq - 1], end_to_end=False)
+    sample = [5, per_seq + 77, 2 * per_seq + 130, 4 * per_seq - 1]
+    cache = {}
+    assert _check_all(oracle, w, run, q, k, v, off, ptr, sample, score_cache=cache) <= 12
+    # the row_lse route (log-sum-exp from sablock_window_attention's 256-row kernel) against the oracle's chain
+    s_two_pass = run.s
+    del run
+    lse = _row_lse_from_window_attention(torch, q, k, v)
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau, row_lse=lse)
+    assert (run.n_sel == B_).all() and (run.b.sum(axis=1) == B_).all()
+    assert (np.diff(run.idx, axis=1) > 0).all() and run.idx.min() >= 0 and run.idx.max() < w.T
+    assert _check_all(oracle, w, run, q, k, v, off, ptr, sample, score_cache=cache) <= 12
+    np.testing.assert_allclose(run.s, s_two_pass, rtol=2e-4, atol=1e-9)
 
 
 def test_segmentation_matches_oracle_and_feeds_the_path(oracle, torch_cuda):
