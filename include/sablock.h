@@ -136,6 +136,24 @@ SABLOCK_API sablock_status sablock_score(const sablock_shape *shape, const void 
                              float *s_out, float *ent_out,
                              void *ws, size_t ws_bytes, void *stream);
 
+/* sablock_score for callers that cannot allocate or hand over a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments (minus ws), same kernels, same results as
+ * sablock_score; the row statistics that sablock_score keeps in the caller's workspace live in an array that is
+ * part of the library's device code (SABLOCK_STATIC_SCRATCH_BYTES per GPU, held from the moment the library is
+ * loaded on that GPU until the process ends).  The call allocates and frees nothing, on the device or through
+ * any library.
+ * Limit: a call whose statistics need more than SABLOCK_STATIC_SCRATCH_BYTES (the sablock_score part of
+ *   sablock_workspace_bytes: about 2 KiB per problem and key chunk) returns UNSUPPORTED and launches nothing.  All
+ *   five configurations this library is measured on fit (the largest, 1 024 problems of 256 rows, takes 4 MiB).
+ *   With row_lse given no scratch is used at all.
+ * Sharing: all calls on one GPU use that GPU's one array.  Calls ordered on one stream are safe; calls that may
+ *   overlap on one GPU (other streams, other host threads) race on it: give those sablock_score and a workspace
+ *   each.  Nothing needs clearing between calls: each call writes every statistic before it reads it. */
+#define SABLOCK_STATIC_SCRATCH_BYTES (8u << 20)
+SABLOCK_API sablock_status sablock_score_static(const sablock_shape *shape, const void *q_win, const void *k,
+                                    const float *row_lse /* nullable */, float eps,
+                                    float *s_out, float *ent_out, void *stream);
+
 /* Segment-guided refinement (Alg. 1).  Per segment S_k of the compressible region:
  *   I_k = mean s_t (Eq. Ik), D_k = mean ent_t (Eq. Dk), omega_k = I_k (1 + eta D_k) (Eq. omegak);
  *   s_tilde_out[p][t] = s_t (1 + alpha omega_k(t)), t in [0, T)            (Eq. st_tilde)

@@ -50,6 +50,35 @@ sablock_status current_device_cus(int32_t *out)
     return SABLOCK_OK;
 }
 
+// Scratch memory of sablock_score_static: one array per GPU, part of the library's code object, so it exists from
+// the moment the library is loaded on a device until the process ends and no allocation call is ever made for
+// it.  In host code the array's name is only a handle: the address a kernel can use comes from
+// hipGetSymbolAddress, asked once per device with that device current (every GPU has its own copy at its own
+// address) and remembered.
+__device__ __align__(256) static unsigned char scratch[SABLOCK_STATIC_SCRATCH_BYTES];
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+
+sablock_status static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
+        (void)hipGetLastError();
+        return fail(SABLOCK_ERR_DEVICE, "sablock_score_static: no current HIP device");
+    }
+    if (dev >= MAX_DEVICES) return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_score_static: device %d: at most %d devices", dev, MAX_DEVICES);
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return fail(SABLOCK_ERR_DEVICE, "sablock_score_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);     // concurrent first calls store the same address
+    }
+    *out = p;
+    return SABLOCK_OK;
+}
+
 sablock_status make_dims(const sablock_shape *s, Dims *d)
 {
     if (!s) return fail(SABLOCK_ERR_INVALID_ARG, "shape is NULL");
@@ -158,7 +187,7 @@ sablock_status sablock_workspace_bytes(const sablock_shape *shape, int32_t max_s
     return SABLOCK_OK;
 }
 
-// argument checks of the scoring call and the bytes of workspace it needs
+// shared by sablock_score and sablock_score_static: everything but where the scratch memory comes from
 static sablock_status score_checked(const char *who, const sablock_shape *shape, const void *q_win, const void *k,
                                     const float *row_lse, float eps, float *s_out, float *ent_out,
                                     Dims *d, size_t *need)
@@ -192,6 +221,27 @@ sablock_status sablock_score(const sablock_shape *shape, const void *q_win, cons
     if (need && (!ws || ws_bytes < need))
         return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_score: workspace %zu < %zu bytes", ws_bytes, need);
     return score_launch("sablock_score", d, q_win, k, row_lse, eps, s_out, ent_out, ws, stream);
+}
+
+sablock_status sablock_score_static(const sablock_shape *shape, const void *q_win, const void *k,
+                                    const float *row_lse, float eps, float *s_out, float *ent_out, void *stream)
+{
+    Dims d;
+    size_t need = 0;
+    sablock_status st = score_checked("sablock_score_static", shape, q_win, k, row_lse, eps, s_out, ent_out, &d, &need);
+    if (st != SABLOCK_OK) return st;
+    if (need > SABLOCK_STATIC_SCRATCH_BYTES)
+        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_score_static: the row statistics of this call need %zu bytes of scratch, "
+                    "the static array holds %zu; use sablock_score with a workspace, or fewer problems per call",
+                    need, (size_t)SABLOCK_STATIC_SCRATCH_BYTES);
+    void *ptr = nullptr;
+    if (need) {
+        st = static_scratch(&ptr);
+        if (st != SABLOCK_OK) return st;
+    }
+    // every word of the statistics that the column pass reads is written by this call's own statistics kernels
+    // first, so the previous call's contents need no clearing
+    return score_launch("sablock_score_static", d, q_win, k, row_lse, eps, s_out, ent_out, ptr, stream);
 }
 
 sablock_status sablock_refine(const sablock_shape *shape, const float *s, const float *ent,
