@@ -154,6 +154,15 @@ SABLOCK_API sablock_status sablock_score_static(const sablock_shape *shape, cons
                                     const float *row_lse /* nullable */, float eps,
                                     float *s_out, float *ent_out, void *stream);
 
+/* Measurement aid (no step of the method): streams K exactly as the MFMA scoring kernels do - the same split of
+ * every problem's keys into workgroups, the same direct-to-LDS ring per wavefront - and computes nothing.  With
+ * read_lds != 0 every key tile is also read from LDS into registers, as the scoring kernels do before their
+ * matrix products.  Its duration is what the memory system delivers to this access pattern, the yardstick the
+ * scoring kernels' times are compared with (bench.py --yardstick).  bf16, head_dim 128 only (UNSUPPORTED
+ * otherwise); sink: 4 bytes of device memory, practically never written. */
+SABLOCK_API sablock_status sablock_stream_probe(const sablock_shape *shape, const void *k, int32_t read_lds,
+                                    void *sink, void *stream);
+
 /* Segment-guided refinement (Alg. 1).  Per segment S_k of the compressible region:
  *   I_k = mean s_t (Eq. Ik), D_k = mean ent_t (Eq. Dk), omega_k = I_k (1 + eta D_k) (Eq. omegak);
  *   s_tilde_out[p][t] = s_t (1 + alpha omega_k(t)), t in [0, T)            (Eq. st_tilde)

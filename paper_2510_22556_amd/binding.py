@@ -26,7 +26,7 @@ EXPORTS = ("sablock_version", "sablock_last_error", "sablock_workspace_bytes", "
            "sablock_segment_count", "sablock_segment_offsets", "sablock_decode_workspace_bytes",
            "sablock_decode_attention", "sablock_score_all_heads_workspace_bytes", "sablock_score_all_heads",
            "sablock_compact_shared", "sablock_search_select", "sablock_window_attention_workspace_bytes",
-           "sablock_window_attention", "sablock_score_static")
+           "sablock_window_attention", "sablock_score_static", "sablock_stream_probe")
 
 
 class SablockError(RuntimeError):
@@ -70,6 +70,7 @@ def load():
         lib.sablock_workspace_bytes.argtypes = [sp, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
         lib.sablock_score.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp, ctypes.c_size_t, vp]
         lib.sablock_score_static.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp]
+        lib.sablock_stream_probe.argtypes = [sp, vp, i32, vp, vp]
         lib.sablock_refine.argtypes = [sp, vp, vp, vp, ctypes.POINTER(i32), i32, ctypes.POINTER(CHparams),
                                        vp, vp, vp, ctypes.c_size_t, vp]
         lib.sablock_search_blocks.argtypes = [sp, vp, vp, ctypes.POINTER(i32), i32, ctypes.POINTER(i32), i32,
@@ -167,6 +168,11 @@ def n_problems(shape: CShape) -> int:
 def sablock_score(shape: CShape, q, k, s_out, ent_out, ws, eps: float = 1e-6, row_lse=None, stream=None):
     _check(load().sablock_score(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(row_lse), eps, _ptr(s_out),
                                 _ptr(ent_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def sablock_stream_probe(shape: CShape, k, sink, read_lds: bool = False, stream=None):
+    """Measurement aid: K through the scoring kernels' load ring, no arithmetic."""
+    _check(load().sablock_stream_probe(ctypes.byref(shape), _ptr(k), 1 if read_lds else 0, _ptr(sink), _stream(stream)))
 
 
 STATIC_SCRATCH_BYTES = 8 << 20

@@ -244,6 +244,17 @@ sablock_status sablock_score_static(const sablock_shape *shape, const void *q_wi
     return score_launch("sablock_score_static", d, q_win, k, row_lse, eps, s_out, ent_out, ptr, stream);
 }
 
+sablock_status sablock_stream_probe(const sablock_shape *shape, const void *k, int32_t read_lds, void *sink, void *stream)
+{
+    Dims d;
+    sablock_status st = make_dims(shape, &d);
+    if (st != SABLOCK_OK) return st;
+    if (!k || !sink) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_stream_probe: NULL argument");
+    if (!aligned16(k)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_stream_probe: K must be 16-byte aligned");
+    if (!stream_probe_supported(d)) return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_stream_probe: needs bf16 and head_dim 128");
+    return dev(launch_stream_probe(d, k, read_lds, sink, static_cast<hipStream_t>(stream)), "sablock_stream_probe");
+}
+
 sablock_status sablock_refine(const sablock_shape *shape, const float *s, const float *ent,
                               const int32_t *seg_off, const int32_t *seg_ptr, int32_t max_segments,
                               const sablock_hparams *hp, float *s_tilde_out, float *omega_out,

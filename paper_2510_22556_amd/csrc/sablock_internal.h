@@ -91,6 +91,10 @@ size_t score_mfma_ws_bytes(const Dims &d);
 hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const float *row_lse, float eps,
                              float *s_out, float *ent_out, void *ws, hipStream_t st);
 
+// measurement aid: K streamed through the scoring kernels' load ring with no arithmetic
+bool stream_probe_supported(const Dims &d);
+hipError_t launch_stream_probe(const Dims &d, const void *k, int read_lds, void *sink, hipStream_t st);
+
 // head mean over all query heads of a layer (one score row per layer)
 bool score_all_heads_supported(const Dims &d);
 size_t score_all_heads_ws_bytes(const Dims &d);

@@ -1516,6 +1516,71 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     return hipGetLastError();
 }
 
+namespace {
+
+// ---- measurement aid: the scoring kernels' key stream without their arithmetic
+// Same chunk plan, same workgroups, same direct-to-LDS ring and waits as score_mfma_columns; per subtile a
+// wavefront either only waits for the subtile and refills its buffer (READ_LDS = false), or also reads the whole
+// subtile from LDS into registers as the scoring kernels do (READ_LDS = true).  What this kernel takes is what the
+// memory system delivers to the scoring kernels' access pattern: the yardstick their times are compared with.
+template <bool READ_LDS>
+__global__ void __launch_bounds__(WAVES * 64)
+stream_probe_kernel(ScoreArgs a, uint32_t *sink)
+{
+    extern __shared__ __attribute__((aligned(8192))) char lds[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    char *ring = lds + __builtin_amdgcn_readfirstlane(wave) * RING_BYTES;
+    const WaveWork w = wave_work(a, wave);
+    KeyStream<NBUF> ks;
+    ks.init(w.kp, a.d.ks[3], ring, w.first, w.n_sub, a.d.L, lane);
+    ks.prime();
+    uint32_t x = 0;
+    for (int u = 0; u < w.n_sub; ++u) {
+        if (READ_LDS) {
+            bf16x8 kb[8];
+            ks.fetch_vgpr(u, kb);
+#pragma unroll
+            for (int s = 0; s < 8; ++s) x ^= ((const uint32_t *)&kb[s])[0] ^ ((const uint32_t *)&kb[s])[3];
+        } else {
+            wait_loads(min(NBUF - 1, w.n_sub - 1 - u));
+            x ^= *reinterpret_cast<const volatile uint32_t *>(ring + (u % NBUF) * BUF_BYTES + lane * 4);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (u + NBUF < w.n_sub) ks.issue(u + NBUF);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (x == 0x5ab10c4bu) *sink = x;                           // keeps the reads alive; practically never taken
+}
+
+}  // namespace
+
+bool stream_probe_supported(const Dims &d) { return d.dtype == SABLOCK_BF16 && d.D == 128; }
+
+hipError_t launch_stream_probe(const Dims &d, const void *k, int read_lds, void *sink, hipStream_t st)
+{
+    static thread_local PerDeviceOnce attr_once;
+    if (attr_once.needed()) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_probe_kernel<false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, P2_LDS);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_probe_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, P2_LDS);
+        if (e != hipSuccess) return e;
+        attr_once.done();
+    }
+    const Plan pl = make_plan(d);
+    ScoreArgs a = {};
+    a.d = d;
+    a.k = static_cast<const uint16_t *>(k);
+    a.chunk_len = pl.chunk_len;
+    a.n_chunks = pl.n_chunks;
+    a.p0 = 0;
+    dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
+    if (read_lds) hipLaunchKernelGGL(stream_probe_kernel<true>, grid, dim3(WAVES * 64), P2_LDS, st, a, static_cast<uint32_t *>(sink));
+    else hipLaunchKernelGGL(stream_probe_kernel<false>, grid, dim3(WAVES * 64), P2_LDS, st, a, static_cast<uint32_t *>(sink));
+    return hipGetLastError();
+}
+
 // ---- head mean over all query heads of a layer (Eq. barA, literal): shapes with up to 128 window-query rows
 bool score_all_heads_supported(const Dims &d)
 {
