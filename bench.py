@@ -291,10 +291,12 @@ def yardstick(torch, B, path, reps=10):
         return e0.elapsed_time(e1) / n
 
     k_bytes = w.n_seq * w.n_layers * w.n_kv_heads * w.seq_len * w.head_dim * elt
-    for read_lds in (False, True):
-        ms = timed(lambda: B.sablock_stream_probe(shape, k, sink, read_lds), reps)
-        out["stream_all_K" + ("_with_lds_reads" if read_lds else "")] = {
-            "bytes": k_bytes, "ms": ms, "TBps": k_bytes / (ms * 1e-3) / 1e12}
+    for read_lds, stores in ((False, False), (True, False), (True, True)):
+        so, eo = (buf.s, buf.ent) if stores else (None, None)
+        ms = timed(lambda: B.sablock_stream_probe(shape, k, sink, read_lds, so, eo), reps)
+        out["stream_all_K" + ("_with_lds_reads" if read_lds else "") + ("_and_score_stores" if stores else "")] = {
+            "bytes": k_bytes + (2 * 4 * w.n_seq * w.n_layers * w.n_kv_heads * w.seq_len if stores else 0),
+            "ms": ms, "TBps_of_K": k_bytes / (ms * 1e-3) / 1e12}
     G = w.n_q_heads // w.n_kv_heads
     out["stream_resident_groups"] = {}
     for n in (1, 2, 4, 8):

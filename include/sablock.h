@@ -157,10 +157,13 @@ SABLOCK_API sablock_status sablock_score_static(const sablock_shape *shape, cons
 /* Measurement aid (no step of the method): streams K exactly as the MFMA scoring kernels do - the same split of
  * every problem's keys into workgroups, the same direct-to-LDS ring per wavefront - and computes nothing.  With
  * read_lds != 0 every key tile is also read from LDS into registers, as the scoring kernels do before their
- * matrix products.  Its duration is what the memory system delivers to this access pattern, the yardstick the
- * scoring kernels' times are compared with (bench.py --yardstick).  bf16, head_dim 128 only (UNSUPPORTED
- * otherwise); sink: 4 bytes of device memory, practically never written. */
+ * matrix products.  With s_out and ent_out given ([P][L] float each; both or neither) it also writes 4 bytes per
+ * key into each, with the store pattern of the scoring step's column pass (the values are meaningless).  Its
+ * duration is what the memory system delivers to this access pattern, the yardstick the scoring kernels' times
+ * are compared with (bench.py --yardstick).  bf16, head_dim 128 only (UNSUPPORTED otherwise); sink: 4 bytes of
+ * device memory, practically never written. */
 SABLOCK_API sablock_status sablock_stream_probe(const sablock_shape *shape, const void *k, int32_t read_lds,
+                                    float *s_out /* nullable */, float *ent_out /* nullable */,
                                     void *sink, void *stream);
 
 /* Segment-guided refinement (Alg. 1).  Per segment S_k of the compressible region:

@@ -70,7 +70,7 @@ def load():
         lib.sablock_workspace_bytes.argtypes = [sp, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
         lib.sablock_score.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp, ctypes.c_size_t, vp]
         lib.sablock_score_static.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp]
-        lib.sablock_stream_probe.argtypes = [sp, vp, i32, vp, vp]
+        lib.sablock_stream_probe.argtypes = [sp, vp, i32, vp, vp, vp, vp]
         lib.sablock_refine.argtypes = [sp, vp, vp, vp, ctypes.POINTER(i32), i32, ctypes.POINTER(CHparams),
                                        vp, vp, vp, ctypes.c_size_t, vp]
         lib.sablock_search_blocks.argtypes = [sp, vp, vp, ctypes.POINTER(i32), i32, ctypes.POINTER(i32), i32,
@@ -170,9 +170,11 @@ def sablock_score(shape: CShape, q, k, s_out, ent_out, ws, eps: float = 1e-6, ro
                                 _ptr(ent_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
-def sablock_stream_probe(shape: CShape, k, sink, read_lds: bool = False, stream=None):
-    """Measurement aid: K through the scoring kernels' load ring, no arithmetic."""
-    _check(load().sablock_stream_probe(ctypes.byref(shape), _ptr(k), 1 if read_lds else 0, _ptr(sink), _stream(stream)))
+def sablock_stream_probe(shape: CShape, k, sink, read_lds: bool = False, s_out=None, ent_out=None, stream=None):
+    """Measurement aid: K through the scoring kernels' load ring, no arithmetic; with ``s_out`` / ``ent_out`` also
+    the column pass's stores."""
+    _check(load().sablock_stream_probe(ctypes.byref(shape), _ptr(k), 1 if read_lds else 0, _ptr(s_out), _ptr(ent_out),
+                                       _ptr(sink), _stream(stream)))
 
 
 STATIC_SCRATCH_BYTES = 8 << 20

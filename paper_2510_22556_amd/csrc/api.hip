@@ -244,15 +244,19 @@ sablock_status sablock_score_static(const sablock_shape *shape, const void *q_wi
     return score_launch("sablock_score_static", d, q_win, k, row_lse, eps, s_out, ent_out, ptr, stream);
 }
 
-sablock_status sablock_stream_probe(const sablock_shape *shape, const void *k, int32_t read_lds, void *sink, void *stream)
+sablock_status sablock_stream_probe(const sablock_shape *shape, const void *k, int32_t read_lds, float *s_out,
+                                    float *ent_out, void *sink, void *stream)
 {
     Dims d;
     sablock_status st = make_dims(shape, &d);
     if (st != SABLOCK_OK) return st;
     if (!k || !sink) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_stream_probe: NULL argument");
+    if ((s_out == nullptr) != (ent_out == nullptr))
+        return fail(SABLOCK_ERR_INVALID_ARG, "sablock_stream_probe: s_out and ent_out must both be given or both be NULL");
     if (!aligned16(k)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_stream_probe: K must be 16-byte aligned");
     if (!stream_probe_supported(d)) return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_stream_probe: needs bf16 and head_dim 128");
-    return dev(launch_stream_probe(d, k, read_lds, sink, static_cast<hipStream_t>(stream)), "sablock_stream_probe");
+    return dev(launch_stream_probe(d, k, read_lds, s_out, ent_out, sink, static_cast<hipStream_t>(stream)),
+               "sablock_stream_probe");
 }
 
 sablock_status sablock_refine(const sablock_shape *shape, const float *s, const float *ent,

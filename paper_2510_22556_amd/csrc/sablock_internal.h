@@ -93,7 +93,8 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
 
 // measurement aid: K streamed through the scoring kernels' load ring with no arithmetic
 bool stream_probe_supported(const Dims &d);
-hipError_t launch_stream_probe(const Dims &d, const void *k, int read_lds, void *sink, hipStream_t st);
+hipError_t launch_stream_probe(const Dims &d, const void *k, int read_lds, float *s_out, float *e_out, void *sink,
+                               hipStream_t st);
 
 // head mean over all query heads of a layer (one score row per layer)
 bool score_all_heads_supported(const Dims &d);

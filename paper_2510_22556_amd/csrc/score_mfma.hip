@@ -518,13 +518,11 @@ __device__ __forceinline__ float columns_finish(const float (&ab)[16], float eps
     for (int i = 0; i < 16; ++i) s_part += ab[i];
     const float s = add_other_half(s_part);
     const float inv_s = s > 0.f ? __builtin_amdgcn_rcpf(s) : 0.f;
+    // sum_i Ahat_i log2(Ahat_i + eps) with Ahat_i = Abar_i / s: the division of the weights is applied once, to the sum
     float e_part = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const float ah = ab[i] * inv_s;
-        e_part = fmaf(ah, __builtin_amdgcn_logf(ah + eps), e_part);
-    }
-    const float ent = -LN2 * add_other_half(e_part);
+    for (int i = 0; i < 16; ++i) e_part = fmaf(ab[i], __builtin_amdgcn_logf(fmaf(ab[i], inv_s, eps)), e_part);
+    const float ent = -LN2 * inv_s * add_other_half(e_part);
     return hf == 0 ? s : ent;
 }
 
@@ -679,11 +677,8 @@ __device__ __forceinline__ float columns_finish8t(const float (&ab)[NB][16], flo
 #pragma unroll
     for (int v = 0; v < NB; ++v)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float ah = ab[v][i] * inv_s;
-            e_part = fmaf(ah, __builtin_amdgcn_logf(ah + eps), e_part);
-        }
-    const float ent = -LN2 * add_other_half(e_part);
+        for (int i = 0; i < 16; ++i) e_part = fmaf(ab[v][i], __builtin_amdgcn_logf(fmaf(ab[v][i], inv_s, eps)), e_part);
+    const float ent = -LN2 * inv_s * add_other_half(e_part);
     return hf == 0 ? s : ent;
 }
 
@@ -1521,9 +1516,11 @@ namespace {
 // ---- measurement aid: the scoring kernels' key stream without their arithmetic
 // Same chunk plan, same workgroups, same direct-to-LDS ring and waits as score_mfma_columns; per subtile a
 // wavefront either only waits for the subtile and refills its buffer (READ_LDS = false), or also reads the whole
-// subtile from LDS into registers as the scoring kernels do (READ_LDS = true).  What this kernel takes is what the
-// memory system delivers to the scoring kernels' access pattern: the yardstick their times are compared with.
-template <bool READ_LDS>
+// subtile from LDS into registers as the scoring kernels do (READ_LDS = true).  With STORES it also writes what the
+// column pass writes, 4 bytes per key into each of two [P][L] rows, with that kernel's store pattern (lanes 0..31 a
+// row of s_out, lanes 32..63 a row of e_out, once per subtile).  What this kernel takes is what the memory system
+// delivers to the scoring kernels' access pattern: the yardstick their times are compared with.
+template <bool READ_LDS, bool STORES>
 __global__ void __launch_bounds__(WAVES * 64)
 stream_probe_kernel(ScoreArgs a, uint32_t *sink)
 {
@@ -1547,6 +1544,11 @@ stream_probe_kernel(ScoreArgs a, uint32_t *sink)
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             if (u + NBUF < w.n_sub) ks.issue(u + NBUF);
         }
+        if (STORES) {
+            const int t = w.first + u * STRIDE + (lane & 31);
+            float *out = ((lane >> 5) == 0 ? a.s_out : a.e_out) + (int64_t)w.p * a.d.L;
+            if (t < a.d.L) out[t] = __uint_as_float(x & 0x3fffffffu);
+        }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (x == 0x5ab10c4bu) *sink = x;                           // keeps the reads alive; practically never taken
@@ -1556,16 +1558,15 @@ stream_probe_kernel(ScoreArgs a, uint32_t *sink)
 
 bool stream_probe_supported(const Dims &d) { return d.dtype == SABLOCK_BF16 && d.D == 128; }
 
-hipError_t launch_stream_probe(const Dims &d, const void *k, int read_lds, void *sink, hipStream_t st)
+hipError_t launch_stream_probe(const Dims &d, const void *k, int read_lds, float *s_out, float *e_out, void *sink, hipStream_t st)
 {
     static thread_local PerDeviceOnce attr_once;
     if (attr_once.needed()) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_probe_kernel<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, P2_LDS);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_probe_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, P2_LDS);
-        if (e != hipSuccess) return e;
+#define X(R, S) { hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_probe_kernel<R, S>), \
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, P2_LDS); \
+                  if (e != hipSuccess) return e; }
+        X(false, false) X(false, true) X(true, false) X(true, true)
+#undef X
         attr_once.done();
     }
     const Plan pl = make_plan(d);
@@ -1575,9 +1576,14 @@ hipError_t launch_stream_probe(const Dims &d, const void *k, int read_lds, void 
     a.chunk_len = pl.chunk_len;
     a.n_chunks = pl.n_chunks;
     a.p0 = 0;
+    a.s_out = s_out;
+    a.e_out = e_out;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
-    if (read_lds) hipLaunchKernelGGL(stream_probe_kernel<true>, grid, dim3(WAVES * 64), P2_LDS, st, a, static_cast<uint32_t *>(sink));
-    else hipLaunchKernelGGL(stream_probe_kernel<false>, grid, dim3(WAVES * 64), P2_LDS, st, a, static_cast<uint32_t *>(sink));
+    uint32_t *sk = static_cast<uint32_t *>(sink);
+    const bool stores = s_out != nullptr;
+#define X(R, S) if ((read_lds != 0) == R && stores == S) hipLaunchKernelGGL((stream_probe_kernel<R, S>), grid, dim3(WAVES * 64), P2_LDS, st, a, sk);
+    X(false, false) X(false, true) X(true, false) X(true, true)
+#undef X
     return hipGetLastError();
 }
 
