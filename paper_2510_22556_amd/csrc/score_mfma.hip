@@ -97,6 +97,24 @@ __device__ __forceinline__ void issue_subtile_fast(const char *base, int64_t row
     for (int j = 0; j < 8; ++j) dma_1k(lane_off[j & 3], base + (int64_t)(4 * j) * row_bytes, buf_lds + j * 1024);
 }
 
+// The same for dense rows (row_bytes = 256): four rows are then 1 KiB apart in memory as in LDS, and the
+// instruction's immediate offset is added to the global address and to the LDS address alike, so four loads share
+// one scalar base and one M0 value; the subtile takes two of each instead of eight.
+__device__ __forceinline__ void dma_4k(const uint32_t (&lane_off)[4], const char *sbase, uint32_t lds_dst)
+{
+    asm volatile("s_mov_b32 m0, %5\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, %4 nt\n\t"
+                 "global_load_lds_dwordx4 %1, %4 offset:1024 nt\n\t"
+                 "global_load_lds_dwordx4 %2, %4 offset:2048 nt\n\t"
+                 "global_load_lds_dwordx4 %3, %4 offset:3072 nt"
+                 : : "v"(lane_off[0]), "v"(lane_off[1]), "v"(lane_off[2]), "v"(lane_off[3]), "s"(sbase), "s"(lds_dst) : "memory", "m0");
+}
+__device__ __forceinline__ void issue_subtile_dense(const char *base, const uint32_t (&lane_off)[4], uint32_t buf_lds)
+{
+    dma_4k(lane_off, base, buf_lds);
+    dma_4k(lane_off, base + 4096, buf_lds + 4096);
+}
+
 // subtile that crosses L: rows past L-1 read row L-1 instead (their results are masked later); t0 < L
 __device__ __forceinline__ void issue_subtile_clamped(const char *base, int64_t row_bytes, int rows_valid, uint32_t buf_lds, int lane)
 {
@@ -219,8 +237,10 @@ struct KeyStream {
         const int t0 = first + u * STRIDE;                     // wave-uniform, < L
         const char *base = reinterpret_cast<const char *>(kp) + (int64_t)t0 * ks3 * 2;
         const uint32_t buf_lds = ring_lds + (u % NBUF) * BUF_BYTES;
-        if (t0 + SUB <= L) issue_subtile_fast(base, ks3 * 2, lane_off, buf_lds);
-        else issue_subtile_clamped(base, ks3 * 2, L - t0, buf_lds, lane);
+        if (t0 + SUB <= L) {
+            if (ks3 == ROW_BYTES / 2) issue_subtile_dense(base, lane_off, buf_lds);
+            else issue_subtile_fast(base, ks3 * 2, lane_off, buf_lds);
+        } else issue_subtile_clamped(base, ks3 * 2, L - t0, buf_lds, lane);
     }
     __device__ __forceinline__ void prime() const
     {
@@ -859,8 +879,10 @@ struct PairStream {
         const int t0 = first + (e >> 1) * SUB;                 // wave-uniform, < L
         const char *base = reinterpret_cast<const char *>((e & 1) ? kp1 : kp0) + (int64_t)t0 * ks3 * 2;
         const uint32_t buf_lds = ring_lds + (e % NBUF) * BUF_BYTES;
-        if (t0 + SUB <= L) issue_subtile_fast(base, ks3 * 2, lane_off, buf_lds);
-        else issue_subtile_clamped(base, ks3 * 2, L - t0, buf_lds, lane);
+        if (t0 + SUB <= L) {
+            if (ks3 == ROW_BYTES / 2) issue_subtile_dense(base, lane_off, buf_lds);
+            else issue_subtile_fast(base, ks3 * 2, lane_off, buf_lds);
+        } else issue_subtile_clamped(base, ks3 * 2, L - t0, buf_lds, lane);
     }
     __device__ __forceinline__ void prime() const
     {
