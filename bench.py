@@ -38,6 +38,8 @@ FP32_VALU_PEAK_TFLOPS = 157.3   # MI355X fp32 vector peak, published (the generi
 # is named next to the figure.  Workloads without an entry report null.
 MEASURED_TRAFFIC = {
     "llama8b_128k": (17.60e9, "profiles/score_mfma_llama8b_128k_hbm_traffic.md"),
+    "llama8b_4x64k": (35.33e9, "profiles/score_mfma_llama8b_4x64k_hbm_traffic.md"),
+    "llama8b_32k_heavy": (4.506e9, "profiles/score_mfma_llama8b_32k_heavy_hbm_traffic.md"),
 }
 
 
@@ -240,7 +242,9 @@ def config_entries(torch, B, synth, dev, name, steps, warmup):
     w = synth.WORKLOADS[name]
     path = Path(torch, B, synth, w, 0, dev)
     torch.cuda.synchronize()
-    out = {"n_seq": w.n_seq, "n_layers": w.n_layers, "seq_len": w.seq_len, "window": w.window,
+    traffic, traffic_source = MEASURED_TRAFFIC.get(name, (None, None))
+    out = {"score_traffic_standalone": traffic, "traffic_source": traffic_source,
+           "n_seq": w.n_seq, "n_layers": w.n_layers, "seq_len": w.seq_len, "window": w.window,
            "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim, "dtype": w.dtype,
            "cand": list(w.cand), "K_bytes": w.n_seq * w.n_layers * w.n_kv_heads * w.seq_len * w.head_dim
            * (4 if w.dtype == "f32" else 2),
@@ -298,16 +302,27 @@ def yardstick(torch, B, path, reps=10):
             "bytes": k_bytes + (2 * 4 * w.n_seq * w.n_layers * w.n_kv_heads * w.seq_len if stores else 0),
             "ms": ms, "TBps_of_K": k_bytes / (ms * 1e-3) / 1e12}
     G = w.n_q_heads // w.n_kv_heads
-    out["stream_resident_groups"] = {}
+    # launches of n problems each: the same n problems again and again (their keys stay in the memory-side cache
+    # when n * 32 MiB fits it, in the L2s at 32 MiB) against launches that walk through all of K (every launch
+    # reads keys that were last touched 8 GiB ago, i.e. from HBM); same launch size, so the launch overhead cancels
+    out["stream_groups"] = {}
     for n in (1, 2, 4, 8):
-        if n > w.n_kv_heads:
+        if n > w.n_kv_heads or w.n_kv_heads % n:
             continue
-        kg = k[:1, :1, :n]
-        sg = B.make_shape(q[:1, :1, :n * G], kg)
         nbytes = n * w.seq_len * w.head_dim * elt
-        ms = timed(lambda: B.sablock_stream_probe(sg, kg, sink, False), 50)
-        out["stream_resident_groups"][f"{n}_problems_{nbytes >> 20}_MiB"] = {
-            "bytes": nbytes, "ms": ms, "TBps": nbytes / (ms * 1e-3) / 1e12}
+        views = [(B.make_shape(q[b:b + 1, l:l + 1, h0 * G:(h0 + n) * G], k[b:b + 1, l:l + 1, h0:h0 + n]),
+                  k[b:b + 1, l:l + 1, h0:h0 + n])
+                 for b in range(w.n_seq) for l in range(w.n_layers) for h0 in range(0, w.n_kv_heads, n)]
+        sg, kg = views[0]
+        ms_same = timed(lambda: B.sablock_stream_probe(sg, kg, sink, False), 64)
+
+        def walk():
+            for sh_, k_ in views:
+                B.sablock_stream_probe(sh_, k_, sink, False)
+        ms_walk = timed(walk, 2) / len(views)
+        out["stream_groups"][f"{n}_problems_{nbytes >> 20}_MiB"] = {
+            "bytes": nbytes, "same_keys_ms": ms_same, "same_keys_TBps": nbytes / (ms_same * 1e-3) / 1e12,
+            "walking_all_K_ms": ms_walk, "walking_all_K_TBps": nbytes / (ms_walk * 1e-3) / 1e12}
     # the two scoring passes, whole call against groups of n problems (a group's second pass starts right after its
     # first, so its keys are the most recently used bytes of the memory-side cache)
     ms_all = timed(lambda: B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, w.eps), reps)
