@@ -1199,3 +1199,48 @@ def test_window_attention_and_its_row_lse_feed_the_scoring(oracle, torch_cuda, G
     torch.cuda.synchronize()
     np.testing.assert_allclose(H.to_np(buf.s), s0, rtol=1e-4, atol=1e-9)
     np.testing.assert_allclose(H.to_np(buf.ent), e0, rtol=1e-4, atol=1e-6)
+
+
+def test_signed_zero_scores_rank_as_equal(oracle, torch_cuda):
+    # -0.0 and +0.0 compare equal, so among zero scores the index decides: a row of zeros of both signs must give
+    # the same Top-B set, budgets and selection as the same row with every zero positive, and as the oracle
+    torch = torch_cuda
+    rng = np.random.default_rng(99)
+    T, P = 6000, 2
+    st = np.where(rng.random((P, T)) < 0.97, 0.0, rng.random((P, T))).astype(np.float32)
+    neg = st.copy()
+    neg[(st == 0) & (rng.random((P, T)) < 0.5)] = -0.0
+    assert np.signbit(neg).any() and (neg == st).all()
+    off = synth.segment_offsets(5, T, mean=20.0, min_len=1, max_len=120)
+    cand, tau = [1, 2, 4, 8], 0.85
+    for budget in (100, 400):                      # fewer / more than the ~180 positive scores per row
+        ref = _assert_search_select(oracle, torch, st, off, cand, budget, tau)
+        got = _search_select_gpu(torch, neg, off, cand, budget, tau)
+        for a, b in zip(ref, got):
+            np.testing.assert_array_equal(a, b)
+
+
+def test_stream_probe_reads_all_keys_and_writes_every_score_slot_once(torch_cuda):
+    # the measurement aid: with the column pass's stores switched on it must write exactly the [P][L] slots of
+    # both outputs (ragged L, several chunks per problem, strided K), and nothing else
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    L, W, D, G, Hkv, nl = 3 * 2048 + 333, 32, 128, 4, 3, 2
+    q = synth.normal_torch(11, 1, (1, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
+    kbig = synth.normal_torch(11, 2, (1, nl, Hkv, L, 2 * D), "cuda", torch.bfloat16)
+    for k in (kbig[..., :D].contiguous(), kbig[..., :D]):           # dense rows and rows 512 bytes apart
+        shape = B.make_shape(q, k, score_chunk=2048)
+        P = nl * Hkv
+        guard = 64
+        s = torch.full((P * L + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
+        e = torch.full((P * L + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
+        sink = torch.zeros((1,), dtype=torch.int32, device="cuda")
+        k0 = k.clone()
+        B.sablock_stream_probe(shape, k, sink, True, s[guard:guard + P * L], e[guard:guard + P * L])
+        B.sablock_stream_probe(shape, k, sink, False)
+        torch.cuda.synchronize()
+        for out in (s, e):
+            assert bool(torch.isnan(out[:guard]).all()) and bool(torch.isnan(out[-guard:]).all())
+            assert bool(torch.isfinite(out[guard:guard + P * L]).all())
+        assert torch.equal(k, k0) and int(sink[0]) == 0

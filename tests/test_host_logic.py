@@ -136,6 +136,15 @@ def test_calls_reject_bad_host_arguments_before_launch(lib):
     assert lib.sablock_compact(sp, fake, None, fake, fake, 8, 1, fake, fake, None) == 1
     assert lib.sablock_compact(sp, fake, fake, fake, fake, -8, 1, fake, fake, None) == 1
     assert lib.sablock_score(None, fake, fake, None, 1e-6, fake, fake, fake, 0, None) == 1
+    # eps keeps the logarithm of a masked or underflowed entry finite: zero, negative and NaN are refused
+    for bad_eps in (0.0, -1e-6, float("nan")):
+        assert lib.sablock_score(sp, fake, fake, None, bad_eps, fake, fake, fake, 1 << 30, None) == 1
+        assert lib.sablock_score_static(sp, fake, fake, None, bad_eps, fake, fake, None) == 1
+    assert b"eps" in lib.sablock_last_error()
+    # the measurement aid validates like the calls it imitates
+    assert lib.sablock_stream_probe(sp, fake, 0, None, None, fake, None) == 2          # fp32, D 64: unsupported
+    assert lib.sablock_stream_probe(sp, None, 0, None, None, fake, None) == 1
+    assert lib.sablock_stream_probe(sp, fake, 0, fake, None, fake, None) == 1          # only one of the two output rows
     # segmentation
     dl = (ctypes.c_int32 * 2)(11, 13)
     many = (ctypes.c_int32 * 65)(*range(65))
