@@ -80,3 +80,38 @@ def test_static_scratch_scoring_equals_workspace_scoring():
     assert lib.sablock_score_static(ctypes.byref(big), fake, fake, None, 1e-6, fake, fake, None) == 2
     assert b"static array" in lib.sablock_last_error()
     assert lib.sablock_score_static(ctypes.byref(shape), None, fake, None, 1e-6, fake, fake, None) == 1
+
+
+def test_static_scratch_scoring_replays_in_a_hip_graph():
+    # the callers the entry point is for: a captured graph cannot allocate.  After one eager call on the device (which
+    # asks for the array's address) the call only enqueues kernels, so it can be captured; several replays, with eager
+    # work and synchronisations between them and the outputs cleared before each, reproduce the eager run bit for bit
+    import torch
+
+    from paper_2510_22556_amd import binding as B
+
+    B.load()
+    w = synth.WORKLOADS["llama8b_8k"]
+    q, k, v = synth.device_tensors(w, "cuda")
+    shape = B.make_shape(q, k, v)
+    P, L = B.n_problems(shape), shape.seq_len
+    s, e = (torch.empty((P, L), dtype=torch.float32, device="cuda") for _ in range(2))
+    B.sablock_score_static(shape, q, k, s, e, w.eps)
+    torch.cuda.synchronize()
+    eager = [s.clone(), e.clone()]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.sablock_score_static(shape, q, k, s, e, w.eps)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        B.sablock_score_static(shape, q, k, s, e, w.eps)
+    for rep in range(3):
+        s.zero_()
+        e.zero_()
+        (q.float().sum() + k.float().sum()).item()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(s, eager[0]) and torch.equal(e, eager[1]), f"replay {rep} differs from the eager run"
