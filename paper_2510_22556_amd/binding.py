@@ -62,6 +62,10 @@ def load():
             raise FileNotFoundError(
                 f"{LIB_PATH} not found: build it with `python -m paper_2510_22556_amd.build` "
                 "(there is no fallback path)")
+        # torch first: it ships its own copy of the HIP runtime, and a process must hold one runtime only (device
+        # pointers and streams of torch are meaningless to a second copy loaded through this library)
+        import torch  # noqa: F401
+
         lib = ctypes.CDLL(LIB_PATH)
         vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
         sp = ctypes.POINTER(CShape)
