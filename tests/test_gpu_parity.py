@@ -620,6 +620,53 @@ def test_llama8b_32k_full_size_three_budgets_both_routes(oracle, torch_cuda):
         assert mean_g[0] <= mean_g[1] <= mean_g[2]      # larger budgets pick larger blocks (Sec. 3.3 trend)
 
 
+@pytest.mark.parametrize("name", ["tiny", "llama8b_8k"])
+def test_small_configurations_with_row_lse_against_the_oracle(oracle, torch_cuda, name):
+    # configurations 1 and 2 on the row_lse route, every problem against the oracle's chain: the log-sum-exp comes
+    # from sablock_window_attention where that kernel covers the shape (configuration 2) and from a library
+    # routine in fp64 otherwise (configuration 1: fp32, D 64, generic kernels)
+    torch = torch_cuda
+    from scipy.special import logsumexp
+
+    w = synth.WORKLOADS[name]
+    q, k, v, off, ptr = _device_workload(torch, w)
+    if name == "llama8b_8k":
+        lse = _row_lse_from_window_attention(torch, q, k, v)
+    else:
+        lse_h = np.zeros((1, 1, w.n_q_heads, w.window), dtype=np.float32)
+        qn, kn = H.widen(H.to_np(q[0, 0])), H.widen(H.to_np(k[0, 0]))
+        for h in range(w.n_q_heads):
+            x = qn[h] @ kn[h // w.G].T / np.sqrt(w.head_dim)
+            for i in range(w.window):
+                lse_h[0, 0, h, i] = logsumexp(x[i, :w.T + i + 1])
+        lse = torch.as_tensor(lse_h).cuda()
+    run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau, row_lse=lse)
+    assert _check_all(oracle, w, run, q, k, v, off, ptr, range(w.n_kv_heads)) <= 8
+    assert np.allclose(run.s.sum(axis=1), w.window, rtol=1e-4)
+    assert (run.n_sel == w.budget()).all()
+
+
+def test_paper_default_settings_full_size_both_routes(oracle, torch_cuda):
+    # the paper's own settings (window of 8, candidate block sizes {1, 2, 3, 5, 7, 9, 11, 13}) at the size bench.py
+    # times them: 32 layers x 32 768 tokens in one call, cache budgets 96 / 128 / 1 024, standing alone and on the
+    # row_lse route; sampled problems end to end against the oracle's chain
+    torch = torch_cuda
+    w = synth.WORKLOADS["paper_defaults_32k"]
+    q, k, v, off, ptr = _device_workload(torch, w)
+    lse = _row_lse_from_window_attention(torch, q, k, v)
+    cache = {}
+    for route in ("two_pass", "row_lse"):
+        for bi in range(3):
+            run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(bi), w.eps, w.alpha, w.eta, w.tau,
+                           row_lse=lse if route == "row_lse" else None)
+            B_ = w.budget(bi)
+            assert np.allclose(run.s.sum(axis=1), w.window, rtol=1e-4)
+            assert (run.n_sel == B_).all() and (run.b.sum(axis=1) == B_).all()
+            assert np.isin(run.g, (0,) + tuple(w.cand)).all()
+            assert _check_all(oracle, w, run, q, k, v, off, ptr, [7, 8 * 20 + 3], score_cache=cache) <= 6, (route, bi)
+            del run
+
+
 def test_paper_default_settings_three_budgets(oracle, torch_cuda):
     # the paper's own hyperparameters (Sec. 4.1): window of 8, candidate block sizes {1, 2, 3, 5, 7, 9, 11, 13};
     # two of the 32 layers at cache budgets 96 / 128 / 1024
