@@ -130,7 +130,10 @@ SABLOCK_API sablock_status sablock_workspace_bytes(const sablock_shape *shape, i
  *   prefill attention kernel already has); when NULL it is computed here with an
  *   extra pass over K.
  * eps: > 0 (it keeps the logarithm of a masked or underflowed entry finite; INVALID_ARG otherwise).
- * s_out, ent_out: [P][L] float.  Arithmetic: fp32 accumulate and outputs. */
+ * s_out, ent_out: [P][L] float.  Arithmetic: fp32 accumulate and outputs.
+ * Any shape within the limits of sablock_shape is accepted.  bf16 with head_dim 128 and (G, W) in {(4, 32), (4, 64),
+ * (8, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)}, or head_dim 64 and the same pairs up to 128 rows
+ * (G * W <= 128), runs on the matrix pipe; every other shape and fp32 on a plain vector kernel, ~25 x slower per key. */
 SABLOCK_API sablock_status sablock_score(const sablock_shape *shape, const void *q_win, const void *k,
                              const float *row_lse /* nullable */, float eps,
                              float *s_out, float *ent_out,

@@ -203,9 +203,10 @@ __device__ __forceinline__ void read_subtile_vgpr(uint32_t lane_addr, bf16x8 (&k
 }
 
 // k-steps [S0, S1) of one head's 32x32 tile; the first step takes `c` as its C operand
-template <int S0, int S1>
-__device__ __forceinline__ floatx16 chain(const bf16x8 (&qa)[8], const bf16x8 (&kb)[8], floatx16 c)
+template <int S0, int S1, int N>
+__device__ __forceinline__ floatx16 chain(const bf16x8 (&qa)[N], const bf16x8 (&kb)[N], floatx16 c)
 {
+    static_assert(S1 <= N, "k-step outside the operands");
 #pragma unroll
     for (int s = S0; s < S1; ++s) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], kb[s], c, 0, 0, 0);
     return c;
@@ -259,6 +260,45 @@ struct KeyStream {
         if (u + NBUF < n_sub) issue(u + NBUF);
     }
 };
+
+// Keys of 64 elements (128-byte rows) for the kernels that take any row shape: no LDS staging.  A lane loads its
+// own B operand (key lane % 32, elements (2s + lane / 32) * 8 .. +8 of k-step s: the two lane halves of a key read
+// adjacent 16-byte pieces) straight into registers with ordinary loads, whose counter the compiler keeps; subtile
+// u + 1 is requested before subtile u is worked on.  Keys past the end of the sequence read key L - 1 (their results
+// are masked later, as in the staged stream).  Same interface as KeyStream.
+template <int KS>
+struct KeyStreamDirect {
+    const uint16_t *kp;
+    int64_t ks3;
+    int first, n_sub, L, lane;
+    bf16x8 nxt[KS];
+
+    __device__ __forceinline__ void init(const uint16_t *kp_, int64_t ks3_, char *, int first_, int n_sub_, int L_, int lane_)
+    {
+        kp = kp_; ks3 = ks3_; first = first_; n_sub = n_sub_; L = L_; lane = lane_;
+    }
+    __device__ __forceinline__ void load(int u)
+    {
+        const int t = min(first + u * STRIDE + (lane & 31), L - 1);
+        const uint16_t *row = kp + (int64_t)t * ks3 + (lane >> 5) * 8;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) nxt[s] = *reinterpret_cast<const bf16x8 *>(row + 16 * s);
+    }
+    __device__ __forceinline__ void prime()
+    {
+        if (n_sub > 0) load(0);
+    }
+    __device__ __forceinline__ void fetch(int u, bf16x8 (&kb)[KS])
+    {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kb[s] = nxt[s];
+        if (u + 1 < n_sub) load(u + 1);
+    }
+};
+
+// the key stream of the any-row-shape kernels by k-steps per key: 8 (D = 128) staged through LDS, 4 (D = 64) direct
+template <int KS> struct StreamFor { using type = KeyStream<4>; };
+template <> struct StreamFor<4> { using type = KeyStreamDirect<4>; };
 
 // A operands: the window queries of the four heads, query row `n`, k-slices (2s + hf) * 8 .. +8, into
 // accumulation registers.  All 32 loads are issued before the first is consumed.
@@ -1096,7 +1136,7 @@ template <int G, int W> struct Rows {
     __device__ static int slot_query(int s, int hf) { return W >= 32 ? 32 * (s / 16) + tile_row(s % 16, hf) : tile_row(s, hf) % W; }
 };
 
-template <int G, int W>
+template <int G, int W, int KS>
 __global__ void __launch_bounds__(WAVES * 64)
 score_mfma_stats_g(ScoreArgs a)
 {
@@ -1112,22 +1152,22 @@ score_mfma_stats_g(ScoreArgs a)
     float *cref = wg_red + WAVES * M * 2 + wave_u * M;                         // [NT tiles][2 halves][16], this wave's
     const WaveWork w = wave_work(a, wave);
 
-    KeyStream<NBUF> ks;
+    typename StreamFor<KS>::type ks;
     ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
     ks.prime();
 
-    bf16x8 qa[NT][8];
+    bf16x8 qa[NT][KS];
 #pragma unroll
     for (int J = 0; J < NT; ++J) {
         const int r = 32 * J + n;                                              // row of the window-query matrix
         const uint16_t *row = a.q + q_row_offset(d, w.p, r / W, r % W);
 #pragma unroll
-        for (int s = 0; s < 8; ++s) qa[J][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+        for (int s = 0; s < KS; ++s) qa[J][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
     }
 #pragma unroll
     for (int J = 0; J < NT; ++J)
 #pragma unroll
-        for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qa[J][s]));
+        for (int s = 0; s < KS; ++s) asm volatile("" : "+a"(qa[J][s]));
     for (int i = lane; i < M; i += 64) cref[i] = 0.f;
 
     float z[NT][16];
@@ -1137,13 +1177,13 @@ score_mfma_stats_g(ScoreArgs a)
         for (int i = 0; i < 16; ++i) z[J][i] = 0.f;
     const float lim = RESCALE_AT / a.c1;
     for (int u = 0; u < w.n_sub; ++u) {
-        bf16x8 kb[8];
+        bf16x8 kb[KS];
         ks.fetch(u, kb);
         const int t0 = w.first + u * STRIDE;
         const bool plain = u > 0 && t0 + SUB <= d.T;
 #pragma unroll
         for (int J = 0; J < NT; ++J) {
-            const floatx16 acc = chain<0, 8>(qa[J], kb, load_cref(cref, J, hf));
+            const floatx16 acc = chain<0, KS>(qa[J], kb, load_cref(cref, J, hf));
             if (plain && !stats_guard(acc, lim)) stats_add(acc, z[J], a.c1);
             else stats_tile_careful(acc, z[J], cref + 32 * J, a.c1, u == 0, t0 + n, hf, n,
                                     [J, hf](int i) { return R::query(J, i, hf); }, d.T, d.L);
@@ -1186,7 +1226,7 @@ score_mfma_stats_g(ScoreArgs a)
 // STORE: instead of the column sum and entropy of the KV head, write the head-group mean Abar[query][key] itself
 // (for the mean over ALL heads of a layer, which is formed across KV heads afterwards), four consecutive window
 // queries of a key per 16-byte store, layout [problem][W / 4][L][4].
-template <int G, int W, bool STORE>
+template <int G, int W, bool STORE, int KS>
 __global__ void __launch_bounds__(WAVES * 64)
 score_mfma_columns_g(ScoreArgs a)
 {
@@ -1200,7 +1240,7 @@ score_mfma_columns_g(ScoreArgs a)
     float *lse2 = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [M] log2-domain lse + log2 G, row head * W + query
     const WaveWork w = wave_work(a, wave);
 
-    KeyStream<NBUF> ks;
+    typename StreamFor<KS>::type ks;
     ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
     ks.prime();
 
@@ -1225,7 +1265,7 @@ score_mfma_columns_g(ScoreArgs a)
     }
     __syncthreads();
 
-    bf16x8 qa[NT][8];
+    bf16x8 qa[NT][KS];
     floatx16 cinit[NT];
     const float inv_c1 = 1.0f / a.c1;
 #pragma unroll
@@ -1233,18 +1273,18 @@ score_mfma_columns_g(ScoreArgs a)
         const int r = 32 * J + n;
         const uint16_t *row = a.q + q_row_offset(d, w.p, r / W, r % W);
 #pragma unroll
-        for (int s = 0; s < 8; ++s) qa[J][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+        for (int s = 0; s < KS; ++s) qa[J][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
 #pragma unroll
         for (int i = 0; i < 16; ++i) cinit[J][i] = -lse2[32 * J + R::tile_row(i, hf)] * inv_c1;
     }
 #pragma unroll
     for (int J = 0; J < NT; ++J)
 #pragma unroll
-        for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qa[J][s]));
+        for (int s = 0; s < KS; ++s) asm volatile("" : "+a"(qa[J][s]));
     float *out = (hf == 0 ? a.s_out : a.e_out) + (int64_t)w.p * d.L;
 
     for (int u = 0; u < w.n_sub; ++u) {
-        bf16x8 kb[8];
+        bf16x8 kb[KS];
         ks.fetch(u, kb);
         const int t0 = w.first + u * STRIDE, t = t0 + n;
         const bool edge = t0 + SUB > d.T;
@@ -1253,7 +1293,7 @@ score_mfma_columns_g(ScoreArgs a)
         for (int i = 0; i < NS; ++i) ab[i] = 0.f;
 #pragma unroll
         for (int J = 0; J < NT; ++J) {
-            const floatx16 acc = chain<0, 8>(qa[J], kb, cinit[J]);
+            const floatx16 acc = chain<0, KS>(qa[J], kb, cinit[J]);
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 float v = __builtin_amdgcn_exp2f(acc[i] * a.c1);                        // A / G
@@ -1332,25 +1372,25 @@ void launch_merge(const ScoreArgs &a, int blocks, int M, hipStream_t st)
                        a.partial, const_cast<float *>(a.merged), a.n_chunks, M, n_rows);
 }
 
-template <int G, int W, bool STORE>
+template <int G, int W, bool STORE, int KS = 8>
 hipError_t launch_score_g(const ScoreArgs &a, dim3 grid, bool with_stats, hipStream_t st)
 {
     static thread_local PerDeviceOnce attr_once;
     if (attr_once.needed()) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats_g<G, W>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats_g<G, W, KS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, stats_g_lds<G, W>());
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_g<G, W, STORE>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_g<G, W, STORE, KS>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, columns_g_lds<G, W>());
         if (e != hipSuccess) return e;
         attr_once.done();
     }
     constexpr int lds1 = stats_g_lds<G, W>(), lds2 = columns_g_lds<G, W>();
     if (with_stats) {
-        hipLaunchKernelGGL((score_mfma_stats_g<G, W>), grid, dim3(WAVES * 64), lds1, st, a);
+        hipLaunchKernelGGL((score_mfma_stats_g<G, W, KS>), grid, dim3(WAVES * 64), lds1, st, a);
         launch_merge(a, a.d.P, G * W, st);
     }
-    hipLaunchKernelGGL((score_mfma_columns_g<G, W, STORE>), grid, dim3(WAVES * 64), lds2, st, a);
+    hipLaunchKernelGGL((score_mfma_columns_g<G, W, STORE, KS>), grid, dim3(WAVES * 64), lds2, st, a);
     return hipGetLastError();
 }
 
@@ -1453,8 +1493,9 @@ void plan_partials(ScoreArgs &a, const Dims &d, const Plan &pl, void *ws)
 
 bool score_mfma_supported(const Dims &d)
 {
-    return d.dtype == SABLOCK_BF16 && d.D == 128 &&
-           ((d.G == 4 && (d.W == 32 || d.W == 64)) || (d.G == 8 && d.W == 32) || small_shape(d));
+    if (d.dtype != SABLOCK_BF16) return false;
+    if (d.D == 64) return (d.G == 4 && d.W == 32) || small_shape(d);        // up to 128 rows, kernels for any row shape
+    return d.D == 128 && ((d.G == 4 && (d.W == 32 || d.W == 64)) || (d.G == 8 && d.W == 32) || small_shape(d));
 }
 
 // pass 1 for 256 rows by the transposed-score kernel (csrc/window_attn.hip): K is read once instead of once per
@@ -1504,6 +1545,12 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.p0 = 0;
     a.nv = d.G * d.W > M_ROWS ? d.G * d.W / M_ROWS : 1;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
+    if (d.D == 64) {
+#define X(GV, WV) if (d.G == GV && d.W == WV) return launch_score_g<GV, WV, false, 4>(a, grid, !row_lse, st);
+        SABLOCK_SMALL_SHAPES(X)
+        X(4, 32)
+#undef X
+    }
 #define X(GV, WV) if (d.G == GV && d.W == WV) return launch_score_g<GV, WV, false>(a, grid, !row_lse, st);
     SABLOCK_SMALL_SHAPES(X)
 #undef X

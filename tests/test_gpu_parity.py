@@ -445,6 +445,42 @@ def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, G, W):
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
 
+@pytest.mark.parametrize("G,W", [(4, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)])
+@pytest.mark.parametrize("chunk", [0, 1024])
+def test_mfma_score_head_dim_64(oracle, torch_cuda, G, W, chunk):
+    # bf16 heads of 64 elements on the matrix pipe (four k-steps per key, keys loaded straight into registers): ragged
+    # length, one and several chunks per problem, planted keys that move row references, strided K, all five steps;
+    # then the row_lse route from a library log-sum-exp
+    torch = torch_cuda
+    from scipy.special import logsumexp
+
+    L, D, Hkv, nl = 2 * 2048 + 411 + W, 64, 2, 2
+    T = L - W
+    q = synth.normal_torch(6400 + G * W, 1, (1, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
+    kbig = synth.normal_torch(6400 + G * W, 2, (1, nl, Hkv, L, 2 * D), "cuda", torch.bfloat16)
+    k = kbig[..., :D] if chunk else kbig[..., :D].contiguous()          # rows 256 bytes apart / dense
+    v = synth.normal_torch(6400 + G * W, 3, (1, nl, Hkv, L, D), "cuda", torch.bfloat16)
+    for l, g, h, i, t in [(0, 0, 0, 0, 700), (0, 0, G - 1, W - 1, 1900), (1, 1, G // 2, W // 2, 3000), (1, 1, G - 1, 1, T + 1)]:
+        k[0, l, g, t, :] = (q[0, l, g * G + h, i, :].float() * 7.0).to(torch.bfloat16)
+    off = synth.segment_offsets(64, T, mean=28.0, min_len=1, max_len=200)
+    cand = [1, 2, 3, 5, 7, 9, 11, 13]
+    w = synth.Workload("d64", 0, 1, nl, G * Hkv, Hkv, D, L, W, "bf16", tuple(cand), (512 + W,), (28.0,))
+    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget(), tuning=dict(score_chunk=chunk))
+    assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
+    assert run.s[0, 700] > 0.99 / G and run.s[nl * Hkv - 1, 3000] > 0.99 / G       # planted keys take their rows
+    _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(nl * Hkv))
+    lse = np.zeros((1, nl, G * Hkv, W), dtype=np.float32)
+    for l in range(nl):
+        qn, kn = H.widen(H.to_np(q[0, l])), H.widen(H.to_np(k[0, l].contiguous()))
+        for h in range(G * Hkv):
+            x = qn[h] @ kn[h // G].T / np.sqrt(D)
+            for i in range(W):
+                lse[0, l, h, i] = logsumexp(x[i, :T + i + 1])
+    run2 = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget(), row_lse=torch.as_tensor(lse).cuda(),
+                    tuning=dict(score_chunk=chunk))
+    _check_all(oracle, w, run2, q, k, v, off, [0, len(off)], range(nl * Hkv))
+
+
 @pytest.mark.parametrize("seed", range(18))
 def test_mfma_score_random_sweep(oracle, torch_cuda, seed):
     # every (G, W) the MFMA kernels cover, with random lengths (ragged, from W + 1 on), KV heads, layers, chunk
