@@ -131,9 +131,10 @@ SABLOCK_API sablock_status sablock_workspace_bytes(const sablock_shape *shape, i
  *   extra pass over K.
  * eps: > 0 (it keeps the logarithm of a masked or underflowed entry finite; INVALID_ARG otherwise).
  * s_out, ent_out: [P][L] float.  Arithmetic: fp32 accumulate and outputs.
- * Any shape within the limits of sablock_shape is accepted.  bf16 with head_dim 128 and (G, W) in {(4, 32), (4, 64),
- * (8, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)}, or head_dim 64 and the same pairs up to 128 rows
- * (G * W <= 128), runs on the matrix pipe; every other shape and fp32 on a plain vector kernel, ~25 x slower per key. */
+ * Any shape within the limits of sablock_shape is accepted.  bf16 with head_dim 64 or 128, W in {8, 16, 32, 64} and
+ * any G with G * W <= 128 (e.g. G = 7 with W = 16, G = 3 with W = 32, G = 16 with W = 8), and head_dim 128 with
+ * (G, W) = (4, 64) or (8, 32) (256 rows), runs on the matrix pipe; every other shape and fp32 on a plain vector
+ * kernel, ~25 x slower per key. */
 SABLOCK_API sablock_status sablock_score(const sablock_shape *shape, const void *q_win, const void *k,
                              const float *row_lse /* nullable */, float eps,
                              float *s_out, float *ent_out,
@@ -248,7 +249,7 @@ SABLOCK_API sablock_status sablock_compact(const sablock_shape *shape, const voi
  * retained set, per (sequence, layer) instead of one per KV head.
  *   sablock_score_all_heads   as sablock_score, but Abar[i, t] is the mean over all n_q_heads heads of the layer;
  *       s_out / ent_out are [n_seq * n_layers][L].  row_lse as in sablock_score.  Supported: bf16, head_dim 128,
- *       (G, W) in {(4, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)}; otherwise UNSUPPORTED.  With 8 KV
+ *       W in {8, 16, 32} and any G with G * W <= 128; otherwise UNSUPPORTED.  With 8 KV
  *       heads, G = 4 and W = 32 the heads of a layer are summed on chip and the workspace
  *       (sablock_score_all_heads_workspace_bytes) holds row statistics only; for the other shapes it also holds
  *       the head-group means of every KV head, 4 * W bytes per key and KV head, before they are averaged.

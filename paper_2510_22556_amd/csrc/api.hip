@@ -410,7 +410,7 @@ sablock_status sablock_score_all_heads_workspace_bytes(const sablock_shape *shap
     sablock_status st = make_dims(shape, &d);
     if (st != SABLOCK_OK) return st;
     if (!score_all_heads_supported(d))
-        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_score_all_heads: needs bf16, head_dim 128 and at most 128 window-query rows per KV head in a shape the MFMA kernels cover");
+        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_score_all_heads: needs bf16, head_dim 128, a window of 8, 16 or 32 and at most 128 window-query rows per KV head");
     *bytes_out = score_all_heads_ws_bytes(d);
     return SABLOCK_OK;
 }
@@ -426,7 +426,7 @@ sablock_status sablock_score_all_heads(const sablock_shape *shape, const void *q
     if (!aligned16(q_win) || !aligned16(k)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score_all_heads: Q/K must be 16-byte aligned");
     if (!(eps > 0.f)) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_score_all_heads: eps must be > 0");
     if (!score_all_heads_supported(d))
-        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_score_all_heads: needs bf16, head_dim 128 and at most 128 window-query rows per KV head in a shape the MFMA kernels cover");
+        return fail(SABLOCK_ERR_UNSUPPORTED, "sablock_score_all_heads: needs bf16, head_dim 128, a window of 8, 16 or 32 and at most 128 window-query rows per KV head");
     const size_t need = score_all_heads_ws_bytes(d);
     if (!ws || ws_bytes < need)
         return fail(SABLOCK_ERR_WORKSPACE_TOO_SMALL, "sablock_score_all_heads: workspace %zu < %zu bytes", ws_bytes, need);

@@ -67,6 +67,7 @@ struct ScoreArgs {
     int nv;                // 128-row blocks per problem in pass 1 (G * W / 128)
     int pc;                // (reference, sum) pairs per row that pass 2 reads: n_chunks, or 1 once they are merged
     float c1;              // log2(e) / sqrt(D)
+    float log2_G;          // log2 of the heads per KV head (the head mean is folded into the rows' log-sum-exp)
     float eps;
     float *partial;        // pass 1 out: [problem][query block][chunk][128][2] (reference, sum), log2 domain
     const float *merged;   // pass 2 in: the same layout with pc chunks
@@ -1117,40 +1118,56 @@ score_mfma_columns_layer(ScoreArgs a)
 }
 
 // ------------------------------------------------------------------ other head / window shapes
-// G * W = 32, 64 or 128 rows in one to four 32-row tiles, row = head * W + window query.  For W < 32 a tile holds
-// several heads, so the head mean adds REGISTERS of one accumulator (register i of lane half hf is row
-// 8 (i / 4) + 4 hf + i % 4 of the tile); for W >= 32 it adds accumulators, as in the kernels above.  These
-// kernels run the tiles of a subtile one after the other (no rotation of accumulators): with at most a quarter
-// of the arithmetic of the 128-row case per key they wait for memory anyway.
-template <int G, int W> struct Rows {
-    static constexpr int M = G * W;
-    static constexpr int NT = M / 32;                       // tiles
+// Any G with G * W <= 128 rows, W = 8, 16, 32 or 64: NT = ceil(G * W / 32) tiles of 32 rows, row = head * W +
+// window query; the rows behind the problem's G * W are padding (W < 32 and G not a multiple of 32 / W): zero
+// queries, never written by pass 1 and given an infinite log-sum-exp in pass 2, so they add exact zeros.  For
+// W < 32 a tile holds several heads, so the head mean adds REGISTERS of one accumulator (register i of lane half
+// hf is row 8 (i / 4) + 4 hf + i % 4 of the tile); for W >= 32 it adds accumulators, as in the kernels above.
+// These kernels run the tiles of a subtile one after the other (no rotation of accumulators): with at most the
+// arithmetic of the 128-row case per key and usually far less they wait for memory anyway.
+template <int NT_, int W> struct Rows {
+    static constexpr int NT = NT_;                          // tiles
+    static constexpr int MP = 32 * NT;                      // rows of the tiles (padding included)
     static constexpr int QB = W >= 32 ? W / 32 : 1;         // 32-query blocks of the window
     static constexpr int NS = W >= 32 ? 16 * QB : W / 2;    // head-mean values per lane
-    static_assert(M == 32 || M == 64 || M == 128, "unsupported shape");
+    static_assert(NT >= 1 && NT <= 4 && (W == 8 || W == 16 || W == 32 || W == 64) && NT % QB == 0, "unsupported shape");
     __device__ static int tile_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
     __device__ static int query(int J, int i, int hf) { return W >= 32 ? 32 * (J % QB) + tile_row(i, hf) : tile_row(i, hf) % W; }
-    __device__ static int head(int J, int i, int hf) { return W >= 32 ? J / QB : J * (32 / W) + tile_row(i, hf) / W; }
     __host__ __device__ static constexpr int slot(int J, int i) { return W >= 32 ? 16 * (J % QB) + i : i % (W / 2); }
     // window query that head-mean value `s` of lane half hf belongs to
     __device__ static int slot_query(int s, int hf) { return W >= 32 ? 32 * (s / 16) + tile_row(s % 16, hf) : tile_row(s, hf) % W; }
 };
 
-template <int G, int W, int KS>
+// a lane's A operands: row `r` of the problem's window-query matrix, zeros for a padding row
+template <int KS>
+__device__ __forceinline__ void load_query_row(bf16x8 (&qa)[KS], const ScoreArgs &a, int p, int r, int W, int hf)
+{
+    if (r < a.d.G * W) {
+        const uint16_t *row = a.q + q_row_offset(a.d, p, r / W, r % W);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qa[s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+    } else {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qa[s] = bf16x8{};
+    }
+}
+
+template <int NT, int W, int KS>
 __global__ void __launch_bounds__(WAVES * 64)
 score_mfma_stats_g(ScoreArgs a)
 {
-    using R = Rows<G, W>;
-    constexpr int M = R::M, NT = R::NT;
+    using R = Rows<NT, W>;
+    constexpr int MP = R::MP;
     extern __shared__ __attribute__((aligned(8192))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hf = lane >> 5;
     const Dims &d = a.d;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     char *ring = lds + wave_u * RING_BYTES;
-    float *wg_red = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [WAVES][M][2]
-    float *cref = wg_red + WAVES * M * 2 + wave_u * M;                         // [NT tiles][2 halves][16], this wave's
+    float *wg_red = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [WAVES][MP][2]
+    float *cref = wg_red + WAVES * MP * 2 + wave_u * MP;                         // [NT tiles][2 halves][16], this wave's
     const WaveWork w = wave_work(a, wave);
+    const int M = d.G * W;                                                     // rows of the problem; [M, MP) is padding
 
     typename StreamFor<KS>::type ks;
     ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
@@ -1158,17 +1175,12 @@ score_mfma_stats_g(ScoreArgs a)
 
     bf16x8 qa[NT][KS];
 #pragma unroll
-    for (int J = 0; J < NT; ++J) {
-        const int r = 32 * J + n;                                              // row of the window-query matrix
-        const uint16_t *row = a.q + q_row_offset(d, w.p, r / W, r % W);
-#pragma unroll
-        for (int s = 0; s < KS; ++s) qa[J][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
-    }
+    for (int J = 0; J < NT; ++J) load_query_row(qa[J], a, w.p, 32 * J + n, W, hf);   // row of the window-query matrix
 #pragma unroll
     for (int J = 0; J < NT; ++J)
 #pragma unroll
         for (int s = 0; s < KS; ++s) asm volatile("" : "+a"(qa[J][s]));
-    for (int i = lane; i < M; i += 64) cref[i] = 0.f;
+    for (int i = lane; i < MP; i += 64) cref[i] = 0.f;
 
     float z[NT][16];
 #pragma unroll
@@ -1191,30 +1203,30 @@ score_mfma_stats_g(ScoreArgs a)
     }
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    float *scr_z = reinterpret_cast<float *>(ring);            // [M rows][32 lanes]
+    float *scr_z = reinterpret_cast<float *>(ring);            // [MP rows][32 lanes]
 #pragma unroll
     for (int J = 0; J < NT; ++J)
 #pragma unroll
         for (int i = 0; i < 16; ++i) scr_z[(J * 32 + R::tile_row(i, hf)) * 32 + n] = z[J][i];
     __builtin_amdgcn_wave_barrier();
-    for (int row = lane; row < M; row += 64) {                  // row = 32 * tile + row in tile
+    for (int row = lane; row < MP; row += 64) {                 // row = 32 * tile + row in tile
         float zz = 0.f;
         for (int j = 0; j < 32; ++j) zz += scr_z[row * 32 + ((j + lane) & 31)];
         const int q = row & 31, hfq = (q >> 2) & 1, iq = ((q >> 3) << 2) | (q & 3);
-        wg_red[(wave * M + row) * 2] = -cref[(row >> 5) * 32 + hfq * 16 + iq] * a.c1;   // reference, log2 domain
-        wg_red[(wave * M + row) * 2 + 1] = zz;
+        wg_red[(wave * MP + row) * 2] = -cref[(row >> 5) * 32 + hfq * 16 + iq] * a.c1;   // reference, log2 domain
+        wg_red[(wave * MP + row) * 2 + 1] = zz;
     }
     __syncthreads();
     if (threadIdx.x < M) {
         const int row = threadIdx.x;
         float m = -INFINITY;
         for (int wv = 0; wv < WAVES; ++wv) {
-            const float *e = wg_red + (wv * M + row) * 2;
+            const float *e = wg_red + (wv * MP + row) * 2;
             if (e[1] > 0.f) m = fmaxf(m, e[0]);
         }
         float zz = 0.f;
         for (int wv = 0; wv < WAVES; ++wv) {
-            const float *e = wg_red + (wv * M + row) * 2;
+            const float *e = wg_red + (wv * MP + row) * 2;
             if (e[1] > 0.f) zz += e[1] * __builtin_amdgcn_exp2f(e[0] - m);
         }
         float *o = a.partial + (((int64_t)w.p * a.n_chunks + w.chunk) * M + row) * 2;
@@ -1226,24 +1238,26 @@ score_mfma_stats_g(ScoreArgs a)
 // STORE: instead of the column sum and entropy of the KV head, write the head-group mean Abar[query][key] itself
 // (for the mean over ALL heads of a layer, which is formed across KV heads afterwards), four consecutive window
 // queries of a key per 16-byte store, layout [problem][W / 4][L][4].
-template <int G, int W, bool STORE, int KS>
+template <int NT, int W, bool STORE, int KS>
 __global__ void __launch_bounds__(WAVES * 64)
 score_mfma_columns_g(ScoreArgs a)
 {
-    using R = Rows<G, W>;
-    constexpr int M = R::M, NT = R::NT, NS = R::NS;
+    using R = Rows<NT, W>;
+    constexpr int MP = R::MP, NS = R::NS;
     extern __shared__ __attribute__((aligned(8192))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hf = lane >> 5;
     const Dims &d = a.d;
     char *ring = lds + __builtin_amdgcn_readfirstlane(wave) * RING_BYTES;
-    float *lse2 = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [M] log2-domain lse + log2 G, row head * W + query
+    float *lse2 = reinterpret_cast<float *>(lds + WAVES * RING_BYTES);       // [MP] log2-domain lse + log2 G, row head * W + query; +inf for padding rows
     const WaveWork w = wave_work(a, wave);
+    const int M = d.G * W;                                                   // rows of the problem; [M, MP) is padding
 
     typename StreamFor<KS>::type ks;
     ks.init(w.kp, d.ks[3], ring, w.first, w.n_sub, d.L, lane);
     ks.prime();
 
+    if (threadIdx.x >= M && threadIdx.x < MP) lse2[threadIdx.x] = INFINITY;
     if (threadIdx.x < M) {
         const int r = threadIdx.x;
         float m = -INFINITY, zz = 0.f;
@@ -1261,7 +1275,7 @@ score_mfma_columns_g(ScoreArgs a)
                 }
             }
         }
-        lse2[r] = m + __builtin_amdgcn_logf(zz) + (G == 1 ? 0.f : G == 2 ? 1.f : G == 4 ? 2.f : 3.f);   // + log2(G)
+        lse2[r] = m + __builtin_amdgcn_logf(zz) + a.log2_G;
     }
     __syncthreads();
 
@@ -1270,10 +1284,7 @@ score_mfma_columns_g(ScoreArgs a)
     const float inv_c1 = 1.0f / a.c1;
 #pragma unroll
     for (int J = 0; J < NT; ++J) {
-        const int r = 32 * J + n;
-        const uint16_t *row = a.q + q_row_offset(d, w.p, r / W, r % W);
-#pragma unroll
-        for (int s = 0; s < KS; ++s) qa[J][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+        load_query_row(qa[J], a, w.p, 32 * J + n, W, hf);
 #pragma unroll
         for (int i = 0; i < 16; ++i) cinit[J][i] = -lse2[32 * J + R::tile_row(i, hf)] * inv_c1;
     }
@@ -1328,8 +1339,8 @@ score_mfma_columns_g(ScoreArgs a)
     }
 }
 
-template <int G, int W> constexpr int stats_g_lds() { return 4 * 4 * BUF_BYTES + 4 * G * W * 2 * 4 + 4 * G * W * 4; }
-template <int G, int W> constexpr int columns_g_lds() { return 4 * 4 * BUF_BYTES + G * W * 4; }
+template <int NT> constexpr int stats_g_lds() { return 4 * 4 * BUF_BYTES + 4 * 32 * NT * 2 * 4 + 4 * 32 * NT * 4; }
+template <int NT> constexpr int columns_g_lds() { return 4 * 4 * BUF_BYTES + 32 * NT * 4; }
 
 // Folds the chunk partials of pass 1 into one (reference, sum) pair per row, one wavefront per row, so that
 // with many chunks per problem the workgroups of pass 2 do not each repeat the fold.
@@ -1372,25 +1383,25 @@ void launch_merge(const ScoreArgs &a, int blocks, int M, hipStream_t st)
                        a.partial, const_cast<float *>(a.merged), a.n_chunks, M, n_rows);
 }
 
-template <int G, int W, bool STORE, int KS = 8>
+template <int NT, int W, bool STORE, int KS = 8>
 hipError_t launch_score_g(const ScoreArgs &a, dim3 grid, bool with_stats, hipStream_t st)
 {
     static thread_local PerDeviceOnce attr_once;
     if (attr_once.needed()) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats_g<G, W, KS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, stats_g_lds<G, W>());
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_stats_g<NT, W, KS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, stats_g_lds<NT>());
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_g<G, W, STORE, KS>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, columns_g_lds<G, W>());
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(score_mfma_columns_g<NT, W, STORE, KS>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, columns_g_lds<NT>());
         if (e != hipSuccess) return e;
         attr_once.done();
     }
-    constexpr int lds1 = stats_g_lds<G, W>(), lds2 = columns_g_lds<G, W>();
+    constexpr int lds1 = stats_g_lds<NT>(), lds2 = columns_g_lds<NT>();
     if (with_stats) {
-        hipLaunchKernelGGL((score_mfma_stats_g<G, W, KS>), grid, dim3(WAVES * 64), lds1, st, a);
-        launch_merge(a, a.d.P, G * W, st);
+        hipLaunchKernelGGL((score_mfma_stats_g<NT, W, KS>), grid, dim3(WAVES * 64), lds1, st, a);
+        launch_merge(a, a.d.P, a.d.G * W, st);
     }
-    hipLaunchKernelGGL((score_mfma_columns_g<G, W, STORE, KS>), grid, dim3(WAVES * 64), lds2, st, a);
+    hipLaunchKernelGGL((score_mfma_columns_g<NT, W, STORE, KS>), grid, dim3(WAVES * 64), lds2, st, a);
     return hipGetLastError();
 }
 
@@ -1430,15 +1441,16 @@ abar_reduce_kernel(const float *abar, int Hkv, int L, float eps, float *s_out, f
 }
 
 // the (G, W) pairs served by the generic-row kernels
-#define SABLOCK_SMALL_SHAPES(X) X(4, 8) X(4, 16) X(8, 8) X(8, 16) X(2, 32) X(1, 32)
+// (tiles, window) pairs of the any-row-shape kernels: tiles = ceil(G * W / 32) <= 4.  Four tiles of a 32-query
+// window are G = 4, which has kernels of its own at D = 128, so that pair is listed apart.
+#define SABLOCK_TILE_SHAPES(X) X(1, 8) X(2, 8) X(3, 8) X(4, 8) X(1, 16) X(2, 16) X(3, 16) X(4, 16) X(1, 32) X(2, 32) X(3, 32)
+#define SABLOCK_TILE_SHAPES_W64(X) X(2, 64) X(4, 64)
 
-bool small_shape(const Dims &d)
+bool tile_shape(const Dims &d)
 {
-#define X(GV, WV) if (d.G == GV && d.W == WV) return true;
-    SABLOCK_SMALL_SHAPES(X)
-#undef X
-    return false;
+    return (d.W == 8 || d.W == 16 || d.W == 32 || d.W == 64) && d.G >= 1 && d.G * d.W <= M_ROWS;
 }
+int tiles_of(const Dims &d) { return (d.G * d.W + 31) / 32; }
 
 struct Plan {
     int chunk_len;    // keys per workgroup
@@ -1494,8 +1506,8 @@ void plan_partials(ScoreArgs &a, const Dims &d, const Plan &pl, void *ws)
 bool score_mfma_supported(const Dims &d)
 {
     if (d.dtype != SABLOCK_BF16) return false;
-    if (d.D == 64) return (d.G == 4 && d.W == 32) || small_shape(d);        // up to 128 rows, kernels for any row shape
-    return d.D == 128 && ((d.G == 4 && (d.W == 32 || d.W == 64)) || (d.G == 8 && d.W == 32) || small_shape(d));
+    if (d.D == 64) return tile_shape(d);                                    // up to 128 rows, kernels for any row shape
+    return d.D == 128 && (tile_shape(d) || (d.G == 4 && d.W == 64) || (d.G == 8 && d.W == 32));
 }
 
 // pass 1 for 256 rows by the transposed-score kernel (csrc/window_attn.hip): K is read once instead of once per
@@ -1537,6 +1549,7 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.k = static_cast<const uint16_t *>(k);
     plan_partials(a, d, pl, ws);
     a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
+    a.log2_G = (float)log2((double)d.G);
     a.eps = eps;
     a.s_out = s_out;
     a.e_out = ent_out;
@@ -1545,15 +1558,20 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.p0 = 0;
     a.nv = d.G * d.W > M_ROWS ? d.G * d.W / M_ROWS : 1;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
-    if (d.D == 64) {
-#define X(GV, WV) if (d.G == GV && d.W == WV) return launch_score_g<GV, WV, false, 4>(a, grid, !row_lse, st);
-        SABLOCK_SMALL_SHAPES(X)
-        X(4, 32)
+    if (tile_shape(d)) {
+        const int nt = tiles_of(d);
+        if (d.D == 64) {
+#define X(NTV, WV) if (nt == NTV && d.W == WV) return launch_score_g<NTV, WV, false, 4>(a, grid, !row_lse, st);
+            SABLOCK_TILE_SHAPES(X)
+            X(4, 32)
+            SABLOCK_TILE_SHAPES_W64(X)
+#undef X
+        }
+#define X(NTV, WV) if (nt == NTV && d.W == WV) return launch_score_g<NTV, WV, false>(a, grid, !row_lse, st);
+        SABLOCK_TILE_SHAPES(X)
+        SABLOCK_TILE_SHAPES_W64(X)
 #undef X
     }
-#define X(GV, WV) if (d.G == GV && d.W == WV) return launch_score_g<GV, WV, false>(a, grid, !row_lse, st);
-    SABLOCK_SMALL_SHAPES(X)
-#undef X
     dim3 grid1((unsigned)((int64_t)d.P * a.nv * pl.n_chunks));
     if (!row_lse && stats_by_rows(d)) {
         // a lane per window query: one read of K serves all 256 rows; the chunks of this pass are its own
@@ -1659,7 +1677,7 @@ hipError_t launch_stream_probe(const Dims &d, const void *k, int read_lds, float
 // ---- head mean over all query heads of a layer (Eq. barA, literal): shapes with up to 128 window-query rows
 bool score_all_heads_supported(const Dims &d)
 {
-    return d.dtype == SABLOCK_BF16 && d.D == 128 && ((d.G == 4 && d.W == 32) || small_shape(d));
+    return d.dtype == SABLOCK_BF16 && d.D == 128 && tile_shape(d) && d.W <= 32;
 }
 
 // the shape whose layers one workgroup can sum in registers and LDS (score_mfma_columns_layer)
@@ -1683,6 +1701,7 @@ hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, c
     plan_partials(a, d, pl, ws);
     a.nv = 1;
     a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
+    a.log2_G = (float)log2((double)d.G);
     a.eps = eps;
     a.lse = row_lse;
     a.p0 = 0;
@@ -1724,8 +1743,9 @@ hipError_t launch_score_all_heads(const Dims &d, const void *q, const void *k, c
     a.e_out = nullptr;
     a.abar = reinterpret_cast<float *>(static_cast<char *>(ws) + partial_bytes(d, pl) + merged_bytes(d));
     hipError_t e = hipErrorInvalidValue;
-#define X(GV, WV) if (d.G == GV && d.W == WV) e = launch_score_g<GV, WV, true>(a, grid, !row_lse, st);
-    SABLOCK_SMALL_SHAPES(X)
+    const int nt = tiles_of(d);
+#define X(NTV, WV) if (nt == NTV && d.W == WV) e = launch_score_g<NTV, WV, true>(a, grid, !row_lse, st);
+    SABLOCK_TILE_SHAPES(X)
     X(4, 32)
 #undef X
     if (e != hipSuccess) return e;

@@ -445,16 +445,12 @@ def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, G, W):
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
 
-@pytest.mark.parametrize("G,W", [(4, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)])
-@pytest.mark.parametrize("chunk", [0, 1024])
-def test_mfma_score_head_dim_64(oracle, torch_cuda, G, W, chunk):
-    # bf16 heads of 64 elements on the matrix pipe (four k-steps per key, keys loaded straight into registers): ragged
-    # length, one and several chunks per problem, planted keys that move row references, strided K, all five steps;
-    # then the row_lse route from a library log-sum-exp
-    torch = torch_cuda
+def _mfma_row_shape_case(oracle, torch, G, W, D, chunk):
+    # ragged length, one or several chunks per problem, planted keys that move row references, strided K when chunked,
+    # all five steps; then the row_lse route from a library log-sum-exp
     from scipy.special import logsumexp
 
-    L, D, Hkv, nl = 2 * 2048 + 411 + W, 64, 2, 2
+    L, Hkv, nl = 2 * 2048 + 411 + W, 2, 2
     T = L - W
     q = synth.normal_torch(6400 + G * W, 1, (1, nl, G * Hkv, W, D), "cuda", torch.bfloat16)
     kbig = synth.normal_torch(6400 + G * W, 2, (1, nl, Hkv, L, 2 * D), "cuda", torch.bfloat16)
@@ -464,7 +460,7 @@ def test_mfma_score_head_dim_64(oracle, torch_cuda, G, W, chunk):
         k[0, l, g, t, :] = (q[0, l, g * G + h, i, :].float() * 7.0).to(torch.bfloat16)
     off = synth.segment_offsets(64, T, mean=28.0, min_len=1, max_len=200)
     cand = [1, 2, 3, 5, 7, 9, 11, 13]
-    w = synth.Workload("d64", 0, 1, nl, G * Hkv, Hkv, D, L, W, "bf16", tuple(cand), (512 + W,), (28.0,))
+    w = synth.Workload("rows", 0, 1, nl, G * Hkv, Hkv, D, L, W, "bf16", tuple(cand), (512 + W,), (28.0,))
     run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget(), tuning=dict(score_chunk=chunk))
     assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
     assert run.s[0, 700] > 0.99 / G and run.s[nl * Hkv - 1, 3000] > 0.99 / G       # planted keys take their rows
@@ -481,15 +477,38 @@ def test_mfma_score_head_dim_64(oracle, torch_cuda, G, W, chunk):
     _check_all(oracle, w, run2, q, k, v, off, [0, len(off)], range(nl * Hkv))
 
 
-@pytest.mark.parametrize("seed", range(27))
+@pytest.mark.parametrize("G,W", [(4, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)])
+@pytest.mark.parametrize("chunk", [0, 1024])
+def test_mfma_score_head_dim_64(oracle, torch_cuda, G, W, chunk):
+    # bf16 heads of 64 elements on the matrix pipe (four k-steps per key, keys loaded straight into registers)
+    _mfma_row_shape_case(oracle, torch_cuda, G, W, 64, chunk)
+
+
+@pytest.mark.parametrize("G,W,D", [(7, 16, 128), (7, 8, 128), (5, 16, 128), (3, 32, 128), (3, 8, 128), (1, 8, 128),
+                                   (12, 8, 128), (16, 8, 128), (1, 16, 128), (6, 16, 128), (1, 64, 128), (2, 64, 128),
+                                   (7, 16, 64), (5, 8, 64), (3, 16, 64), (3, 32, 64), (2, 8, 64), (2, 64, 64), (1, 64, 64)])
+@pytest.mark.parametrize("chunk", [0, 1024])
+def test_mfma_score_any_group_size(oracle, torch_cuda, G, W, D, chunk):
+    # G * W <= 128 rows with any G: the row tiles are padded to a multiple of 32 rows where 32 / W does not divide G
+    # (G = 7 with W = 16: 112 rows in four tiles; G = 3 with W = 8: 24 rows in one), and the padding adds exact
+    # zeros; windows of 64 queries take two tiles per head
+    _mfma_row_shape_case(oracle, torch_cuda, G, W, D, chunk)
+
+
+@pytest.mark.parametrize("seed", range(45))
 def test_mfma_score_random_sweep(oracle, torch_cuda, seed):
-    # every (G, W) the MFMA kernels cover, with random lengths (ragged, from W + 1 on), KV heads, layers, chunk
-    # lengths (one to many chunks per problem, with and without the fold kernel) and a few dominant keys
+    # (G, W) pairs of every kind the MFMA kernels cover (256 rows, 128 rows, fewer, padded row tiles), with random
+    # lengths (ragged, from W + 1 on), KV heads, layers, chunk lengths (one to many chunks per problem, with and
+    # without the fold kernel) and a few dominant keys
     torch = torch_cuda
     rng = np.random.default_rng(6100 + seed)
-    G, W = [(4, 32), (4, 64), (8, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)][seed % 9]
+    if seed < 27:
+        G, W = [(4, 32), (4, 64), (8, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)][seed % 9]
+        D = 64 if seed >= 18 and G * W <= 128 else 128         # seeds 18-26: heads of 64 elements where covered
+    else:
+        G, W = [(7, 16), (5, 8), (3, 32), (6, 16), (1, 8), (2, 64), (12, 8), (3, 16), (1, 64)][seed % 9]
+        D = 64 if seed >= 36 else 128
     Hkv, nl = int(rng.integers(1, 4)), int(rng.integers(1, 3))
-    D = 64 if seed >= 18 and G * W <= 128 else 128             # the last nine seeds: heads of 64 elements where covered
     L = W + int([rng.integers(1, 40), rng.integers(40, 700), rng.integers(700, 5000)][seed % 3])
     T = L - W
     chunk = [0, 128, 256, 1024][int(rng.integers(0, 4))]
@@ -938,7 +957,7 @@ def test_decode_attention_128k_full_and_compacted(oracle, torch_cuda):
         np.testing.assert_allclose(out_c[0, l, h * w.G:(h + 1) * w.G], ref, rtol=2e-4, atol=2e-5)
 
 
-@pytest.mark.parametrize("G,W,Hkv", [(4, 32, 8), (4, 32, 3), (4, 8, 3), (2, 32, 3)])
+@pytest.mark.parametrize("G,W,Hkv", [(4, 32, 8), (4, 32, 3), (4, 8, 3), (2, 32, 3), (7, 16, 3), (3, 8, 2), (3, 32, 2)])
 def test_head_mean_over_all_heads_of_a_layer(oracle, torch_cuda, G, W, Hkv):
     # Eq. barA taken literally: one score row and one retained set per (sequence, layer).  Scores against the
     # oracle's all-head mean; refine / search / select stage-wise on the per-layer rows; shared compaction.
