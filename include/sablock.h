@@ -305,6 +305,20 @@ SABLOCK_API sablock_status sablock_segment_offsets(const int32_t *token_ids, int
                                        const int32_t *seg_ptr, int32_t *seg_off_out, void *stream);
 
 /*
+ * Check of a CSR segment array on the device (Sec. 3.1: the segments S_1 .. S_K partition the compressible
+ * region, so every sequence's offsets must read 0 = off[0] < off[1] < ... < off[K] = n_tokens).  The five calls
+ * do not look at the values in seg_off (they are device data) and index s, ent and s_tilde with them, so offsets
+ * from an untrusted source are checked with this call first; it is no step of the path.
+ *   seg_off (device), seg_ptr (host, n_seq + 1 entries): as in the other calls.  n_tokens = T.
+ *   n_bad_out (device, n_seq int32): per sequence the number of offsets that break the rule (0 = valid).
+ * Enqueues one kernel on `stream`; the caller reads n_bad_out back.  Errors: INVALID_ARG for NULL pointers,
+ * n_seq < 1, n_tokens < 1, a seg_ptr that leaves a sequence fewer than 2 or more than n_tokens + 1 offsets;
+ * UNSUPPORTED for n_seq > 64.
+ */
+SABLOCK_API sablock_status sablock_validate_segments(const int32_t *seg_off, const int32_t *seg_ptr, int32_t n_seq,
+                                         int32_t n_tokens, int32_t *n_bad_out, void *stream);
+
+/*
  * Decode-time attention of ONE new token over a KV cache (Sec. 2.1, Eq. 1 with a single query position): the
  * step after the path, over the compacted cache that sablock_compact wrote or over the full cache.  For every
  * problem p and each of its G query heads h:  out[h] = softmax_r(<q[h], K[p][r]> / sqrt(D)) . V[p][r].

@@ -26,7 +26,7 @@ EXPORTS = ("sablock_version", "sablock_last_error", "sablock_workspace_bytes", "
            "sablock_segment_count", "sablock_segment_offsets", "sablock_decode_workspace_bytes",
            "sablock_decode_attention", "sablock_score_all_heads_workspace_bytes", "sablock_score_all_heads",
            "sablock_compact_shared", "sablock_search_select", "sablock_window_attention_workspace_bytes",
-           "sablock_window_attention", "sablock_score_static", "sablock_stream_probe")
+           "sablock_window_attention", "sablock_score_static", "sablock_stream_probe", "sablock_validate_segments")
 
 
 class SablockError(RuntimeError):
@@ -87,6 +87,7 @@ def load():
         lib.sablock_segment_count.argtypes = [vp, ctypes.c_int64, i32, i32, ctypes.POINTER(i32), i32, vp, vp]
         lib.sablock_segment_offsets.argtypes = [vp, ctypes.c_int64, i32, i32, ctypes.POINTER(i32), i32,
                                                 ctypes.POINTER(i32), vp, vp]
+        lib.sablock_validate_segments.argtypes = [vp, ctypes.POINTER(i32), i32, i32, vp, vp]
         lib.sablock_decode_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
         lib.sablock_decode_attention.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, ctypes.c_size_t, vp]
         lib.sablock_score_all_heads_workspace_bytes.argtypes = [sp, ctypes.POINTER(ctypes.c_size_t)]
@@ -242,6 +243,12 @@ def sablock_segment_offsets(token_ids, delims: Sequence[int], seg_ptr: Sequence[
     sp = (ctypes.c_int32 * len(seg_ptr))(*[int(x) for x in seg_ptr])
     _check(load().sablock_segment_offsets(_ptr(token_ids), token_ids.stride(0), token_ids.shape[0],
                                           token_ids.shape[1], d, len(delims), sp, _ptr(seg_off_out), _stream(stream)))
+
+
+def sablock_validate_segments(seg_off, seg_ptr: Sequence[int], n_tokens: int, n_bad_out, stream=None):
+    sp = (ctypes.c_int32 * len(seg_ptr))(*[int(x) for x in seg_ptr])
+    _check(load().sablock_validate_segments(_ptr(seg_off), sp, len(seg_ptr) - 1, int(n_tokens), _ptr(n_bad_out),
+                                            _stream(stream)))
 
 
 def segment(token_ids, delims: Sequence[int]) -> "Segments":

@@ -511,6 +511,24 @@ sablock_status sablock_segment_offsets(const int32_t *token_ids, int64_t token_s
                                       static_cast<hipStream_t>(stream)), "sablock_segment_offsets");
 }
 
+sablock_status sablock_validate_segments(const int32_t *seg_off, const int32_t *seg_ptr, int32_t n_seq, int32_t n_tokens,
+                                         int32_t *n_bad_out, void *stream)
+{
+    if (!seg_off || !seg_ptr || !n_bad_out) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_validate_segments: NULL argument");
+    if (n_seq < 1 || n_tokens < 1) return fail(SABLOCK_ERR_INVALID_ARG, "sablock_validate_segments: need n_seq >= 1, n_tokens >= 1");
+    if (n_seq > MAX_SEQ) return fail(SABLOCK_ERR_UNSUPPORTED, "n_seq %d: at most %d per call", n_seq, MAX_SEQ);
+    if (seg_ptr[0] < 0) return fail(SABLOCK_ERR_INVALID_ARG, "seg_ptr[0] < 0");
+    SeqPtr sp;
+    for (int s = 0; s <= MAX_SEQ; ++s) sp.ptr[s] = seg_ptr[s < n_seq ? s : n_seq];
+    for (int s = 0; s < n_seq; ++s) {
+        const int n = seg_ptr[s + 1] - seg_ptr[s];
+        if (n < 2 || n > n_tokens + 1)
+            return fail(SABLOCK_ERR_INVALID_ARG, "sequence %d: seg_ptr leaves %d offsets, need 2 .. n_tokens + 1", s, n);
+    }
+    return dev(launch_segment_check(seg_off, n_seq, n_tokens, sp, n_bad_out, static_cast<hipStream_t>(stream)),
+               "sablock_validate_segments");
+}
+
 static sablock_status make_cache_dims(const sablock_shape *shape, Dims *d)
 {
     if (!shape) return fail(SABLOCK_ERR_INVALID_ARG, "shape is NULL");

@@ -136,6 +136,8 @@ hipError_t launch_segment_count(const int32_t *tok, int64_t stride, int32_t n_se
                                 int32_t *seg_count, hipStream_t st);
 hipError_t launch_segment_offsets(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,
                                   const SeqPtr &sp, int32_t *seg_off, hipStream_t st);
+hipError_t launch_segment_check(const int32_t *seg_off, int32_t n_seq, int32_t T, const SeqPtr &sp, int32_t *bad,
+                                hipStream_t st);
 
 // Opt-ins that hold per device (dynamic LDS above 64 KiB for a kernel) are made once per host thread and device:
 //     static thread_local PerDeviceOnce once;  if (once.needed()) { ...; once.done(); }

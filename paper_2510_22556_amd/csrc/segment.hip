@@ -84,7 +84,36 @@ segment_offsets_kernel(const int32_t *tok, int64_t stride, int T, DelimSet ds, S
     if (threadIdx.x == 0 && carry < n_out) out[carry] = T;
 }
 
+// grid (n_seq): bad[s] = number of offsets of sequence s that break "0 = off[0] < off[1] < ... < off[K] = T"
+// (an entry counts when it is not above its predecessor; the first when it is not 0, the last also when it is not T)
+__global__ void __launch_bounds__(SG_THREADS)
+segment_check_kernel(const int32_t *seg_off, SeqPtr sp, int T, int32_t *bad)
+{
+    __shared__ int sh_w[SG_THREADS / 64];
+    const int s = blockIdx.x;
+    const int32_t *off = seg_off + sp.ptr[s];
+    const int n = sp.ptr[s + 1] - sp.ptr[s];              // offsets of this sequence, >= 2
+    int mine = 0;
+    for (int j = threadIdx.x; j < n; j += SG_THREADS) {
+        const int v = off[j];
+        bool ok = j == 0 ? v == 0 : v > off[j - 1];
+        if (j == n - 1) ok = ok && v == T;
+        mine += !ok;
+    }
+    int total;
+    block_exclusive(mine, sh_w, total);
+    if (threadIdx.x == 0) bad[s] = total;
+}
+
 }  // namespace
+
+hipError_t launch_segment_check(const int32_t *seg_off, int32_t n_seq, int32_t T, const SeqPtr &sp, int32_t *bad,
+                                hipStream_t st)
+{
+    if (n_seq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(segment_check_kernel, dim3(n_seq), dim3(SG_THREADS), 0, st, seg_off, sp, T, bad);
+    return hipGetLastError();
+}
 
 hipError_t launch_segment_count(const int32_t *tok, int64_t stride, int32_t n_seq, int32_t T, const DelimSet &ds,
                                 int32_t *seg_count, hipStream_t st)

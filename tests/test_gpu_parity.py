@@ -856,6 +856,38 @@ def test_segmentation_matches_oracle_and_feeds_the_path(oracle, torch_cuda):
     _check_all(oracle, w, run, q, k, v, off, ptr, range(w.n_kv_heads))
 
 
+def test_segment_offsets_are_checked_on_the_device(torch_cuda):
+    # the debug call in front of the path: counts, per sequence, the offsets that break 0 = off[0] < ... < off[K] = T
+    torch = torch_cuda
+    from paper_2510_22556_amd import binding as B
+
+    T = 5000
+    a = synth.segment_offsets(5, T, mean=9.0, min_len=1, max_len=64)
+    b = synth.segment_offsets(6, T, mean=300.0, min_len=1, max_len=2000)
+    c = np.array([0, T], dtype=np.int32)
+    ptr = [0, len(a), len(a) + len(b), len(a) + len(b) + 2]
+
+    def bad(xa, xb, xc):
+        off = torch.as_tensor(np.concatenate([xa, xb, xc]).astype(np.int32)).cuda()
+        out = torch.full((3,), -1, dtype=torch.int32, device="cuda")
+        B.sablock_validate_segments(off, ptr, T, out)
+        torch.cuda.synchronize()
+        return H.to_np(out).tolist()
+
+    assert bad(a, b, c) == [0, 0, 0]
+    a1 = a.copy(); a1[0] = 1                                    # does not start at 0 (a[1] >= 1: may also stop the rise)
+    assert bad(a1, b, c)[0] in (1, 2) and bad(a1, b, c)[1:] == [0, 0]
+    b1 = b.copy(); b1[-1] = T - 1                               # does not end at T
+    assert bad(a, b1, c) == [0, 1, 0]
+    a2 = a.copy(); a2[7] = a2[6]                                # an empty segment
+    assert bad(a2, b, c) == [1, 0, 0]
+    a3 = a.copy(); a3[1200 % len(a)] = T + 50                   # beyond the region: it and its successor break the rise
+    n3 = bad(a3, b, c)
+    assert n3[0] >= 1 and n3[1:] == [0, 0]
+    assert bad(a, b, np.array([0, T + 1])) == [0, 0, 1]
+    assert bad(a[::-1].copy(), b, c)[0] == len(a)               # descending: every entry counts (first is not 0, ...)
+
+
 def _decode_gpu(torch, q, kc, vc, n_sel=None, budget=0):
     from paper_2510_22556_amd import binding as B
 

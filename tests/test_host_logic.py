@@ -154,6 +154,11 @@ def test_calls_reject_bad_host_arguments_before_launch(lib):
     assert lib.sablock_segment_count(fake, 100, 1, 100, many, 65, fake, None) == 2
     assert lib.sablock_segment_count(fake, 100, 65, 100, dl, 2, fake, None) == 2
     assert lib.sablock_segment_offsets(fake, 100, 1, 100, dl, 2, None, fake, None) == 1
+    assert lib.sablock_validate_segments(None, (ctypes.c_int32 * 2)(0, 3), 1, 100, fake, None) == 1
+    assert lib.sablock_validate_segments(fake, (ctypes.c_int32 * 2)(0, 3), 1, 100, None, None) == 1
+    assert lib.sablock_validate_segments(fake, (ctypes.c_int32 * 2)(0, 1), 1, 100, fake, None) == 1               # < 2 offsets
+    assert lib.sablock_validate_segments(fake, (ctypes.c_int32 * 2)(0, 200), 1, 100, fake, None) == 1             # > T + 1
+    assert lib.sablock_validate_segments(fake, (ctypes.c_int32 * 2)(0, 3), 65, 100, fake, None) == 2
     assert lib.sablock_segment_offsets(fake, 100, 1, 100, dl, 2, (ctypes.c_int32 * 2)(0, 1), fake, None) == 1     # < 2 offsets
     assert lib.sablock_segment_offsets(fake, 100, 1, 100, dl, 2, (ctypes.c_int32 * 2)(0, 200), fake, None) == 1   # > T + 1
 
