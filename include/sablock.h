@@ -273,8 +273,7 @@ SABLOCK_API sablock_status sablock_compact_shared(const sablock_shape *shape, co
  * kernel) hands row_lse to sablock_score, which then reads K once.
  *   out          [n_seq][n_layers][n_q_heads][W][D] fp32: softmax(q . k / sqrt(D)) @ v
  *   row_lse_out  [P][G * W] fp32, natural log of the softmax denominators, in the layout sablock_score takes
- * Supported: bf16, head_dim 128, W in {8, 16, 32, 64} with G * W in {32, 64, 128, 256} (the shapes of the MFMA
- * scoring kernels, e.g. (G, W) = (4, 32), (4, 64), (8, 32), (4, 8), (4, 16)); otherwise UNSUPPORTED.  Probabilities enter
+ * Supported: bf16, head_dim 128, W in {8, 16, 32, 64} and any G with G * W <= 256; otherwise UNSUPPORTED.  Probabilities enter
  * the second product rounded to bf16 (the denominators are summed in fp32 before rounding).
  */
 SABLOCK_API sablock_status sablock_window_attention_workspace_bytes(const sablock_shape *shape, size_t *bytes_out);

@@ -147,10 +147,14 @@ window_attention_kernel(WinArgs a)
 
     // ---- this block's window queries: B operand of S^T = K Q^T, lane (query n, half hf) holds Q[n][(2s + hf) * 8 .. +8]
     bf16x8 qa[8];
-    {
+    const bool real_row = ROWS * wave + n < d.G * d.W;         // rows behind the problem's G * W pad the last block(s)
+    if (real_row) {
         const uint16_t *row = a.q + q_row_offset(d, p, head, qoff + n);
 #pragma unroll
         for (int s = 0; s < 8; ++s) qa[s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+    } else {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) qa[s] = bf16x8{};
     }
 
     floatx16 o[4];                                             // O[query][32 t + d], rows = queries
@@ -358,10 +362,11 @@ window_attention_kernel(WinArgs a)
     }
     const int pb = p * NW + wave;                              // (problem, row block)
     const int64_t out_row0 = (int64_t)p * d.G * d.W + ROWS * wave;             // first output row of this block
+    const int rows_here = min(ROWS, d.G * d.W - ROWS * wave);  // real rows of this block (<= 0: all padding)
     if (a.n_chunks == 1) {
         if (hf == 0) {
             fac[n] = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-            a.lse[out_row0 + n] = (ref2 + __builtin_amdgcn_logf(l_tot)) * LN2;
+            if (real_row) a.lse[out_row0 + n] = (ref2 + __builtin_amdgcn_logf(l_tot)) * LN2;
         }
     } else if (hf == 0) {
         fac[n] = 1.f;
@@ -377,18 +382,20 @@ window_attention_kernel(WinArgs a)
         const int qy = row_of(i, hf);
         const float fi = fac[qy];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) ob[qy * 128 + 32 * t + n] = o[t][i] * fi;
+        for (int t = 0; t < 4; ++t)
+            if (a.n_chunks > 1 || qy < rows_here) ob[qy * 128 + 32 * t + n] = o[t][i] * fi;
     }
 }
 
 // merge of the chunks' partial results: one workgroup per output row (problem, head, window query), one thread per
 // output column; the row's partial results sit in row block (head, window half) of its problem
 __global__ void __launch_bounds__(128)
-window_attention_merge_kernel(const float *o_part, const float *ml_part, int n_chunks, int G, int W, float *out, float *lse)
+window_attention_merge_kernel(const float *o_part, const float *ml_part, int n_chunks, int G, int W, int nw, float *out,
+                              float *lse)
 {
     const int row = blockIdx.x;                                // (p * G + h) * W + i
     const int GW = G * W, p = row / GW, r = row - p * GW;      // r = h * W + i: blocks of 32 consecutive r
-    const int pb = p * (GW / ROWS) + r / ROWS, qy = r % ROWS;
+    const int pb = p * nw + r / ROWS, qy = r % ROWS;           // nw row blocks per problem (the last ones may be padding)
     float m = -INFINITY;
     for (int c = 0; c < n_chunks; ++c) {
         const float *ml = ml_part + (((int64_t)pb * n_chunks + c) * ROWS + qy) * 2;
@@ -462,18 +469,25 @@ hipError_t launch_row_stats(const Dims &d, const void *q, const void *k, float *
 
 bool window_attention_supported(const Dims &d)
 {
-    // whole blocks of 32 rows, each of whole heads or inside one head: the shapes of the MFMA scoring kernels
-    const int rows = d.G * d.W;
-    return d.dtype == SABLOCK_BF16 && d.D == 128 && (rows == 32 || rows == 64 || rows == 128 || rows == 256) &&
+    // blocks of 32 rows, each of whole heads or inside one head; up to 8 blocks
+    return d.dtype == SABLOCK_BF16 && d.D == 128 && d.G * d.W <= 8 * ROWS &&
            (d.W == 8 || d.W == 16 || d.W == 32 || d.W == 64);
+}
+
+// wavefronts per workgroup: the problem's G * W rows in blocks of 32, rounded up to 1, 2, 4 or 8 blocks (the
+// kernel splits a stage's eight key pieces evenly over its wavefronts); blocks behind the rows are padding
+static int wa_blocks(const Dims &d)
+{
+    const int nb = (d.G * d.W + ROWS - 1) / ROWS;
+    return nb <= 1 ? 1 : nb <= 2 ? 2 : nb <= 4 ? 4 : 8;
 }
 
 size_t window_attention_ws_bytes(const Dims &d)
 {
     int len, nc;
-    wa_plan(d, &len, &nc, d.G * d.W / ROWS <= 4 ? 2 : 1);
+    wa_plan(d, &len, &nc, wa_blocks(d) <= 4 ? 2 : 1);
     if (nc == 1) return 256;
-    const size_t blocks = (size_t)d.P * (d.G * d.W / ROWS);
+    const size_t blocks = (size_t)d.P * wa_blocks(d);
     return align256(blocks * nc * ROWS * 128 * 4) + align256(blocks * nc * ROWS * 2 * 4);
 }
 
@@ -496,7 +510,7 @@ hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, 
         if (e != hipSuccess) return e;
         attr_once.done();
     }
-    const int nw = d.G * d.W / ROWS;                           // 1, 2, 4 or 8 row blocks = wavefronts per workgroup
+    const int nw = wa_blocks(d);                               // 1, 2, 4 or 8 row blocks = wavefronts per workgroup
     WinArgs a;
     a.d = d;
     a.q = static_cast<const uint16_t *>(q);
@@ -517,7 +531,7 @@ hipError_t launch_window_attention(const Dims &d, const void *q, const void *k, 
     else hipLaunchKernelGGL((window_attention_kernel<8, true>), grid, dim3(8 * 64), wa_lds(8), st, a);
     if (a.n_chunks > 1)
         hipLaunchKernelGGL(window_attention_merge_kernel, dim3((unsigned)((int64_t)d.P * d.G * d.W)), dim3(128), 0, st,
-                           a.o_part, a.ml_part, a.n_chunks, d.G, d.W, out, lse);
+                           a.o_part, a.ml_part, a.n_chunks, d.G, d.W, nw, out, lse);
     return hipGetLastError();
 }
 

@@ -1251,10 +1251,12 @@ def test_ablation_switches_as_degenerate_configurations(oracle, torch_cuda):
     assert np.array_equal(run.st, run.s[:, :w.T])
 
 
-@pytest.mark.parametrize("G,W", [(4, 32), (4, 64), (8, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32)])
+@pytest.mark.parametrize("G,W", [(4, 32), (4, 64), (8, 32), (4, 8), (4, 16), (8, 8), (8, 16), (2, 32), (1, 32),
+                                 (7, 16), (3, 32), (5, 8), (7, 32), (3, 64), (6, 16), (1, 8), (5, 32)])
 @pytest.mark.parametrize("extra", [1, 31, 32, 33, 200, 3001])
 def test_window_attention_short_contexts(oracle, torch_cuda, G, W, extra):
-    # every shape the kernel covers (one to eight blocks of 32 rows; several heads per block when W < 32) on
+    # every kind of shape the kernel covers (one to eight blocks of 32 rows; several heads per block when W < 32;
+    # group sizes that leave the last block partly or wholly padding: 112, 96, 40, 224, 192, 8, 160 rows) on
     # contexts of W + 1 ... W + 3001 tokens: a single ragged subtile, chunks whose keys most rows do not see (their
     # partial sums are empty), the window starting inside the first subtile, many chunks
     torch = torch_cuda

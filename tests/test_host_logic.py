@@ -218,9 +218,10 @@ def test_all_head_calls_validate_host_arguments(lib):
     assert lib.sablock_window_attention(sp, fake, fake, ctypes.c_void_p(0x1008), fake, fake, fake, nw, None) == 1
     assert lib.sablock_window_attention(sp, fake, fake, fake, fake, fake, fake, nw - 1, None) == 3
     assert lib.sablock_window_attention(sp, fake, fake, fake, fake, fake, None, nw, None) == 3
-    for ok in (dict(window=8), dict(window=16), dict(window=64), dict(n_q_heads=16), dict(n_q_heads=4), dict(n_q_heads=2)):
+    for ok in (dict(window=8), dict(window=16), dict(window=64), dict(n_q_heads=16), dict(n_q_heads=4), dict(n_q_heads=2),
+               dict(n_q_heads=6), dict(n_q_heads=14), dict(n_q_heads=10, window=8)):
         assert B.sablock_window_attention_workspace_bytes(llama_shape(**ok)) >= 256, ok
-    for bad in (dict(dtype=B.SABLOCK_F32), dict(head_dim=64), dict(window=24), dict(window=128), dict(n_q_heads=6), dict(n_q_heads=32)):
+    for bad in (dict(dtype=B.SABLOCK_F32), dict(head_dim=64), dict(window=24), dict(window=128), dict(n_q_heads=18), dict(n_q_heads=32)):
         with pytest.raises(B.SablockError) as ei:
             B.sablock_window_attention_workspace_bytes(llama_shape(**bad))
         assert ei.value.status == 2, bad
