@@ -307,9 +307,14 @@ __device__ __forceinline__ void load_queries(bf16x8 (&qa)[4][8], const uint16_t 
 {
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-        const uint16_t *row = q + q_row_offset(d, p, h0 + h, n);   // n: window query of this lane
+        if (h0 + h < d.G) {
+            const uint16_t *row = q + q_row_offset(d, p, h0 + h, n);   // n: window query of this lane
 #pragma unroll
-        for (int s = 0; s < 8; ++s) qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+            for (int s = 0; s < 8; ++s) qa[h][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+        } else {                                                   // a head behind the group's last: padding, zero queries
+#pragma unroll
+            for (int s = 0; s < 8; ++s) qa[h][s] = bf16x8{};
+        }
     }
 #pragma unroll
     for (int h = 0; h < 4; ++h)
@@ -708,9 +713,10 @@ score_mfma_columns(ScoreArgs a)
 }
 
 // ------------------------------------------------------------------ pass 2, 256 rows
-// Eight 32-row tiles.  W = 64: tile j holds head j / 2, window queries 32 (j % 2) .. +32; W = 32 (G = 8): tile j
-// holds head j.  Same pipeline as above with the tiles rotating through two accumulators; ab[b] collects the
-// head mean of the window queries 32 b .. 32 b + 31.
+// Eight 32-row tiles.  W = 64: tile j holds head j / 2, window queries 32 (j % 2) .. +32; W = 32: tile j holds
+// head j.  Groups of fewer heads than the tiles hold (G = 5 .. 7 with W = 32, G = 3 with W = 64) leave the last
+// tiles as padding: zero queries and an infinite log-sum-exp, so they add exact zeros.  Same pipeline as above with
+// the tiles rotating through two accumulators; ab[b] collects the head mean of the window queries 32 b .. 32 b + 31.
 template <int W> struct Tiles8 {
     static constexpr int NB = W / 32;                                        // 32-query blocks of the window
     __host__ __device__ static constexpr int head(int j) { return W == 64 ? j / 2 : j; }
@@ -788,7 +794,6 @@ __global__ void __launch_bounds__(WAVES * 64)
 score_mfma_columns8t(ScoreArgs a)
 {
     using TL = Tiles8<W>;
-    constexpr int G = M_ROWS64 / W;
     extern __shared__ __attribute__((aligned(8192))) char lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hf = lane >> 5;
@@ -808,8 +813,11 @@ score_mfma_columns8t(ScoreArgs a)
         const int r = threadIdx.x, h = r / W, i = r % W;
         const int j = W == 64 ? 2 * h + i / 32 : h;                           // the row's tile
         float m = -INFINITY, zz = 0.f;
-        if (a.lse) {
-            m = a.lse[(int64_t)w.p * M_ROWS64 + r] * LOG2E;
+        if (h >= d.G) {                                                       // padding row
+            m = INFINITY;
+            zz = 1.f;
+        } else if (a.lse) {
+            m = a.lse[(int64_t)w.p * d.G * W + r] * LOG2E;
             zz = 1.f;
         } else {
             const float *pp = a.merged + (((int64_t)(w.p * 2 + TL::p1_block(j)) * a.pc) * M_ROWS + TL::p1_group(j) * 32 + (i & 31)) * 2;
@@ -822,7 +830,7 @@ score_mfma_columns8t(ScoreArgs a)
                 }
             }
         }
-        lse2[r] = m + __builtin_amdgcn_logf(zz) + (G == 4 ? 2.0f : 3.0f);    // + log2(G): exp2 then yields A / G
+        lse2[r] = m + __builtin_amdgcn_logf(zz) + a.log2_G;                   // + log2(G): exp2 then yields A / G
     }
     __syncthreads();
     {
@@ -836,9 +844,14 @@ score_mfma_columns8t(ScoreArgs a)
     bf16x8 qa[8][8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const uint16_t *row = a.q + q_row_offset(d, w.p, TL::head(j), TL::qoff(j) + n);
+        if (TL::head(j) < d.G) {
+            const uint16_t *row = a.q + q_row_offset(d, w.p, TL::head(j), TL::qoff(j) + n);
 #pragma unroll
-        for (int s = 0; s < 8; ++s) qa[j][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+            for (int s = 0; s < 8; ++s) qa[j][s] = *reinterpret_cast<const bf16x8 *>(row + (2 * s + hf) * 8);
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) qa[j][s] = bf16x8{};
+        }
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -1451,6 +1464,11 @@ bool tile_shape(const Dims &d)
     return (d.W == 8 || d.W == 16 || d.W == 32 || d.W == 64) && d.G >= 1 && d.G * d.W <= M_ROWS;
 }
 int tiles_of(const Dims &d) { return (d.G * d.W + 31) / 32; }
+// 129 .. 256 rows of a window of 32 or 64 queries (G = 5 .. 8 / G = 3, 4): the eight-tile column kernels
+bool wide_shape(const Dims &d)
+{
+    return (d.W == 32 || d.W == 64) && d.G * d.W > M_ROWS && d.G * d.W <= 2 * M_ROWS;
+}
 
 struct Plan {
     int chunk_len;    // keys per workgroup
@@ -1484,8 +1502,10 @@ Plan make_plan(const Dims &d)
 }
 
 // bytes of the chunk partials, and of their merged form behind them
-size_t partial_bytes(const Dims &d, const Plan &pl) { return align256((size_t)d.P * pl.n_chunks * d.G * d.W * 2 * 4); }
-size_t merged_bytes(const Dims &d) { return align256((size_t)d.P * d.G * d.W * 2 * 4); }
+// (more than 128 rows: two blocks of 128 rows, the second padded where G * W < 256)
+int stat_rows(const Dims &d) { return d.G * d.W > M_ROWS ? 2 * M_ROWS : d.G * d.W; }
+size_t partial_bytes(const Dims &d, const Plan &pl) { return align256((size_t)d.P * pl.n_chunks * stat_rows(d) * 2 * 4); }
+size_t merged_bytes(const Dims &d) { return align256((size_t)d.P * stat_rows(d) * 2 * 4); }
 
 // pass-1 bookkeeping of both entry points: where the partials go and what pass 2 reads
 void plan_partials(ScoreArgs &a, const Dims &d, const Plan &pl, void *ws)
@@ -1507,7 +1527,7 @@ bool score_mfma_supported(const Dims &d)
 {
     if (d.dtype != SABLOCK_BF16) return false;
     if (d.D == 64) return tile_shape(d);                                    // up to 128 rows, kernels for any row shape
-    return d.D == 128 && (tile_shape(d) || (d.G == 4 && d.W == 64) || (d.G == 8 && d.W == 32));
+    return d.D == 128 && (tile_shape(d) || wide_shape(d));
 }
 
 // pass 1 for 256 rows by the transposed-score kernel (csrc/window_attn.hip): K is read once instead of once per
@@ -1556,7 +1576,7 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
     a.lse = row_lse;
     a.abar = nullptr;
     a.p0 = 0;
-    a.nv = d.G * d.W > M_ROWS ? d.G * d.W / M_ROWS : 1;
+    a.nv = d.G * d.W > M_ROWS ? 2 : 1;
     dim3 grid((unsigned)((int64_t)d.P * pl.n_chunks));
     if (tile_shape(d)) {
         const int nt = tiles_of(d);
@@ -1593,7 +1613,7 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
         launch_merge(a, d.P * a.nv, M_ROWS, st);
     }
     if (d.W == 64) hipLaunchKernelGGL(score_mfma_columns8t<64>, grid, dim3(WAVES * 64), P2W_LDS, st, a);
-    else if (d.G == 8) hipLaunchKernelGGL(score_mfma_columns8t<32>, grid, dim3(WAVES * 64), P2W_LDS, st, a);
+    else if (d.G > 4) hipLaunchKernelGGL(score_mfma_columns8t<32>, grid, dim3(WAVES * 64), P2W_LDS, st, a);
     else hipLaunchKernelGGL(score_mfma_columns, grid, dim3(WAVES * 64), P2_LDS, st, a);
     return hipGetLastError();
 }

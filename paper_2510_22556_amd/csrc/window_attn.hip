@@ -434,7 +434,7 @@ void wa_plan(const Dims &d, int *chunk_len, int *n_chunks, int wgs_per_cu)
 // ---- the statistics alone for 256 window-query rows per KV head, as the first pass of the scoring step
 bool row_stats_supported(const Dims &d)
 {
-    return d.dtype == SABLOCK_BF16 && d.D == 128 && ((d.G == 4 && d.W == 64) || (d.G == 8 && d.W == 32));
+    return d.dtype == SABLOCK_BF16 && d.D == 128 && (d.W == 32 || d.W == 64) && d.G * d.W > 128 && d.G * d.W <= 256;
 }
 
 int row_stats_chunks(const Dims &d)

@@ -445,7 +445,7 @@ def test_mfma_score_other_head_and_window_shapes(oracle, torch_cuda, G, W):
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(Hkv))
 
 
-def _mfma_row_shape_case(oracle, torch, G, W, D, chunk):
+def _mfma_row_shape_case(oracle, torch, G, W, D, chunk, **tuning):
     # ragged length, one or several chunks per problem, planted keys that move row references, strided K when chunked,
     # all five steps; then the row_lse route from a library log-sum-exp
     from scipy.special import logsumexp
@@ -461,7 +461,7 @@ def _mfma_row_shape_case(oracle, torch, G, W, D, chunk):
     off = synth.segment_offsets(64, T, mean=28.0, min_len=1, max_len=200)
     cand = [1, 2, 3, 5, 7, 9, 11, 13]
     w = synth.Workload("rows", 0, 1, nl, G * Hkv, Hkv, D, L, W, "bf16", tuple(cand), (512 + W,), (28.0,))
-    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget(), tuning=dict(score_chunk=chunk))
+    run = H.GpuRun(q, k, v, off, [0, len(off)], cand, w.budget(), tuning=dict(score_chunk=chunk, **tuning))
     assert np.allclose(run.s.sum(axis=1), W, rtol=1e-4)
     assert run.s[0, 700] > 0.99 / G and run.s[nl * Hkv - 1, 3000] > 0.99 / G       # planted keys take their rows
     _check_all(oracle, w, run, q, k, v, off, [0, len(off)], range(nl * Hkv))
@@ -493,6 +493,15 @@ def test_mfma_score_any_group_size(oracle, torch_cuda, G, W, D, chunk):
     # (G = 7 with W = 16: 112 rows in four tiles; G = 3 with W = 8: 24 rows in one), and the padding adds exact
     # zeros; windows of 64 queries take two tiles per head
     _mfma_row_shape_case(oracle, torch_cuda, G, W, D, chunk)
+
+
+@pytest.mark.parametrize("G,W", [(5, 32), (6, 32), (7, 32), (3, 64), (8, 32), (4, 64)])
+@pytest.mark.parametrize("chunk,per_key", [(0, 0), (1024, 0), (1024, 1)])
+def test_mfma_score_wide_groups(oracle, torch_cuda, G, W, chunk, per_key):
+    # 129 .. 256 rows on the eight-tile column kernel: G = 5, 6, 7 with W = 32 and G = 3 with W = 64 leave its last
+    # tiles as padding (zero queries, infinite log-sum-exp); both forms of the statistics pass (a lane per window
+    # query over all rows; a lane per key over blocks of 128 rows), one and several chunks, then the row_lse route
+    _mfma_row_shape_case(oracle, torch_cuda, G, W, 128, chunk, stats_per_key=per_key)
 
 
 @pytest.mark.parametrize("seed", range(45))
