@@ -224,37 +224,42 @@ struct KeyStream {
     uint32_t lane_addr0, ring_lds;
     uint32_t lane_off[4];
     int first, n_sub, L, lane;
+    const char *next;                                          // keys of the next subtile to issue
+    int64_t step;                                              // bytes between consecutive subtiles of this stream
 
     __device__ __forceinline__ void init(const uint16_t *kp_, int64_t ks3_, char *ring_, int first_, int n_sub_, int L_, int lane_)
     {
         kp = kp_; ks3 = ks3_; ring = ring_; first = first_; n_sub = n_sub_; L = L_; lane = lane_;
+        next = reinterpret_cast<const char *>(kp) + (int64_t)first * ks3 * 2;
+        step = (int64_t)STRIDE * ks3 * 2;
         const int n = lane & 31, hf = lane >> 5, r4 = lane >> 4, pos = lane & 15;
         ring_lds = __builtin_amdgcn_readfirstlane(lds_addr(ring));
         lane_addr0 = ring_lds + n * ROW_BYTES + ((hf ^ (n & 15)) << 4);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) lane_off[jj] = (uint32_t)(r4 * ks3 * 2) + (uint32_t)(((pos ^ r4 ^ (4 * jj)) & 15) << 4);
     }
-    __device__ __forceinline__ void issue(int u) const
+    __device__ __forceinline__ void issue(int u)
     {
         const int t0 = first + u * STRIDE;                     // wave-uniform, < L
-        const char *base = reinterpret_cast<const char *>(kp) + (int64_t)t0 * ks3 * 2;
+        const char *base = next;                               // subtiles are issued in order: a running address
+        next += step;
         const uint32_t buf_lds = ring_lds + (u % NBUF) * BUF_BYTES;
         if (t0 + SUB <= L) {
             if (ks3 == ROW_BYTES / 2) issue_subtile_dense(base, lane_off, buf_lds);
             else issue_subtile_fast(base, ks3 * 2, lane_off, buf_lds);
         } else issue_subtile_clamped(base, ks3 * 2, L - t0, buf_lds, lane);
     }
-    __device__ __forceinline__ void prime() const
+    __device__ __forceinline__ void prime()
     {
         for (int u = 0; u < min(NBUF, n_sub); ++u) issue(u);
     }
-    __device__ __forceinline__ void fetch(int u, bf16x8 (&kb)[8]) const
+    __device__ __forceinline__ void fetch(int u, bf16x8 (&kb)[8])
     {
         wait_loads(min(NBUF - 1, n_sub - 1 - u));
         read_subtile_acc(lane_addr0 + (u % NBUF) * BUF_BYTES, kb);
         if (u + NBUF < n_sub) issue(u + NBUF);
     }
-    __device__ __forceinline__ void fetch_vgpr(int u, bf16x8 (&kb)[8]) const
+    __device__ __forceinline__ void fetch_vgpr(int u, bf16x8 (&kb)[8])
     {
         wait_loads(min(NBUF - 1, n_sub - 1 - u));
         read_subtile_vgpr(lane_addr0 + (u % NBUF) * BUF_BYTES, kb);
