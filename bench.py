@@ -327,6 +327,13 @@ def yardstick(torch, B, path, reps=10):
     # first, so its keys are the most recently used bytes of the memory-side cache)
     ms_all = timed(lambda: B.sablock_score(shape, q, k, buf.s, buf.ent, buf.ws, w.eps), reps)
     out["score_two_passes"] = {"one_call_all_problems_ms": ms_all, "groups": {}}
+    if G == 4 and w.window == 32:
+        # the statistics pass by the other kernel design (a lane per window query, four wavefronts per SIMD sharing
+        # the key tiles through a workgroup-wide ring) instead of a lane per key with a private ring per wavefront
+        shape_rows = B.make_shape(q, k, stats_per_key=2)
+        ws_rows = torch.empty((B.sablock_workspace_bytes(shape_rows, 0, 0),), dtype=torch.uint8, device=path.dev)
+        out["score_two_passes"]["statistics_by_window_query_kernel_ms"] = timed(
+            lambda: B.sablock_score(shape_rows, q, k, buf.s, buf.ent, ws_rows, w.eps), reps)
     for n in (2, 4, 8):
         if w.n_kv_heads % n:
             continue

@@ -84,8 +84,11 @@ typedef struct {
                                  >= 32, rounded down to a multiple of 32; 0 = whole rounds of workgroups */
     int32_t topb_slices;      /* workgroups per row of the two Top-B passes of sablock_search_select, 1 .. 64
                                  (1 = the per-row kernel alone); 0 = by problems per compute unit */
-    int32_t stats_per_key;    /* shapes with 256 window-query rows per KV head: 1 = row statistics by the 128-row
-                                 kernel on two row blocks (K read twice by that pass) instead of the one-read kernel */
+    int32_t stats_per_key;    /* which kernel forms the row statistics where two exist (head_dim 128; 129 .. 256
+                                 window-query rows per KV head, and G = 4 with W = 32): 1 = the kernel with a lane per
+                                 key on blocks of 128 rows (two blocks: K read twice by that pass), 2 = the kernel with a
+                                 lane per window query (one read of K for all rows); 0 = the faster one by measurement
+                                 (2 above 128 rows, 1 at 128) */
     int32_t reserved[3];      /* must be 0 */
 } sablock_tuning;
 

@@ -115,8 +115,8 @@ sablock_status make_dims(const sablock_shape *s, Dims *d)
         return fail(SABLOCK_ERR_INVALID_ARG, "tuning.window_chunk %d: need 0 or 32 .. 131072", tu.window_chunk);
     if (tu.topb_slices < 0 || tu.topb_slices > 64)
         return fail(SABLOCK_ERR_INVALID_ARG, "tuning.topb_slices %d: need 0 .. 64", tu.topb_slices);
-    if (tu.stats_per_key != 0 && tu.stats_per_key != 1)
-        return fail(SABLOCK_ERR_INVALID_ARG, "tuning.stats_per_key %d: need 0 or 1", tu.stats_per_key);
+    if (tu.stats_per_key < 0 || tu.stats_per_key > 2)
+        return fail(SABLOCK_ERR_INVALID_ARG, "tuning.stats_per_key %d: need 0, 1 or 2", tu.stats_per_key);
     if (tu.reserved[0] || tu.reserved[1] || tu.reserved[2])
         return fail(SABLOCK_ERR_INVALID_ARG, "tuning.reserved must be 0");
     d->tune = tu;

@@ -1537,14 +1537,18 @@ bool score_mfma_supported(const Dims &d)
 
 // pass 1 for 256 rows by the transposed-score kernel (csrc/window_attn.hip): K is read once instead of once per
 // block of 128 rows
-static bool stats_by_rows(const Dims &d) { return row_stats_supported(d) && !d.tune.stats_per_key; }
+static bool stats_by_rows(const Dims &d)
+{
+    if (!row_stats_supported(d) || d.tune.stats_per_key == 1) return false;
+    return d.tune.stats_per_key == 2 || d.G * d.W > M_ROWS;
+}
 static size_t row_stats_bytes(const Dims &d) { return align256((size_t)d.P * 2 * row_stats_chunks(d) * M_ROWS * 2 * 4); }
 
 size_t score_mfma_ws_bytes(const Dims &d)
 {
     const Plan pl = make_plan(d);
     size_t part = partial_bytes(d, pl);
-    if (row_stats_supported(d)) part = std::max(part, row_stats_bytes(d));
+    if (stats_by_rows(d)) part = std::max(part, row_stats_bytes(d));
     return part + merged_bytes(d);
 }
 
@@ -1607,7 +1611,7 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
         a.pc = nc1;
         if (nc1 >= MERGE_FROM) {
             float *merged = reinterpret_cast<float *>(static_cast<char *>(ws) + row_stats_bytes(d));
-            const int n_rows = d.P * 2 * M_ROWS;
+            const int n_rows = d.P * a.nv * M_ROWS;
             hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)((n_rows + 3) / 4)), dim3(256), 0, st, a.partial, merged,
                                nc1, M_ROWS, n_rows);
             a.merged = merged;

@@ -354,7 +354,7 @@ window_attention_kernel(WinArgs a)
         const int blk = d.W > ROWS ? qoff / ROWS : head / 4;
         const int row = d.W > ROWS ? head * ROWS + n : (head & 3) * ROWS + n;
         if (hf == 0) {
-            float *o2 = a.stats + ((((int64_t)p * 2 + blk) * a.n_chunks + chunk) * 128 + row) * 2;
+            float *o2 = a.stats + ((((int64_t)p * (NW / 4) + blk) * a.n_chunks + chunk) * 128 + row) * 2;
             o2[0] = ref2;
             o2[1] = l_tot;
         }
@@ -434,13 +434,17 @@ void wa_plan(const Dims &d, int *chunk_len, int *n_chunks, int wgs_per_cu)
 // ---- the statistics alone for 256 window-query rows per KV head, as the first pass of the scoring step
 bool row_stats_supported(const Dims &d)
 {
-    return d.dtype == SABLOCK_BF16 && d.D == 128 && (d.W == 32 || d.W == 64) && d.G * d.W > 128 && d.G * d.W <= 256;
+    return d.dtype == SABLOCK_BF16 && d.D == 128 &&
+           (((d.W == 32 || d.W == 64) && d.G * d.W > 128 && d.G * d.W <= 256) || (d.G == 4 && d.W == 32));
 }
+
+// 32 KiB rings: two 8-wavefront workgroups per CU, or four 4-wavefront ones (128 rows)
+static int row_stats_wgs_per_cu(const Dims &d) { return d.G * d.W > 128 ? 2 : 4; }
 
 int row_stats_chunks(const Dims &d)
 {
     int len, nc;
-    wa_plan(d, &len, &nc, 2);                                  // 32 KiB rings: two 8-wavefront workgroups per CU
+    wa_plan(d, &len, &nc, row_stats_wgs_per_cu(d));
     return nc;
 }
 
@@ -451,6 +455,9 @@ hipError_t launch_row_stats(const Dims &d, const void *q, const void *k, float *
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<8, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(8, false));
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(window_attention_kernel<4, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, wa_lds(4, false));
+        if (e != hipSuccess) return e;
         attr_once.done();
     }
     WinArgs a;
@@ -458,12 +465,13 @@ hipError_t launch_row_stats(const Dims &d, const void *q, const void *k, float *
     a.q = static_cast<const uint16_t *>(q);
     a.k = static_cast<const uint16_t *>(k);
     a.v = nullptr;
-    wa_plan(d, &a.chunk_len, &a.n_chunks, 2);
+    wa_plan(d, &a.chunk_len, &a.n_chunks, row_stats_wgs_per_cu(d));
     a.c1 = (float)(1.4426950408889634 / sqrt((double)d.D));
     a.out = a.lse = a.o_part = a.ml_part = nullptr;
     a.stats = stats;
-    hipLaunchKernelGGL((window_attention_kernel<8, false>), dim3((unsigned)((int64_t)d.P * a.n_chunks)), dim3(8 * 64),
-                       wa_lds(8, false), st, a);
+    const dim3 grid((unsigned)((int64_t)d.P * a.n_chunks));
+    if (d.G * d.W > 128) hipLaunchKernelGGL((window_attention_kernel<8, false>), grid, dim3(8 * 64), wa_lds(8, false), st, a);
+    else hipLaunchKernelGGL((window_attention_kernel<4, false>), grid, dim3(4 * 64), wa_lds(4, false), st, a);
     return hipGetLastError();
 }
 

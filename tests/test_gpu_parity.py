@@ -504,6 +504,13 @@ def test_mfma_score_wide_groups(oracle, torch_cuda, G, W, chunk, per_key):
     _mfma_row_shape_case(oracle, torch_cuda, G, W, 128, chunk, stats_per_key=per_key)
 
 
+@pytest.mark.parametrize("chunk", [0, 1024])
+def test_mfma_score_statistics_by_window_query(oracle, torch_cuda, chunk):
+    # G = 4, W = 32 (128 rows) with the statistics pass of the wider shapes, a lane per window query, four
+    # wavefronts of one workgroup sharing the key tiles: same scores, same decisions
+    _mfma_row_shape_case(oracle, torch_cuda, 4, 32, 128, chunk, stats_per_key=2, window_chunk=chunk)
+
+
 @pytest.mark.parametrize("seed", range(45))
 def test_mfma_score_random_sweep(oracle, torch_cuda, seed):
     # (G, W) pairs of every kind the MFMA kernels cover (256 rows, 128 rows, fewer, padded row tiles), with random

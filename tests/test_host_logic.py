@@ -79,7 +79,7 @@ def test_launch_parameters_are_validated_and_change_only_the_plan(lib):
         return s
 
     for bad in (dict(compute_units=-1), dict(score_chunk=64), dict(score_chunk=1 << 20), dict(window_chunk=8),
-                dict(topb_slices=65), dict(topb_slices=-2), dict(stats_per_key=2)):
+                dict(topb_slices=65), dict(topb_slices=-2), dict(stats_per_key=3), dict(stats_per_key=-1)):
         with pytest.raises(B.SablockError) as ei:
             B.sablock_workspace_bytes(shape(**llama, **bad), 100, 112)
         assert ei.value.status == 1, bad
