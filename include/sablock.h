@@ -134,7 +134,7 @@ SABLOCK_API sablock_status sablock_workspace_bytes(const sablock_shape *shape, i
  *   extra pass over K.
  * eps: > 0 (it keeps the logarithm of a masked or underflowed entry finite; INVALID_ARG otherwise).
  * s_out, ent_out: [P][L] float.  Arithmetic: fp32 accumulate and outputs.
- * Any shape within the limits of sablock_shape is accepted.  bf16 with head_dim 64 or 128, W in {8, 16, 32, 64} and
+ * Any shape within the limits of sablock_shape is accepted.  bf16 with head_dim 64, 96 or 128, W in {8, 16, 32, 64} and
  * any G with G * W <= 128 (e.g. G = 7 with W = 16, G = 3 with W = 32, G = 16 with W = 8), head_dim 256 with the same
  * windows and G * W <= 96 (e.g. G = 2 with W = 32), and head_dim 128 with
  * 129 .. 256 rows of a window of 32 or 64 queries (G = 5 .. 8 with W = 32, G = 3 or 4 with W = 64), runs on the

@@ -302,10 +302,11 @@ struct KeyStreamDirect {
     }
 };
 
-// the key stream of the any-row-shape kernels by k-steps per key: 8 (D = 128) staged through LDS; 4 (D = 64) and
-// 16 (D = 256, whose 512-byte rows would need a ring twice the LDS) direct
+// the key stream of the any-row-shape kernels by k-steps per key: 8 (D = 128) staged through LDS; 4 (D = 64), 6
+// (D = 96) and 16 (D = 256, whose 512-byte rows would need a ring twice the LDS) direct
 template <int KS> struct StreamFor { using type = KeyStream<4>; };
 template <> struct StreamFor<4> { using type = KeyStreamDirect<4>; };
+template <> struct StreamFor<6> { using type = KeyStreamDirect<6>; };
 template <> struct StreamFor<16> { using type = KeyStreamDirect<16>; };
 
 // A operands: the window queries of the four heads, query row `n`, k-slices (2s + hf) * 8 .. +8, into
@@ -1533,7 +1534,7 @@ void plan_partials(ScoreArgs &a, const Dims &d, const Plan &pl, void *ws)
 bool score_mfma_supported(const Dims &d)
 {
     if (d.dtype != SABLOCK_BF16) return false;
-    if (d.D == 64) return tile_shape(d);                                    // up to 128 rows, kernels for any row shape
+    if (d.D == 64 || d.D == 96) return tile_shape(d);                       // up to 128 rows, kernels for any row shape
     if (d.D == 256) return tile_shape(d) && tiles_of(d) <= 3;               // up to 96 rows: four tiles of 16 k-steps do not fit the registers
     return d.D == 128 && (tile_shape(d) || wide_shape(d));
 }
@@ -1595,6 +1596,13 @@ hipError_t launch_score_mfma(const Dims &d, const void *q, const void *k, const 
         if (d.D == 256) {
 #define X(NTV, WV) if (nt == NTV && d.W == WV) return launch_score_g<NTV, WV, false, 16>(a, grid, !row_lse, st);
             X(1, 8) X(2, 8) X(3, 8) X(1, 16) X(2, 16) X(3, 16) X(1, 32) X(2, 32) X(3, 32) X(2, 64)
+#undef X
+        }
+        if (d.D == 96) {
+#define X(NTV, WV) if (nt == NTV && d.W == WV) return launch_score_g<NTV, WV, false, 6>(a, grid, !row_lse, st);
+            SABLOCK_TILE_SHAPES(X)
+            X(4, 32)
+            SABLOCK_TILE_SHAPES_W64(X)
 #undef X
         }
         if (d.D == 64) {

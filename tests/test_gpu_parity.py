@@ -488,12 +488,12 @@ def test_mfma_score_head_dim_64(oracle, torch_cuda, G, W, chunk):
                                    (12, 8, 128), (16, 8, 128), (1, 16, 128), (6, 16, 128), (1, 64, 128), (2, 64, 128),
                                    (7, 16, 64), (5, 8, 64), (3, 16, 64), (3, 32, 64), (2, 8, 64), (2, 64, 64), (1, 64, 64),
                                    (2, 32, 256), (2, 8, 256), (1, 16, 256), (4, 16, 256), (1, 64, 256), (8, 8, 256), (3, 16, 256), (3, 32, 256),
-                                   (5, 16, 256), (11, 8, 256)])
+                                   (5, 16, 256), (11, 8, 256), (1, 32, 96), (4, 32, 96), (4, 8, 96), (7, 16, 96), (2, 64, 96), (3, 8, 96)])
 @pytest.mark.parametrize("chunk", [0, 1024])
 def test_mfma_score_any_group_size(oracle, torch_cuda, G, W, D, chunk):
     # G * W <= 128 rows with any G: the row tiles are padded to a multiple of 32 rows where 32 / W does not divide G
     # (G = 7 with W = 16: 112 rows in four tiles; G = 3 with W = 8: 24 rows in one), and the padding adds exact
-    # zeros; windows of 64 queries take two tiles per head; heads of 256 elements (16 k-steps per key, up to 96 rows)
+    # zeros; windows of 64 queries take two tiles per head; heads of 256 elements (16 k-steps per key, up to 96 rows) and of 96 (6 k-steps)
     _mfma_row_shape_case(oracle, torch_cuda, G, W, D, chunk)
 
 
@@ -546,7 +546,7 @@ def test_mfma_score_random_sweep(oracle, torch_cuda, seed):
 
 
 @pytest.mark.parametrize("G,W,D,dtype", [(4, 32, 128, "bf16"), (4, 64, 128, "bf16"), (4, 8, 128, "bf16"), (4, 32, 64, "bf16"),
-                                         (2, 32, 256, "bf16"), (7, 16, 128, "bf16"), (6, 32, 128, "bf16"), (3, 5, 40, "f32")])
+                                         (2, 32, 256, "bf16"), (4, 32, 96, "bf16"), (7, 16, 128, "bf16"), (6, 32, 128, "bf16"), (3, 5, 40, "f32")])
 def test_score_closed_form_for_zero_queries(torch_cuda, G, W, D, dtype):
     # Q = 0: every visible key gets the same probability, so window query i spreads 1 / (T + i + 1) over keys
     # 0 .. T + i; s_t and the entropy term follow in closed form (checked here without the oracle)
