@@ -297,7 +297,7 @@ topb_split_kernel(Dims d, const float *s_tilde, int budget, const uint32_t *g_hi
 template <bool PLAN>
 __global__ void __launch_bounds__(TB_THREADS)
 topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, int32_t *seg_budget,
-            int32_t *block_size, int32_t *counter, PlanArgs pa, int offs_cap, int hit_cap)
+            int32_t *block_size, int32_t *counter, PlanArgs pa, int offs_cap, int hit_cap, int hist_ways_log2)
 {
     __shared__ uint32_t hist[TB_HITS];           // pass-A histogram (4096 bins), later the list of Top-B tokens (hit_cap == TB_HITS)
     __shared__ uint32_t hist2[2048];             // histograms of the later passes
@@ -334,9 +334,26 @@ topb_kernel(Dims d, const float *s_tilde, int budget, int32_t *thr, SegView sv, 
         if (sliced) {
             for (int i = tid; i < 4096; i += TB_THREADS) hist[i] = pa.pre_hist[(int64_t)p * 4096 + i];
         } else {
-            for (int i = tid; i < 4096; i += TB_THREADS) hist[i] = 0;
-            __syncthreads();
-            scan_row(sp, T, tid, [&](int, float v) { atomicAdd(&hist[ordered_key(v) >> 20], 1u); });
+            if (hist_ways_log2 > 0) {
+                // The scores of a row crowd into a few bins, and LDS atomics of one instruction on one address run one
+                // after the other: threads are dealt out over 2 or 4 copies of the histogram (in the dynamic region,
+                // which holds nothing yet), added up afterwards.
+                uint32_t *hw = reinterpret_cast<uint32_t *>(sh_u);
+                const int sh = hist_ways_log2, way = tid & ((1 << sh) - 1);
+                for (int i = tid; i < (4096 << sh); i += TB_THREADS) hw[i] = 0;
+                __syncthreads();
+                scan_row(sp, T, tid, [&](int, float v) { atomicAdd(&hw[((ordered_key(v) >> 20) << sh) | way], 1u); });
+                __syncthreads();
+                for (int i = tid; i < 4096; i += TB_THREADS) {
+                    uint32_t c = 0;
+                    for (int w2 = 0; w2 < (1 << sh); ++w2) c += hw[(i << sh) | w2];
+                    hist[i] = c;
+                }
+            } else {
+                for (int i = tid; i < 4096; i += TB_THREADS) hist[i] = 0;
+                __syncthreads();
+                scan_row(sp, T, tid, [&](int, float v) { atomicAdd(&hist[ordered_key(v) >> 20], 1u); });
+            }
         }
         __syncthreads();
         uint32_t bin, above;
@@ -1023,13 +1040,17 @@ static int topb_offs_cap(const SegView &sv)
     return sv.max_segments + 1 <= TB_OFFS ? TB_OFFS : sv.max_segments + 1 <= 2 * TB_OFFS ? 2 * TB_OFFS : TB_OFFS_MAX;
 }
 static int topb_hit_cap(int32_t budget) { return budget <= TB_HITS ? TB_HITS : budget <= 2 * TB_HITS ? 2 * TB_HITS : TB_HITS_MAX; }
+// copies of the pass-A histogram (log2): as many as the launch's dynamic LDS holds anyway, and four (64 KiB) when
+// there is at most one workgroup per compute unit, so that the extra LDS costs no occupancy
+static int topb_hist_ways_log2(const Dims &d, size_t lds_needed) { return d.P <= d.cus || lds_needed >= 65536 ? 2 : 1; }
+static size_t topb_lds_with_hist(size_t lds_needed, int ways_log2) { return std::max(lds_needed, (size_t)16384 << ways_log2); }
 
 hipError_t launch_topb(const Dims &d, const float *s_tilde, int32_t budget, int32_t *thr, hipStream_t st)
 {
     if (d.P <= 0) return hipSuccess;
     SegView none{};
     hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), topb_lds(TB_OFFS, TB_HITS), st, d, s_tilde, budget, thr, none,
-                       (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, PlanArgs{}, TB_OFFS, TB_HITS);
+                       (int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, PlanArgs{}, TB_OFFS, TB_HITS, 1);
     return hipGetLastError();
 }
 
@@ -1064,7 +1085,7 @@ hipError_t launch_search(const Dims &d, const float *s_tilde, const SegView &sv,
     w += align256((cap > 0 ? cap : 1) * sizeof(SegRec));
     SegRec *list_long = reinterpret_cast<SegRec *>(w);
     hipLaunchKernelGGL(topb_kernel<false>, dim3(d.P), dim3(TB_THREADS), topb_lds(TB_OFFS, TB_HITS), st, d, s_tilde, budget, thr, sv,
-                       seg_budget, block_size, counters, PlanArgs{}, TB_OFFS, TB_HITS);
+                       seg_budget, block_size, counters, PlanArgs{}, TB_OFFS, TB_HITS, 1);
     if (budget > 0 && d.T > 0) {
         hipLaunchKernelGGL(heavy_list_kernel, dim3(d.P), dim3(LIST_THREADS), 0, st, d, sv, thr, seg_budget, block_size,
                            list, list_long, counters, (int)cap);
@@ -1206,7 +1227,9 @@ hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegVi
     }
     // counters and offsets of all segments of a sequence, and the Top-B tokens of a row, in LDS
     const int offs_cap = topb_offs_cap(sv), hit_cap = topb_hit_cap(budget);
-    if (topb_lds(offs_cap, hit_cap) > topb_lds(TB_OFFS, TB_HITS)) {
+    const int ways_log2 = topb_hist_ways_log2(d, topb_lds(offs_cap, hit_cap));
+    const size_t lds = topb_lds_with_hist(topb_lds(offs_cap, hit_cap), ways_log2);
+    if (lds > topb_lds(TB_OFFS, TB_HITS)) {
         static thread_local PerDeviceOnce attr_once;
         if (attr_once.needed()) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(topb_kernel<true>),
@@ -1215,8 +1238,8 @@ hipError_t launch_search_select(const Dims &d, const float *s_tilde, const SegVi
             attr_once.done();
         }
     }
-    hipLaunchKernelGGL(topb_kernel<true>, dim3(d.P), dim3(TB_THREADS), topb_lds(offs_cap, hit_cap), st, d, s_tilde, budget, thr,
-                       sv, seg_budget, block_size, counters, pa, offs_cap, hit_cap);
+    hipLaunchKernelGGL(topb_kernel<true>, dim3(d.P), dim3(TB_THREADS), lds, st, d, s_tilde, budget, thr,
+                       sv, seg_budget, block_size, counters, pa, offs_cap, hit_cap, ways_log2);
     if (cap > 0) {
         hipLaunchKernelGGL((search_kernel<CAPT, CAPB, true>), dim3((unsigned)(cap < SEARCH_WGS ? cap : SEARCH_WGS)), dim3(64),
                            0, st, d, s_tilde, sv, cand, tau, list, counters, (int)cap, block_size, budget, idx_out);
