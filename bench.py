@@ -616,7 +616,7 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_configs and args.layers == 0:
         others = [n for n in ("tiny", "llama8b_8k", "llama8b_32k_heavy", "llama8b_128k", "llama8b_4x64k",
-                              "paper_defaults_32k") if n != w.name]
+                              "paper_defaults_32k", "gqa7_32k") if n != w.name]
         result["configs"] = {n: config_entries(torch, B, synth, dev, n, max(5, args.steps // 2), args.warmup)
                              for n in others}
     if args.cpu_layers > 0:

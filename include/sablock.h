@@ -334,7 +334,7 @@ SABLOCK_API sablock_status sablock_validate_segments(const int32_t *seg_off, con
  *              and are skipped; rows from `budget` on (the window rows) always count.
  *   out        [n_seq][n_layers][n_q_heads][D] fp32, dense.  A problem without any row gives zeros.
  *   ws         at least sablock_decode_workspace_bytes(shape) bytes (partial results of the row splits).
- * Supported: G in {1,2,4,8}; head_dim * element size / 16 a power of two in [4, 64]; G * head_dim <= 1024;
+ * Supported: G <= 8; head_dim * element size / 16 a power of two in [4, 64]; G * head_dim <= 1024;
  * at least 2 rows.  Errors as for the other calls.
  */
 SABLOCK_API sablock_status sablock_decode_workspace_bytes(const sablock_shape *shape, size_t *bytes_out);

@@ -541,7 +541,7 @@ static sablock_status make_cache_dims(const sablock_shape *shape, Dims *d)
     sablock_status st = make_dims(&s, d);
     if (st != SABLOCK_OK) return st;
     if (!decode_supported(*d))
-        return fail(SABLOCK_ERR_UNSUPPORTED, "decode: need G in {1,2,4,8}, head_dim * element size / 16 a power of two in [4, 64], G * head_dim <= 1024");
+        return fail(SABLOCK_ERR_UNSUPPORTED, "decode: need G <= 8, head_dim * element size / 16 a power of two in [4, 64], G * head_dim <= 1024");
     return SABLOCK_OK;
 }
 

@@ -203,7 +203,7 @@ bool decode_supported(const Dims &d)
     const int elt = d.dtype == SABLOCK_F32 ? 4 : 2;
     const int lpr = d.D * elt / 16;
     const bool pow2 = lpr >= 4 && lpr <= 64 && (lpr & (lpr - 1)) == 0 && lpr * 16 == d.D * elt;
-    const bool g_ok = d.G == 1 || d.G == 2 || d.G == 4 || d.G == 8;
+    const bool g_ok = d.G >= 1 && d.G <= 8;
     return pow2 && g_ok && d.G * d.D <= 1024 && (size_t)(DT / (pow2 ? lpr : 4)) * d.G * (2 + d.D) * 4 <= MAX_LDS;
 }
 
@@ -241,7 +241,8 @@ hipError_t launch_decode(const Dims &d, const void *q, const void *k, const void
     SABLOCK_DECODE_L(GV, true, 4) SABLOCK_DECODE_L(GV, true, 8) SABLOCK_DECODE_L(GV, true, 16) SABLOCK_DECODE_L(GV, true, 32) \
     SABLOCK_DECODE_L(GV, false, 4) SABLOCK_DECODE_L(GV, false, 8) SABLOCK_DECODE_L(GV, false, 16)                    \
     SABLOCK_DECODE_L(GV, false, 32) SABLOCK_DECODE_L(GV, false, 64)
-    SABLOCK_DECODE_G(1) SABLOCK_DECODE_G(2) SABLOCK_DECODE_G(4) SABLOCK_DECODE_G(8)
+    SABLOCK_DECODE_G(1) SABLOCK_DECODE_G(2) SABLOCK_DECODE_G(3) SABLOCK_DECODE_G(4) SABLOCK_DECODE_G(5) SABLOCK_DECODE_G(6)
+    SABLOCK_DECODE_G(7) SABLOCK_DECODE_G(8)
 #undef SABLOCK_DECODE_G
 #undef SABLOCK_DECODE_L
     if (!fn) return hipErrorInvalidValue;

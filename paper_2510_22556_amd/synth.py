@@ -284,6 +284,10 @@ WORKLOADS: Dict[str, Workload] = {
     # length at which a block of 7 crosses a boundary about 21.65 % of the time (Sec. 2.2)
     "paper_defaults_32k": Workload("paper_defaults_32k", 6, 1, 32, 32, 8, 128, 32768, 8, "bf16",
                                    (1, 2, 3, 5, 7, 9, 11, 13), (96, 128, 1024), (28.0,), 2, 224, rope=True),
+    # a head shape whose group size is no power of two (28 query / 4 KV heads, 28 layers: seven heads per KV head,
+    # 112 window-query rows in four row tiles, the last one half padding), outside the paper's models
+    "gqa7_32k": Workload("gqa7_32k", 7, 1, 28, 28, 4, 128, 32768, 16, "bf16",
+                         (1, 2, 4, 8, 16, 32), (1024,), (32.0,), 2, 256, rope=True),
 }
 
 

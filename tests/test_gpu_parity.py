@@ -742,6 +742,24 @@ def test_paper_default_settings_full_size_both_routes(oracle, torch_cuda):
             del run
 
 
+def test_group_of_seven_heads_full_size_both_routes(oracle, torch_cuda):
+    # 28 query / 4 KV heads (G = 7), W = 16: 112 window-query rows in four row tiles with a half-padded last tile, at
+    # the size bench.py times it (28 layers x 32 768 tokens in one call), standing alone and on the row_lse route
+    # (its producer pads the fourth block of rows the same way); sampled problems end to end against the oracle
+    torch = torch_cuda
+    w = synth.WORKLOADS["gqa7_32k"]
+    q, k, v, off, ptr = _device_workload(torch, w)
+    lse = _row_lse_from_window_attention(torch, q, k, v)
+    cache = {}
+    for route in ("two_pass", "row_lse"):
+        run = H.GpuRun(q, k, v, off, ptr, w.cand, w.budget(), w.eps, w.alpha, w.eta, w.tau,
+                       row_lse=lse if route == "row_lse" else None)
+        assert np.allclose(run.s.sum(axis=1), w.window, rtol=1e-4)
+        assert (run.n_sel == w.budget()).all() and (run.b.sum(axis=1) == w.budget()).all()
+        assert _check_all(oracle, w, run, q, k, v, off, ptr, [0, 4 * 13 + 2, 4 * 27 + 3], score_cache=cache) <= 6, route
+        del run
+
+
 def test_paper_default_settings_three_budgets(oracle, torch_cuda):
     # the paper's own hyperparameters (Sec. 4.1): window of 8, candidate block sizes {1, 2, 3, 5, 7, 9, 11, 13};
     # two of the 32 layers at cache budgets 96 / 128 / 1024
@@ -924,6 +942,10 @@ def _decode_gpu(torch, q, kc, vc, n_sel=None, budget=0):
     dict(G=2, Hkv=2, D=256, R=1500, dtype="bf16", nl=1, ns=1),
     dict(G=4, Hkv=2, D=64, R=3001, dtype="f32", nl=1, ns=1),
     dict(G=2, Hkv=1, D=16, R=130, dtype="f32", nl=3, ns=1),
+    dict(G=7, Hkv=2, D=128, R=4099, dtype="bf16", nl=1, ns=1),
+    dict(G=3, Hkv=2, D=64, R=1000, dtype="bf16", nl=2, ns=1),
+    dict(G=5, Hkv=1, D=128, R=333, dtype="f32", nl=1, ns=2),
+    dict(G=6, Hkv=2, D=64, R=50, dtype="bf16", nl=1, ns=1),
 ])
 def test_decode_attention_full_cache(oracle, torch_cuda, case):
     # one decode step over an uncompressed cache given as a strided view (row stride 2 D), ragged row counts

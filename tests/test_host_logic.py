@@ -180,7 +180,8 @@ def test_decode_calls_validate_host_arguments(lib):
     assert lib.sablock_decode_attention(sp, fake, fake, fake, None, 0, fake, fake, 16, None) == 3
     assert lib.sablock_decode_attention(sp, fake, fake, fake, fake, 2000, fake, fake, n, None) == 1      # budget > rows
     assert lib.sablock_decode_attention(sp, ctypes.c_void_p(0x1008), fake, fake, None, 0, fake, fake, n, None) == 1
-    for bad, status in [(dict(n_q_heads=6), 2), (dict(head_dim=24), 2), (dict(seq_len=1), 1), (dict(n_q_heads=7), 1)]:
+    assert B.sablock_decode_workspace_bytes(cache_shape(n_q_heads=6)) > 0                                 # G = 3
+    for bad, status in [(dict(n_q_heads=18), 2), (dict(head_dim=24), 2), (dict(seq_len=1), 1), (dict(n_q_heads=7), 1)]:
         with pytest.raises(B.SablockError) as ei:
             B.sablock_decode_workspace_bytes(cache_shape(**bad))
         assert ei.value.status == status, bad
